@@ -1,0 +1,137 @@
+/*
+ * hq.h - C ABI of the Hadamard-quantised layer of HQ-DM (arxiv 2512.05746) for
+ * AMD MI355X (gfx950).
+ *
+ * The layer replaces every linear / convolution of a diffusion UNet by
+ *   1. a block-diagonal Hadamard transform over the input-channel axis
+ *      (Method, "Matrix Multiplication": H = BlockDiag(H_k, ..., H_k)),
+ *   2. symmetric low-bit quantisation (Background, "Model Quantization":
+ *      X_int = clamp(round(X / S), min, max)),
+ *   3. an integer product with int32 accumulation, and
+ *   4. dequantisation by the product of scales (Method: Y ~ S_XH S_W (...)).
+ *
+ * Conventions shared by every call
+ *   - Every pointer is a DEVICE pointer owned by the caller (the library never
+ *     allocates, frees or keeps one), 16-byte aligned unless stated otherwise.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work on it; they never synchronise.
+ *   - All arguments are validated on the host before anything is launched; a
+ *     bad argument returns the matching HQ_ERR_* and launches nothing.
+ *   - Tensors are row-major and dense (no strides).
+ *   - Packed codes: two 4-bit two's-complement codes per byte; element 2j of a
+ *     row sits in bits 0..3 of byte j and element 2j+1 in bits 4..7.  3-bit
+ *     codes are stored sign-extended in the same 4-bit container.
+ *   - Scales use the orthonormal convention H_k = 2^{-k/2} H_k^raw, so that
+ *     acc * x_scale * w_scale needs no further factor (the paper absorbs
+ *     2^{-k/2} into the scales in the same way).
+ *   - Rounding is round-half-to-even.  Non-finite inputs are undefined.
+ *   - The library is stateless and may be called from several host threads.
+ */
+#ifndef HQ_H
+#define HQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HQ_OK = 0,
+    HQ_ERR_NULL = 1,        /* a required pointer is NULL */
+    HQ_ERR_SHAPE = 2,       /* a size is non-positive, odd where even is needed, or k % had_block != 0 */
+    HQ_ERR_DTYPE = 3,       /* dtype enum not valid for this argument */
+    HQ_ERR_BITS = 4,        /* unsupported bit width */
+    HQ_ERR_ALIGN = 5,       /* pointer not 16-byte aligned */
+    HQ_ERR_UNSUPPORTED = 6, /* valid in principle, not built (e.g. stride != 1) */
+    HQ_ERR_LAUNCH = 7       /* the HIP runtime refused the launch */
+} hq_status;
+
+typedef enum {
+    HQ_F16 = 0, /* IEEE half */
+    HQ_F32 = 1, /* IEEE single */
+    HQ_I32 = 2  /* raw int32 accumulators: outputs of the integer stage only */
+} hq_dtype;
+
+/* Static, NUL-terminated description of a status code. */
+const char *hq_status_string(hq_status s);
+
+/*
+ * Offline weight preparation.  (Method, "Matrix Multiplication" for the
+ * block-diagonal H; "Single Hadamard Transformation" for the offline
+ * quantisation of the transformed weights.)
+ *
+ *   w        [n_out, taps, k_in] of w_dtype (HQ_F16 | HQ_F32); taps = 1 for a
+ *            linear layer y = x W^T with W [n_out, k_in], taps = R*S for a
+ *            convolution stored [Cout, R, S, Cin].
+ *   had_block power of two in 1..128 dividing k_in; the transform runs along
+ *            k_in inside every (n_out, tap) row; 1 means H = I.
+ *   w_bits   4 (codes in [-8, 7]) or 3.
+ *   wq       out, [n_out, taps, k_in / 2] packed codes.
+ *   w_scale  out, [n_out] fp32: max |transformed row over all taps| / (2^(w_bits-1) - 1),
+ *            1.0 for an all-zero channel.
+ */
+hq_status hq_quantize_weights(const void *w, hq_dtype w_dtype, int n_out, int taps, int k_in,
+                              int had_block, int w_bits, uint8_t *wq, float *w_scale,
+                              void *stream);
+
+/*
+ * Online activation path: block Hadamard over the channel axis fused with
+ * per-token symmetric quantisation.  (Method, "Matrix Multiplication";
+ * Background, "Model Quantization".)
+ *
+ *   x        [m, k] of x_dtype (HQ_F16 | HQ_F32).  NHWC activations are passed
+ *            with m = N*H*W and k = C.
+ *   had_block power of two in 1..128 dividing k; k must be a multiple of 8.
+ *   a_bits   4 (codes in [-8, 7]) or 3 (codes in [-4, 3]).
+ *   xq       out, [m, k / 2] packed codes.
+ *   x_scale  out, [m] fp32: max |transformed token| / (2^(a_bits-1) - 1), 1.0 for an
+ *            all-zero token.
+ */
+hq_status hq_act_hadamard_quant(const void *x, hq_dtype x_dtype, int64_t m, int k,
+                                int had_block, int a_bits, uint8_t *xq, float *x_scale,
+                                void *stream);
+
+/*
+ * Integer linear layer with dequantising epilogue.  (Method, linear-layer
+ * equation: only an integer matrix product between the quantised operands,
+ * then the product of scales.)
+ *
+ *   acc[i, j] = sum_c xq[i, c] * wq[j, c]                       (int32)
+ *   y[i, j]   = acc[i, j] * x_scale[i] * w_scale[j] + bias[j]   (fp32, cast to y_dtype)
+ *
+ *   xq [m, k/2], x_scale [m], wq [n, k/2], w_scale [n]; bias [n] of y_dtype or
+ *   NULL; k a multiple of 64, k < 131072; y [m, n].
+ *   y_dtype == HQ_I32 writes acc itself (bias and scales ignored; they may be NULL).
+ */
+hq_status hq_int_linear(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
+                        const float *w_scale, const void *bias, int64_t m, int n, int k,
+                        void *y, hq_dtype y_dtype, void *stream);
+
+/*
+ * Integer NHWC convolution (implicit GEMM) with dequantising epilogue.
+ * (Method, "Convolution": integer convolution of the quantised operands, then
+ * the product of scales.)  Every input pixel carries its own scale, so the
+ * integer sum is kept per kernel tap t = (r, s) and the taps are combined in
+ * fp32, in the order t = 0 .. R*S-1:
+ *
+ *   acc_t[b, p, q, co] = sum_ci xq[b, p + r - pad, q + s - pad, ci] * wq[co, r, s, ci]
+ *   y[b, p, q, co]     = w_scale[co] * sum_t x_scale[b, p + r - pad, q + s - pad] * acc_t
+ *                        + bias[co]
+ *
+ *   A tap outside the image contributes 0.
+ *   xq [nb, h, w, c_in/2], x_scale [nb, h, w], wq [c_out, R, S, c_in/2],
+ *   w_scale [c_out], bias [c_out] of y_dtype or NULL, y [nb, h, w, c_out].
+ *   Built: R = S in {1, 3}, stride 1, pad (R-1)/2 (same-size output); anything
+ *   else returns HQ_ERR_UNSUPPORTED.  c_in a multiple of 64.
+ *   y_dtype == HQ_I32 writes the per-tap accumulators [nb, h, w, R*S, c_out].
+ */
+hq_status hq_int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
+                        const float *w_scale, const void *bias, int nb, int h, int w,
+                        int c_in, int c_out, int r, int s, int stride, int pad,
+                        void *y, hq_dtype y_dtype, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HQ_H */

@@ -1,0 +1,10 @@
+"""MI355X-native Hadamard-quantised layer of HQ-DM: thin Python face of libhq.so."""
+from .binding import (  # noqa: F401
+    HqError,
+    hq_act_hadamard_quant,
+    hq_int_conv2d,
+    hq_int_linear,
+    hq_quantize_weights,
+    load_library,
+    status_string,
+)

@@ -1,0 +1,151 @@
+"""ctypes binding of libhq.so: argument marshalling only.
+
+Every function here has the name and meaning of the C entry point declared in
+``include/hq.h``; tensors are PyTorch tensors used purely as device buffers, and
+the work is enqueued on PyTorch's current HIP stream.  There is no fallback: if
+the library cannot be loaded or a call is refused, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+from . import build as _build
+
+HQ_F16, HQ_F32, HQ_I32 = 0, 1, 2
+_DTYPES = {torch.float16: HQ_F16, torch.float32: HQ_F32, torch.int32: HQ_I32}
+
+SYMBOLS = ("hq_status_string", "hq_quantize_weights", "hq_act_hadamard_quant",
+           "hq_int_linear", "hq_int_conv2d")
+
+
+class HqError(RuntimeError):
+    def __init__(self, fn: str, code: int, text: str):
+        super().__init__("%s failed: %s (status %d)" % (fn, text, code))
+        self.code = code
+
+
+_lib = None
+
+
+def load_library(path: Optional[str] = None) -> ctypes.CDLL:
+    """Loads libhq.so, building it first only if no built library exists."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or _build.LIB
+    if not os.path.exists(path):
+        _build.build_lib()
+    lib = ctypes.CDLL(path)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+    lib.hq_status_string.argtypes = [i32]
+    lib.hq_status_string.restype = ctypes.c_char_p
+    lib.hq_quantize_weights.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, vp]
+    lib.hq_act_hadamard_quant.argtypes = [vp, i32, i64, i32, i32, i32, vp, vp, vp]
+    lib.hq_int_linear.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, vp, i32, vp]
+    lib.hq_int_conv2d.argtypes = [vp] * 5 + [i32] * 9 + [vp, i32, vp]
+    for name in SYMBOLS[1:]:
+        getattr(lib, name).restype = i32
+    _lib = lib
+    return lib
+
+
+def status_string(code: int) -> str:
+    return load_library().hq_status_string(code).decode()
+
+
+def _check(fn: str, code: int) -> None:
+    if code != 0:
+        raise HqError(fn, code, status_string(code))
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _dev(t: torch.Tensor, name: str) -> torch.Tensor:
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("%s must be a contiguous device tensor" % name)
+    return t
+
+
+def hq_quantize_weights(w: torch.Tensor, had_block: int = 64, w_bits: int = 4
+                        ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """w [n_out, taps, k_in] fp16/fp32 -> (wq uint8 [n_out, taps, k_in/2], w_scale fp32 [n_out])."""
+    _dev(w, "w")
+    n_out, taps, k_in = w.shape
+    wq = torch.empty((n_out, taps, k_in // 2), dtype=torch.uint8, device=w.device)
+    ws = torch.empty((n_out,), dtype=torch.float32, device=w.device)
+    _check("hq_quantize_weights", load_library().hq_quantize_weights(
+        _ptr(w), _DTYPES[w.dtype], n_out, taps, k_in, had_block, w_bits, _ptr(wq), _ptr(ws), _stream()))
+    return wq, ws
+
+
+def hq_act_hadamard_quant(x: torch.Tensor, had_block: int = 64, a_bits: int = 4,
+                          out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None
+                          ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """x [..., k] fp16/fp32 -> (xq uint8 [..., k/2], x_scale fp32 [...])."""
+    _dev(x, "x")
+    k = x.shape[-1]
+    m = x.numel() // k
+    if out is None:
+        xq = torch.empty(x.shape[:-1] + (k // 2,), dtype=torch.uint8, device=x.device)
+        xs = torch.empty(x.shape[:-1], dtype=torch.float32, device=x.device)
+    else:
+        xq, xs = out
+    _check("hq_act_hadamard_quant", load_library().hq_act_hadamard_quant(
+        _ptr(x), _DTYPES[x.dtype], m, k, had_block, a_bits, _ptr(xq), _ptr(xs), _stream()))
+    return xq, xs
+
+
+def hq_int_linear(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torch.Tensor,
+                  w_scale: Optional[torch.Tensor], bias: Optional[torch.Tensor] = None,
+                  y_dtype: torch.dtype = torch.float16, out: Optional[torch.Tensor] = None
+                  ) -> torch.Tensor:
+    """xq [m, k/2], wq [n, k/2] (or [n, 1, k/2]) -> y [m, n]; y_dtype int32 returns the raw sums."""
+    _dev(xq, "xq"), _dev(wq, "wq")
+    m, kb = xq.shape
+    n = wq.shape[0]
+    if wq.numel() != n * kb:
+        raise ValueError("wq does not match xq in k")
+    if bias is not None and bias.dtype != y_dtype:
+        raise ValueError("bias must have the output dtype")
+    y = out if out is not None else torch.empty((m, n), dtype=y_dtype, device=xq.device)
+    _check("hq_int_linear", load_library().hq_int_linear(
+        _ptr(xq), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), m, n, kb * 2,
+        _ptr(y), _DTYPES[y_dtype], _stream()))
+    return y
+
+
+def hq_int_conv2d(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torch.Tensor,
+                  w_scale: Optional[torch.Tensor], bias: Optional[torch.Tensor] = None,
+                  ksize: int = 3, stride: int = 1, pad: Optional[int] = None,
+                  y_dtype: torch.dtype = torch.float16, out: Optional[torch.Tensor] = None
+                  ) -> torch.Tensor:
+    """xq [nb, h, w, cin/2], wq [cout, ksize*ksize, cin/2] -> y [nb, h, w, cout];
+    y_dtype int32 returns the per-tap sums [nb, h, w, ksize*ksize, cout]."""
+    _dev(xq, "xq"), _dev(wq, "wq")
+    nb, h, w, cb = xq.shape
+    cout = wq.shape[0]
+    if wq.numel() != cout * ksize * ksize * cb:
+        raise ValueError("wq does not match xq / ksize")
+    if bias is not None and bias.dtype != y_dtype:
+        raise ValueError("bias must have the output dtype")
+    pad = (ksize - 1) // 2 if pad is None else pad
+    if out is not None:
+        y = out
+    elif y_dtype == torch.int32:
+        y = torch.empty((nb, h, w, ksize * ksize, cout), dtype=y_dtype, device=xq.device)
+    else:
+        y = torch.empty((nb, h, w, cout), dtype=y_dtype, device=xq.device)
+    _check("hq_int_conv2d", load_library().hq_int_conv2d(
+        _ptr(xq), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), nb, h, w, cb * 2, cout,
+        ksize, ksize, stride, pad, _ptr(y), _DTYPES[y_dtype], _stream()))
+    return y

@@ -1,0 +1,330 @@
+// Block Hadamard transform fused with per-row symmetric quantisation (gfx950).
+//
+// One kernel family serves both the online activation path (one row per token,
+// Method "Matrix Multiplication" + Background "Model Quantization") and the
+// offline weight path (one row per output channel, all taps of it).
+//
+// Work decomposition: a lane owns a "chunk" of 8 consecutive elements (one
+// 16-byte load of fp16).  The Sylvester transform of order 2^LOGB is a
+// butterfly over the LOGB index bits: bits 0..2 live inside the lane's
+// registers, bits 3.. live across 2^(LOGB-3) neighbouring lanes and are done
+// with DPP lane permutes.  The normalisation 2^{-LOGB/2} is never applied to
+// the data: it only enters the reported scale (the paper absorbs it into the
+// scales as well).
+#include <hip/hip_fp16.h>
+
+#include "hq_common.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxRowsPerWg = 1024;
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+// Value held by lane (lane ^ (1 << J)), J = 0..3; partners stay inside a row of 16 lanes.
+template <int J>
+__device__ __forceinline__ float lane_xor(float v) {
+    static_assert(J >= 0 && J <= 3, "partner must be inside a DPP row");
+    if constexpr (J == 0) return dpp_mov<0xB1>(v);                       // quad_perm [1,0,3,2]
+    else if constexpr (J == 1) return dpp_mov<0x4E>(v);                  // quad_perm [2,3,0,1]
+    else if constexpr (J == 2) return dpp_mov<0x1B>(dpp_mov<0x141>(v));  // half-row mirror, then quad reverse
+    else return dpp_mov<0x128>(v);                                       // row rotate by 8
+}
+
+__device__ __forceinline__ void load8(const __half *p, float (&v)[8]) {
+    uint4 raw = *reinterpret_cast<const uint4 *>(p);
+    const __half2 *h = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float2 f = __half22float2(h[i]);
+        v[2 * i] = f.x;
+        v[2 * i + 1] = f.y;
+    }
+}
+
+__device__ __forceinline__ void load8(const float *p, float (&v)[8]) {
+    float4 a = reinterpret_cast<const float4 *>(p)[0];
+    float4 b = reinterpret_cast<const float4 *>(p)[1];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+
+template <int S>
+__device__ __forceinline__ void stage_in_lane(float (&v)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        if ((i & S) == 0) {
+            float a = v[i], b = v[i + S];
+            v[i] = a + b;
+            v[i + S] = a - b;
+        }
+}
+
+template <int J>
+__device__ __forceinline__ void stage_cross_lane(float (&v)[8], int lane) {
+    const bool upper = (lane >> J) & 1;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float p = lane_xor<J>(v[i]);
+        v[i] = upper ? (p - v[i]) : (v[i] + p);
+    }
+}
+
+// Unnormalised Sylvester transform of order 2^LOGB over element index bits 0..LOGB-1.
+template <int LOGB>
+__device__ __forceinline__ void hadamard_raw(float (&v)[8], int lane) {
+    if constexpr (LOGB >= 1) stage_in_lane<1>(v);
+    if constexpr (LOGB >= 2) stage_in_lane<2>(v);
+    if constexpr (LOGB >= 3) stage_in_lane<4>(v);
+    if constexpr (LOGB >= 4) stage_cross_lane<0>(v, lane);
+    if constexpr (LOGB >= 5) stage_cross_lane<1>(v, lane);
+    if constexpr (LOGB >= 6) stage_cross_lane<2>(v, lane);
+    if constexpr (LOGB >= 7) stage_cross_lane<3>(v, lane);
+}
+
+__device__ __forceinline__ float absmax8(const float (&v)[8]) {
+    float a = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a = fmaxf(a, fabsf(v[i]));
+    return a;
+}
+
+// max over an aligned group of `group` lanes (group = 1, 2, 4, 8 or 16; wave-uniform)
+__device__ __forceinline__ float group_max(float a, int group) {
+    if (group > 1) a = fmaxf(a, lane_xor<0>(a));
+    if (group > 2) a = fmaxf(a, lane_xor<1>(a));
+    if (group > 4) a = fmaxf(a, lane_xor<2>(a));
+    if (group > 8) a = fmaxf(a, lane_xor<3>(a));
+    return a;
+}
+
+// codes = clamp(rne(v * inv), qmin, qmax), eight of them packed into one dword,
+// element i in bits 4i..4i+3 (two's complement).
+__device__ __forceinline__ uint32_t quant_pack8(const float (&v)[8], float inv, float qmin, float qmax) {
+    uint32_t w = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float r = fminf(fmaxf(rintf(v[i] * inv), qmin), qmax);
+        w |= (static_cast<uint32_t>(static_cast<int>(r)) & 0xFu) << (4 * i);
+    }
+    return w;
+}
+
+struct RowQuantArgs {
+    int64_t m;          // rows
+    int chunks;         // 8-element chunks per row
+    uint32_t inv_chunks;  // ceil(2^32 / chunks) for chunks >= 2 (exact quotient for slot < 65536)
+    int rows_per_wg;
+    int max_group;      // power of two <= 16 dividing `chunks`
+    float qmin, qmax;
+    float norm;         // 2^{-LOGB/2}
+};
+
+// Rows short enough that a workgroup keeps several whole rows in registers.
+template <typename T, int LOGB, int U>
+__global__ __launch_bounds__(kThreads) void rowquant_small(const T *__restrict__ x, RowQuantArgs a,
+                                                           uint32_t *__restrict__ xq,
+                                                           float *__restrict__ scale) {
+    __shared__ unsigned s_max[kMaxRowsPerWg];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int64_t row0 = static_cast<int64_t>(blockIdx.x) * a.rows_per_wg;
+    const int64_t left = a.m - row0;
+    const int nrows = left < a.rows_per_wg ? static_cast<int>(left) : a.rows_per_wg;
+    const int nslots = nrows * a.chunks;
+    const int64_t chunk0 = row0 * a.chunks;
+
+    for (int i = tid; i < a.rows_per_wg; i += kThreads) s_max[i] = 0u;
+
+    float v[U][8];
+    int rl[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int slot = tid + kThreads * u;
+        if (slot < nslots) {
+            load8(x + (chunk0 + slot) * 8, v[u]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[u][i] = 0.f;
+        }
+        rl[u] = a.chunks == 1 ? slot : static_cast<int>(__umulhi(static_cast<uint32_t>(slot), a.inv_chunks));
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        hadamard_raw<LOGB>(v[u], lane);
+        const float amax = group_max(absmax8(v[u]), a.max_group);
+        const int slot = tid + kThreads * u;
+        if (slot < nslots && (lane & (a.max_group - 1)) == 0)
+            atomicMax(&s_max[rl[u]], __float_as_uint(amax));  // non-negative floats order like uints
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int slot = tid + kThreads * u;
+        if (slot < nslots) {
+            const float amax = __uint_as_float(s_max[rl[u]]);
+            const float inv = amax > 0.f ? a.qmax / amax : 0.f;
+            xq[chunk0 + slot] = quant_pack8(v[u], inv, a.qmin, a.qmax);
+            if (slot == rl[u] * a.chunks)
+                scale[row0 + rl[u]] = amax > 0.f ? (amax * a.norm) / a.qmax : 1.0f;
+        }
+    }
+}
+
+// Arbitrarily long rows: one workgroup per row, the row is read twice.
+template <typename T, int LOGB>
+__global__ __launch_bounds__(kThreads) void rowquant_large(const T *__restrict__ x, RowQuantArgs a,
+                                                           uint32_t *__restrict__ xq,
+                                                           float *__restrict__ scale) {
+    __shared__ unsigned s_max;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int64_t chunk0 = static_cast<int64_t>(blockIdx.x) * a.chunks;
+    const int rounded = (a.chunks + kThreads - 1) / kThreads * kThreads;
+    if (tid == 0) s_max = 0u;
+    __syncthreads();
+
+    float amax = 0.f;
+    for (int c = tid; c < rounded; c += kThreads) {
+        float v[8];
+        if (c < a.chunks) {
+            load8(x + (chunk0 + c) * 8, v);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = 0.f;
+        }
+        hadamard_raw<LOGB>(v, lane);
+        amax = fmaxf(amax, absmax8(v));
+    }
+    atomicMax(&s_max, __float_as_uint(amax));
+    __syncthreads();
+    amax = __uint_as_float(s_max);
+    const float inv = amax > 0.f ? a.qmax / amax : 0.f;
+
+    for (int c = tid; c < rounded; c += kThreads) {
+        float v[8];
+        if (c < a.chunks) {
+            load8(x + (chunk0 + c) * 8, v);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = 0.f;
+        }
+        hadamard_raw<LOGB>(v, lane);
+        if (c < a.chunks) xq[chunk0 + c] = quant_pack8(v, inv, a.qmin, a.qmax);
+    }
+    if (tid == 0) scale[blockIdx.x] = amax > 0.f ? (amax * a.norm) / a.qmax : 1.0f;
+}
+
+template <typename T, int LOGB>
+hq_status launch_rowquant(const T *x, int64_t m, int row_len, int bits, uint32_t *xq, float *scale,
+                          hipStream_t stream) {
+    RowQuantArgs a;
+    a.m = m;
+    a.chunks = row_len / 8;
+    a.inv_chunks = a.chunks >= 2 ? static_cast<uint32_t>(((1ull << 32) + a.chunks - 1) / a.chunks) : 0u;
+    a.max_group = 1;
+    while (a.max_group < 16 && a.chunks % (a.max_group * 2) == 0) a.max_group *= 2;
+    a.qmax = static_cast<float>((1 << (bits - 1)) - 1);
+    a.qmin = -static_cast<float>(1 << (bits - 1));
+    a.norm = static_cast<float>(1.0 / sqrt(static_cast<double>(1 << LOGB)));
+
+    if (a.chunks <= kThreads * 4) {
+        // several loads in flight per lane once the tensor is big enough to fill the chip anyway
+        const bool deep = a.chunks > kThreads || m * static_cast<int64_t>(a.chunks) >= (1 << 21);
+        const int cap = kThreads * (deep ? 4 : 1);
+        a.rows_per_wg = cap / a.chunks;
+        const int64_t grid = (m + a.rows_per_wg - 1) / a.rows_per_wg;
+        if (grid > 0x7fffffffLL) return HQ_ERR_SHAPE;
+        if (deep)
+            hipLaunchKernelGGL((rowquant_small<T, LOGB, 4>), dim3(static_cast<unsigned>(grid)),
+                               dim3(kThreads), 0, stream, x, a, xq, scale);
+        else
+            hipLaunchKernelGGL((rowquant_small<T, LOGB, 1>), dim3(static_cast<unsigned>(grid)),
+                               dim3(kThreads), 0, stream, x, a, xq, scale);
+    } else {
+        if (m > 0x7fffffffLL) return HQ_ERR_SHAPE;
+        a.rows_per_wg = 1;
+        hipLaunchKernelGGL((rowquant_large<T, LOGB>), dim3(static_cast<unsigned>(m)), dim3(kThreads), 0,
+                           stream, x, a, xq, scale);
+    }
+    return hq::launch_status();
+}
+
+template <typename T>
+hq_status dispatch_block(const T *x, int64_t m, int row_len, int had_block, int bits, uint32_t *xq,
+                         float *scale, hipStream_t stream) {
+    switch (hq::ilog2(had_block)) {
+        case 0: return launch_rowquant<T, 0>(x, m, row_len, bits, xq, scale, stream);
+        case 1: return launch_rowquant<T, 1>(x, m, row_len, bits, xq, scale, stream);
+        case 2: return launch_rowquant<T, 2>(x, m, row_len, bits, xq, scale, stream);
+        case 3: return launch_rowquant<T, 3>(x, m, row_len, bits, xq, scale, stream);
+        case 4: return launch_rowquant<T, 4>(x, m, row_len, bits, xq, scale, stream);
+        case 5: return launch_rowquant<T, 5>(x, m, row_len, bits, xq, scale, stream);
+        case 6: return launch_rowquant<T, 6>(x, m, row_len, bits, xq, scale, stream);
+        case 7: return launch_rowquant<T, 7>(x, m, row_len, bits, xq, scale, stream);
+        default: return HQ_ERR_SHAPE;
+    }
+}
+
+// Shared argument checks.  `k` is the length the transform blocks must divide,
+// `row_len` the length one scale covers.
+hq_status check_rowquant(const void *x, hq_dtype dt, int64_t m, int k, int64_t row_len, int had_block,
+                         int bits, const void *xq, const void *scale) {
+    if (!x || !xq || !scale) return HQ_ERR_NULL;
+    if (dt != HQ_F16 && dt != HQ_F32) return HQ_ERR_DTYPE;
+    if (bits != 3 && bits != 4) return HQ_ERR_BITS;
+    if (m <= 0 || k <= 0 || row_len <= 0 || row_len > 0x7fffffffLL) return HQ_ERR_SHAPE;
+    if (!hq::pow2_upto_128(had_block) || k % had_block != 0 || k % 8 != 0) return HQ_ERR_SHAPE;
+    if (!hq::aligned16(x) || !hq::aligned16(xq) || (reinterpret_cast<uintptr_t>(scale) & 3u))
+        return HQ_ERR_ALIGN;
+    return HQ_OK;
+}
+
+}  // namespace
+
+extern "C" hq_status hq_act_hadamard_quant(const void *x, hq_dtype x_dtype, int64_t m, int k,
+                                           int had_block, int a_bits, uint8_t *xq, float *x_scale,
+                                           void *stream) {
+    hq_status st = check_rowquant(x, x_dtype, m, k, k, had_block, a_bits, xq, x_scale);
+    if (st != HQ_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint32_t *out = reinterpret_cast<uint32_t *>(xq);
+    if (x_dtype == HQ_F16)
+        return dispatch_block(static_cast<const __half *>(x), m, k, had_block, a_bits, out, x_scale, s);
+    return dispatch_block(static_cast<const float *>(x), m, k, had_block, a_bits, out, x_scale, s);
+}
+
+extern "C" hq_status hq_quantize_weights(const void *w, hq_dtype w_dtype, int n_out, int taps, int k_in,
+                                         int had_block, int w_bits, uint8_t *wq, float *w_scale,
+                                         void *stream) {
+    if (taps <= 0) return (!w || !wq || !w_scale) ? HQ_ERR_NULL : HQ_ERR_SHAPE;
+    const int64_t row_len = static_cast<int64_t>(taps) * k_in;
+    hq_status st = check_rowquant(w, w_dtype, n_out, k_in, row_len, had_block, w_bits, wq, w_scale);
+    if (st != HQ_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint32_t *out = reinterpret_cast<uint32_t *>(wq);
+    const int len = static_cast<int>(row_len);
+    if (w_dtype == HQ_F16)
+        return dispatch_block(static_cast<const __half *>(w), n_out, len, had_block, w_bits, out, w_scale, s);
+    return dispatch_block(static_cast<const float *>(w), n_out, len, had_block, w_bits, out, w_scale, s);
+}
+
+extern "C" const char *hq_status_string(hq_status s) {
+    switch (s) {
+        case HQ_OK: return "ok";
+        case HQ_ERR_NULL: return "a required pointer is NULL";
+        case HQ_ERR_SHAPE: return "bad shape";
+        case HQ_ERR_DTYPE: return "bad dtype";
+        case HQ_ERR_BITS: return "unsupported bit width";
+        case HQ_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case HQ_ERR_UNSUPPORTED: return "configuration not supported";
+        case HQ_ERR_LAUNCH: return "kernel launch failed";
+    }
+    return "unknown status";
+}

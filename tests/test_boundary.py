@@ -1,0 +1,105 @@
+"""The C-ABI library: it loads, exports what include/hq.h declares, and rejects
+bad arguments on the host before anything is launched.  No GPU needed."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2512_05746_amd as hq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, NULL, SHAPE, DTYPE, BITS, ALIGN, UNSUPPORTED = range(7)
+P = 4096  # any non-null, 16-byte-aligned fake device address: validation never dereferences it
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return hq.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "hq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(hq.binding.SYMBOLS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings(lib):
+    texts = [hq.status_string(i) for i in range(8)]
+    assert texts[0] == "ok" and len(set(texts)) == 8
+    assert hq.status_string(99) == "unknown status"
+
+
+def test_act_quant_argument_errors(lib):
+    f = lib.hq_act_hadamard_quant
+    assert f(None, 0, 8, 64, 64, 4, P, P, None) == NULL
+    assert f(P, 0, 8, 64, 64, 4, None, P, None) == NULL
+    assert f(P, 0, 8, 64, 64, 4, P, None, None) == NULL
+    assert f(P, 2, 8, 64, 64, 4, P, P, None) == DTYPE      # int32 is not an input dtype
+    assert f(P, 0, 8, 64, 64, 8, P, P, None) == BITS
+    assert f(P, 0, 8, 64, 64, 2, P, P, None) == BITS
+    assert f(P, 0, 0, 64, 64, 4, P, P, None) == SHAPE      # no rows
+    assert f(P, 0, 8, 96, 64, 4, P, P, None) == SHAPE      # k not a multiple of the block
+    assert f(P, 0, 8, 64, 48, 4, P, P, None) == SHAPE      # block not a power of two
+    assert f(P, 0, 8, 256, 256, 4, P, P, None) == SHAPE    # block above 128
+    assert f(P, 0, 8, 4, 4, 4, P, P, None) == SHAPE        # k not a multiple of 8
+    assert f(P + 8, 0, 8, 64, 64, 4, P, P, None) == ALIGN
+    assert f(P, 0, 8, 64, 64, 4, P + 4, P, None) == ALIGN
+    assert f(P, 0, 8, 64, 64, 4, P, P + 2, None) == ALIGN
+
+
+def test_weight_quant_argument_errors(lib):
+    f = lib.hq_quantize_weights
+    assert f(None, 0, 8, 1, 64, 64, 4, P, P, None) == NULL
+    assert f(P, 0, 8, 0, 64, 64, 4, P, P, None) == SHAPE
+    assert f(P, 0, 0, 1, 64, 64, 4, P, P, None) == SHAPE
+    assert f(P, 0, 8, 9, 96, 64, 4, P, P, None) == SHAPE
+    assert f(P, 7, 8, 9, 64, 64, 4, P, P, None) == DTYPE
+    assert f(P, 0, 8, 9, 64, 64, 5, P, P, None) == BITS
+
+
+def test_linear_argument_errors(lib):
+    f = lib.hq_int_linear
+    assert f(None, P, P, P, None, 8, 8, 64, P, 0, None) == NULL
+    assert f(P, None, P, P, None, 8, 8, 64, P, 0, None) == NULL    # scales needed for fp output
+    assert f(P, P, P, P, None, 8, 8, 64, None, 0, None) == NULL
+    assert f(P, P, P, P, None, 8, 8, 64, P, 5, None) == DTYPE
+    assert f(P, P, P, P, None, 8, 8, 32, P, 0, None) == SHAPE       # k not a multiple of 64
+    assert f(P, P, P, P, None, 8, 0, 64, P, 0, None) == SHAPE
+    assert f(P, P, P, P, None, 0, 8, 64, P, 0, None) == SHAPE
+    assert f(P, P, P, P, None, 8, 8, 131072, P, 0, None) == SHAPE   # 256 * acc would overflow
+    assert f(P + 4, P, P, P, None, 8, 8, 64, P, 0, None) == ALIGN
+    assert f(P, P, P, P, P + 1, 8, 8, 64, P, 0, None) == ALIGN
+
+
+def test_conv_argument_errors(lib):
+    f = lib.hq_int_conv2d
+    args = lambda **kw: [kw.get(k, d) for k, d in [
+        ("xq", P), ("sx", P), ("wq", P), ("sw", P), ("bias", None), ("nb", 1), ("h", 4), ("w", 4),
+        ("cin", 64), ("cout", 8), ("r", 3), ("s", 3), ("stride", 1), ("pad", 1), ("y", P),
+        ("dt", 0), ("stream", None)]]
+    assert f(*args(xq=None)) == NULL
+    assert f(*args(h=0)) == SHAPE
+    assert f(*args(cin=96)) == SHAPE
+    assert f(*args(stride=2)) == UNSUPPORTED
+    assert f(*args(pad=0)) == UNSUPPORTED
+    assert f(*args(r=5, s=5, pad=2)) == UNSUPPORTED
+    assert f(*args(r=3, s=1)) == UNSUPPORTED
+    assert f(*args(dt=9)) == DTYPE
+    assert f(*args(y=P + 2)) == ALIGN
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2512_05746_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert "oracle" not in text, os.path.join(dirpath, fn)

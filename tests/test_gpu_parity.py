@@ -1,0 +1,212 @@
+"""Parity of the HIP library against the CPU oracle, element by element, on the
+same seeded stored tensors.  Every call goes through the C ABI (via the ctypes
+binding).  Three layers of checks per layer of a workload:
+
+  (i)   codes and scales of both quantisers against the oracle's: scales to
+        1e-6 relative, codes identical except where the oracle's pre-rounding
+        value is within 1e-5 of a tie (then off by at most one);
+  (ii)  the integer stage fed the ORACLE's codes: int32 sums bit-equal to the
+        oracle's int64 sums (per tap for a convolution);
+  (iii) the whole chain on the GPU against the oracle's fp64 result within
+        max|y - ref| / max|ref| <= 2e-3.  If (i) found codes that legitimately
+        differ at a tie, the oracle's integer + dequantisation stages are re-run
+        on the validated GPU codes (with the oracle's own fp64 scales), since a
+        single flipped code moves a whole output row by more than the tolerance.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from parity_util import (check_codes, check_scales, check_y, pack_codes, unpack_codes)
+
+pytestmark = pytest.mark.gpu
+
+TORCH_DT = {"f16": torch.float16, "f32": torch.float32}
+
+
+@pytest.fixture(scope="module")
+def hq():
+    import paper_2512_05746_amd as lib
+    lib.load_library()
+    return lib
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def run_layer(hq, layer, block=workloads.HAD_BLOCK):
+    print("layer", layer.name, layer.kind, layer.x_shape, "->", layer.n_out, flush=True)
+    x, w, bias = workloads.make_x(layer), workloads.make_w(layer), workloads.make_bias(layer)
+    ydt = TORCH_DT[layer.dtype]
+
+    # oracle, stages S0..S3
+    xq_o, sx_o, tx = oracle.act_hadamard_quant(x, block, layer.a_bits)
+    wq_o, sw_o, tw = oracle.quantize_weights(w, block, layer.w_bits)
+
+    # (i) quantisers
+    xq_g, sx_g = hq.hq_act_hadamard_quant(dev(x), block, layer.a_bits)
+    wq_g, sw_g = hq.hq_quantize_weights(dev(w), block, layer.w_bits)
+    xq_gc, wq_gc = unpack_codes(host(xq_g)), unpack_codes(host(wq_g))
+    check_scales(layer.name + " x_scale", host(sx_g), sx_o)
+    check_scales(layer.name + " w_scale", host(sw_g), sw_o)
+    flips = check_codes(layer.name + " xq", xq_gc, xq_o, tx, layer.a_bits)
+    flips += check_codes(layer.name + " wq", wq_gc, wq_o, tw, layer.w_bits)
+
+    # (ii) integer stage on the oracle's codes, (iii) whole chain
+    xq_od, wq_od = dev(pack_codes(xq_o)), dev(pack_codes(wq_o))
+    bias_d = dev(bias) if bias is not None else None
+    if layer.kind == "linear":
+        acc_o, y_o = oracle.int_linear(xq_o, sx_o, wq_o[:, 0, :], sw_o, bias)
+        acc_g = host(hq.hq_int_linear(xq_od, None, wq_od, None, None, y_dtype=torch.int32))
+        assert np.array_equal(acc_g, acc_o), layer.name + " int32 sums"
+        del acc_g, acc_o
+        if flips:
+            _, y_o = oracle.int_linear(xq_gc, sx_o, wq_gc[:, 0, :], sw_o, bias)
+        y_g = host(hq.hq_int_linear(xq_g, sx_g, wq_g, sw_g, bias_d, y_dtype=ydt))
+    else:
+        ks = layer.ksize
+        wq4 = lambda c: c.reshape(layer.n_out, ks, ks, layer.k_in)
+        acc_o, y_o = oracle.int_conv2d(xq_o, sx_o, wq4(wq_o), sw_o, bias, stride=1, pad=layer.pad)
+        acc_g = host(hq.hq_int_conv2d(xq_od, None, wq_od, None, None, ksize=ks, y_dtype=torch.int32))
+        assert np.array_equal(acc_g, acc_o), layer.name + " per-tap int32 sums"
+        del acc_g, acc_o
+        if flips:
+            _, y_o = oracle.int_conv2d(xq_gc, sx_o, wq4(wq_gc), sw_o, bias, stride=1, pad=layer.pad,
+                                       want_acc=False)
+        y_g = host(hq.hq_int_conv2d(xq_g, sx_g, wq_g, sw_g, bias_d, ksize=ks, y_dtype=ydt))
+    err = check_y(layer.name + " y", y_g.reshape(y_o.shape), y_o)
+    print("   ok: tie flips %d, y err %.2e" % (flips, err), flush=True)
+    return flips, err
+
+
+@pytest.mark.parametrize("layer", workloads.tiny_layers(), ids=lambda l: l.name)
+def test_tiny_layers(hq, layer):
+    run_layer(hq, layer)
+
+
+@pytest.mark.parametrize("config", [1, 2, 3, 4, 5])
+def test_benchmark_configs_full_size(hq, config):
+    """All five configurations at their full sizes, every output element compared."""
+    for layer in workloads.config_layers(config):
+        run_layer(hq, layer)
+
+
+# ---- quantiser edge cases --------------------------------------------------------------------
+
+@pytest.mark.parametrize("block", [1, 2, 4, 8, 16, 32, 64, 128])
+@pytest.mark.parametrize("dtype", [np.float16, np.float32])
+def test_act_quant_block_sizes(hq, block, dtype):
+    rng = np.random.default_rng(100 + block)
+    k = 384 if block <= 64 else 256
+    x = rng.standard_normal((77, k))
+    x[:, 5] *= 20
+    x = x.astype(dtype)
+    for bits in (3, 4):
+        q_o, s_o, t = oracle.act_hadamard_quant(x, block, bits)
+        q_g, s_g = hq.hq_act_hadamard_quant(dev(x), block, bits)
+        check_scales("scale", host(s_g), s_o)
+        check_codes("codes", unpack_codes(host(q_g)), q_o, t, bits)
+
+
+@pytest.mark.parametrize("m,k", [(1, 64), (1, 8640), (3, 9600), (5, 8), (1025, 8), (300, 2048),
+                                 (7, 2112), (4099, 192), (2, 16384)])
+def test_act_quant_shapes(hq, m, k):
+    """One row, rows longer than a workgroup holds, the shortest legal row, ragged last workgroup."""
+    rng = np.random.default_rng(m * 7 + k)
+    x = rng.standard_normal((m, k)).astype(np.float16)
+    block = 64 if k % 64 == 0 else 8
+    q_o, s_o, t = oracle.act_hadamard_quant(x, block, 4)
+    q_g, s_g = hq.hq_act_hadamard_quant(dev(x), block, 4)
+    check_scales("scale", host(s_g), s_o)
+    check_codes("codes", unpack_codes(host(q_g)), q_o, t, 4)
+
+
+def test_act_quant_degenerate_rows(hq):
+    """All-zero tokens (scale 1, codes 0), the paper's two worked examples, and exact ties."""
+    x = np.zeros((5, 192), dtype=np.float16)
+    x[1, 64 + 5] = -2.5                      # one-hot -> flat +-qmax pattern
+    x[2, 128:] = 0.75                        # constant block -> single spike
+    x[4, :] = 1.0
+    q_o, s_o, _ = oracle.act_hadamard_quant(x, 64, 4)
+    q_g, s_g = hq.hq_act_hadamard_quant(dev(x), 64, 4)
+    assert np.array_equal(unpack_codes(host(q_g)), q_o)      # all values exact in fp32: no slack
+    assert np.array_equal(host(s_g).astype(np.float64), s_o.astype(np.float32).astype(np.float64))
+    assert host(s_g)[0] == 1.0 and host(s_g)[3] == 1.0
+    # ties: abs-max 7 gives scale 1 with H = I, so t is exactly the input
+    xt = np.array([[7.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 6.5]], dtype=np.float32)
+    q_g, s_g = hq.hq_act_hadamard_quant(dev(xt), 1, 4)
+    assert unpack_codes(host(q_g))[0].tolist() == [7, 0, 2, 2, 0, -2, -2, 6]
+    assert host(s_g)[0] == 1.0
+
+
+def test_results_are_deterministic(hq):
+    layer = workloads.tiny_layers()[3]
+    x, w = dev(workloads.make_x(layer)), dev(workloads.make_w(layer))
+    outs = []
+    for _ in range(2):
+        xq, sx = hq.hq_act_hadamard_quant(x, 64, 4)
+        wq, sw = hq.hq_quantize_weights(w, 64, 4)
+        y = hq.hq_int_conv2d(xq, sx, wq, sw, None, ksize=3, y_dtype=torch.float16)
+        outs.append([host(t).copy() for t in (xq, sx, wq, sw, y)])
+    for a, b in zip(*outs):
+        assert np.array_equal(a.view(np.uint8), b.view(np.uint8))
+
+
+# ---- integer stage edge cases ----------------------------------------------------------------
+
+@pytest.mark.parametrize("m,n,k", [(1, 1, 64), (31, 17, 64), (129, 129, 128), (128, 256, 1024),
+                                   (1000, 40, 4096), (64, 520, 64)])
+def test_int_linear_extreme_codes(hq, m, n, k):
+    """Random full-range codes including -8, ragged tiles, long K: sums bit-exact."""
+    rng = np.random.default_rng(m + n + k)
+    xq = rng.integers(-8, 8, (m, k)).astype(np.int8)
+    wq = rng.integers(-8, 8, (n, k)).astype(np.int8)
+    xq[0, :], wq[0, :] = -8, -8              # the largest possible sum, 64 k
+    acc_o = oracle.int_gemm(xq, wq)
+    acc_g = host(hq.hq_int_linear(dev(pack_codes(xq)), None, dev(pack_codes(wq)), None, None,
+                                  y_dtype=torch.int32))
+    assert np.array_equal(acc_g, acc_o)
+    sx = rng.uniform(0.01, 1.0, m)
+    sw = rng.uniform(0.001, 0.1, n)
+    bias = rng.standard_normal(n).astype(np.float32)
+    _, y_o = oracle.int_linear(xq, sx.astype(np.float32), wq, sw.astype(np.float32), bias)
+    y_g = host(hq.hq_int_linear(dev(pack_codes(xq)), dev(sx.astype(np.float32)), dev(pack_codes(wq)),
+                                dev(sw.astype(np.float32)), dev(bias), y_dtype=torch.float32))
+    check_y("y", y_g, y_o, rtol=1e-5)
+
+
+@pytest.mark.parametrize("nb,h,w,cin,cout,ks", [(1, 1, 1, 64, 8, 3), (1, 3, 5, 64, 16, 3),
+                                                 (2, 8, 8, 128, 32, 3), (1, 20, 7, 64, 24, 3),
+                                                 (3, 5, 5, 64, 8, 1)])
+def test_int_conv_geometry(hq, nb, h, w, cin, cout, ks):
+    """Images smaller than a tile, tiles spanning several images, one-pixel images."""
+    rng = np.random.default_rng(nb * 1000 + h * 100 + w * 10 + ks)
+    xq = rng.integers(-8, 8, (nb, h, w, cin)).astype(np.int8)
+    wq = rng.integers(-8, 8, (cout, ks, ks, cin)).astype(np.int8)
+    sx = rng.uniform(0.01, 1.0, (nb, h, w)).astype(np.float32)
+    sw = rng.uniform(0.001, 0.1, cout).astype(np.float32)
+    bias = rng.standard_normal(cout).astype(np.float32)
+    acc_o, y_o = oracle.int_conv2d(xq, sx, wq, sw, bias, stride=1, pad=(ks - 1) // 2)
+    wq_d = dev(pack_codes(wq.reshape(cout, ks * ks, cin)))
+    acc_g = host(hq.hq_int_conv2d(dev(pack_codes(xq)), None, wq_d, None, None, ksize=ks,
+                                  y_dtype=torch.int32))
+    assert np.array_equal(acc_g, acc_o)
+    y_g = host(hq.hq_int_conv2d(dev(pack_codes(xq)), dev(sx), wq_d, dev(sw), dev(bias), ksize=ks,
+                                y_dtype=torch.float32))
+    check_y("y", y_g, y_o, rtol=1e-5)
+
+
+def test_errors_raise(hq):
+    x = torch.zeros((4, 96), dtype=torch.float16, device="cuda")
+    with pytest.raises(hq.HqError):
+        hq.hq_act_hadamard_quant(x, 64, 4)
+    with pytest.raises(hq.HqError):
+        hq.hq_act_hadamard_quant(x[:, :64].contiguous(), 64, 8)
