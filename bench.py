@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the Hadamard-quantised layer hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over the LDM-4-shaped layer sweep
+(configuration 5: batch 16, W4A4, fp16 I/O, block-64 Hadamard): for each of the
+nine layers, hq_act_hadamard_quant on the fp16 activation followed by
+hq_int_conv2d / hq_int_linear on the packed codes.  Weights are quantised once,
+offline, outside the timed region.  All inputs are seeded synthetic tensors,
+resident in HBM before timing starts.
+
+Prints ONE JSON line.  `value` is the aggregate integer throughput of the sweep
+(2*M*N*K_total operations per layer, summed, divided by the wall time of a
+step).  `roofline` is for the dominant kernel (the 3x3 implicit-GEMM
+convolutions) from HIP-event durations taken around every launch in a second,
+instrumented pass over the same steps.  `hadamard_quant` reports the standalone
+transform+quantise kernel on the largest activation, rotating through enough
+buffers to defeat the 256 MB last-level cache.  `cpu_baseline` is the CPU oracle
+on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 256 * 8192 * 2.4e9 / 1e12      # 5033 TOP/s dense int8, 256 CUs at 2.4 GHz
+HBM_PEAK_GBS = 8000.0
+CONFIG = 5
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2512_05746_amd as hq
+    import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    hq.load_library()
+    torch.cuda.set_device(0)
+    layers = workloads.config_layers(CONFIG)
+
+    # ---- resident inputs, offline weight preparation, preallocated outputs -----------------
+    state = []
+    for layer in layers:
+        x = torch.from_numpy(workloads.make_x(layer)).cuda()
+        w = torch.from_numpy(workloads.make_w(layer)).cuda()
+        wq, sw = hq.hq_quantize_weights(w, workloads.HAD_BLOCK, layer.w_bits)
+        del w
+        xq = torch.empty(x.shape[:-1] + (layer.k_in // 2,), dtype=torch.uint8, device="cuda")
+        sx = torch.empty(x.shape[:-1], dtype=torch.float32, device="cuda")
+        y = torch.empty(x.shape[:-1] + (layer.n_out,), dtype=torch.float16, device="cuda")
+        state.append((layer, x, wq, sw, xq, sx, y))
+    torch.cuda.synchronize()
+
+    def run_quant(s):
+        layer, x, wq, sw, xq, sx, y = s
+        hq.hq_act_hadamard_quant(x, workloads.HAD_BLOCK, layer.a_bits, out=(xq, sx))
+
+    def run_int(s):
+        layer, x, wq, sw, xq, sx, y = s
+        if layer.kind == "conv":
+            hq.hq_int_conv2d(xq, sx, wq, sw, None, ksize=layer.ksize, y_dtype=torch.float16, out=y)
+        else:
+            hq.hq_int_linear(xq, sx, wq, sw, None, y_dtype=torch.float16, out=y)
+
+    def step():
+        for s in state:
+            run_quant(s)
+            run_int(s)
+
+    total_ops = sum(l.ops for l in layers)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+    value = total_ops / (wall / args.steps) / 1e12
+
+    # ---- instrumented pass: HIP events around every launch ----------------------------------
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    records = []
+    for _ in range(args.steps):
+        for i, s in enumerate(state):
+            e0, e1, e2 = ev(), ev(), ev()
+            e0.record()
+            run_quant(s)
+            e1.record()
+            run_int(s)
+            e2.record()
+            records.append((i, e0, e1, e2))
+    torch.cuda.synchronize()
+    quant_us = np.zeros(len(state))
+    int_us = np.zeros(len(state))
+    for i, e0, e1, e2 in records:
+        quant_us[i] += e0.elapsed_time(e1) * 1e3 / args.steps
+        int_us[i] += e1.elapsed_time(e2) * 1e3 / args.steps
+
+    per_layer = []
+    for i, (layer, *_r) in enumerate(state):
+        out_bytes = layer.m * layer.n_out * 2
+        in_bytes = layer.m * layer.k_in // 2 + layer.m * 4
+        w_bytes = layer.n_out * layer.taps * layer.k_in // 2
+        q_bytes = layer.m * layer.k_in * 2 + layer.m * layer.k_in // 2 + layer.m * 4
+        per_layer.append({
+            "layer": layer.name, "gop": round(layer.ops / 1e9, 3),
+            "int_us": round(float(int_us[i]), 2),
+            "int_tops": round(layer.ops / int_us[i] / 1e6, 1),
+            "int_frac_mfma_peak": round(layer.ops / int_us[i] / 1e6 / INT8_MFMA_PEAK_TOPS, 4),
+            "int_gbs": round((out_bytes + in_bytes + w_bytes) / int_us[i] / 1e3, 1),
+            "quant_us": round(float(quant_us[i]), 2),
+            "quant_gbs": round(q_bytes / quant_us[i] / 1e3, 1),
+        })
+    conv3 = [i for i, (l, *_r) in enumerate(state) if l.kind == "conv" and l.ksize == 3]
+    conv3_ops = sum(state[i][0].ops for i in conv3)
+    conv3_us = float(sum(int_us[i] for i in conv3))
+    achieved = conv3_ops / conv3_us / 1e6
+    int_all_tops = total_ops / float(int_us.sum()) / 1e6
+
+    # ---- standalone transform+quantise on the largest activation, cache-defeating rotation --
+    big = max(state, key=lambda s: s[1].numel())
+    layer_b, xb = big[0], big[1]
+    nrot = 16
+    xs = [xb.clone() for _ in range(nrot)]
+    outs = [(torch.empty_like(big[4]), torch.empty_like(big[5])) for _ in range(nrot)]
+    q_bytes = xb.numel() * 2 + xb.numel() // 2 + layer_b.m * 4
+
+    def time_quant(bufs, reps):
+        for j in range(len(bufs)):
+            hq.hq_act_hadamard_quant(bufs[j], workloads.HAD_BLOCK, layer_b.a_bits, out=outs[j])
+        torch.cuda.synchronize()
+        es = [ev() for _ in range(reps + 1)]
+        es[0].record()
+        for r in range(reps):
+            j = r % len(bufs)
+            hq.hq_act_hadamard_quant(bufs[j], workloads.HAD_BLOCK, layer_b.a_bits, out=outs[j])
+            es[r + 1].record()
+        torch.cuda.synchronize()
+        d = [es[r].elapsed_time(es[r + 1]) * 1e3 for r in range(reps)]
+        return float(np.mean(d))
+
+    hq_us_hbm = time_quant(xs, 8 * nrot)
+    hq_us_cached = time_quant(xs[:1], 64)
+    del xs, outs
+
+    result = {
+        "metric": "w4a4_gemm_conv_tops", "value": round(value, 2), "unit": "TOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {
+            "workload": "configs[4]: LDM-4-shaped UNet layer sweep, batch 16, W4A4, fp16 I/O, "
+                        "block-64 Hadamard; 9 layers, act-quant + integer conv/linear each",
+            "total_gop": round(total_ops / 1e9, 2), "launches_per_step": 2 * len(state),
+        },
+        "frac_int8_mfma_peak_wall": round(value / INT8_MFMA_PEAK_TOPS, 4),
+        "int_stage_tops_kernel_time": round(int_all_tops, 1),
+        "frac_int8_mfma_peak_kernel_time": round(int_all_tops / INT8_MFMA_PEAK_TOPS, 4),
+        "roofline": {
+            "kernel": "int_gemm_kernel (3x3 implicit-GEMM convolutions of the sweep)",
+            "bound": "mfma", "achieved": round(achieved, 1), "peak": round(INT8_MFMA_PEAK_TOPS, 1),
+            "unit": "TOP/s", "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
+        },
+        "hadamard_quant": {
+            "kernel": "hq_act_hadamard_quant on %s fp16" % (list(xb.shape),),
+            "bytes_per_launch": q_bytes,
+            "us_hbm": round(hq_us_hbm, 2), "gbs_hbm": round(q_bytes / hq_us_hbm / 1e3, 1),
+            "frac_hbm_peak": round(q_bytes / hq_us_hbm / 1e3 / HBM_PEAK_GBS, 4),
+            "us_cache_resident": round(hq_us_cached, 2),
+            "gbs_cache_resident": round(q_bytes / hq_us_cached / 1e3, 1),
+            "rotating_buffers": nrot, "peak_gbs": HBM_PEAK_GBS,
+        },
+        "layers": per_layer,
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(layers)
+    print(json.dumps(result))
+
+
+def cpu_baseline(layers):
+    """The oracle, as it stands, on the first 2 images of each layer of the sweep."""
+    import numpy as np
+
+    import oracle
+    import workloads
+
+    oracle.build()
+    take = 2
+    ops = 0
+    prepared = []
+    for layer in layers:
+        x = workloads.make_x(layer)
+        w = workloads.make_w(layer)
+        if layer.kind == "conv":
+            x = x[:take]
+            m = take * x.shape[1] * x.shape[2]
+        else:
+            m = layer.m * take // 16
+            x = x[:m]
+        wq, sw, _ = oracle.quantize_weights(w, workloads.HAD_BLOCK, layer.w_bits)   # offline
+        prepared.append((layer, x, wq, sw))
+        ops += 2 * m * layer.n_out * layer.taps * layer.k_in
+    t0 = time.perf_counter()
+    for layer, x, wq, sw in prepared:
+        xq, sx, _ = oracle.act_hadamard_quant(x, workloads.HAD_BLOCK, layer.a_bits)
+        if layer.kind == "conv":
+            oracle.int_conv2d(xq, sx, wq.reshape(layer.n_out, layer.ksize, layer.ksize, layer.k_in), sw,
+                              None, stride=1, pad=layer.pad, want_acc=False)
+        else:
+            oracle.int_linear(xq, sx, wq[:, 0, :], sw, None)
+    dt = time.perf_counter() - t0
+    cores = oracle.max_threads()
+    return {"value": round(ops / dt / 1e12, 5), "unit": "TOP/s", "cores": cores, "kind": "oracle",
+            "seconds": round(dt, 2),
+            "sample": "first %d of 16 images of every layer of the sweep (%.1f GOP), fp64/int64 "
+                      "oracle with OpenMP over rows" % (take, ops / 1e9)}
+
+
+if __name__ == "__main__":
+    main()

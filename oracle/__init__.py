@@ -9,6 +9,7 @@ from .hq_oracle import (  # noqa: F401
     int_conv2d,
     int_gemm,
     int_linear,
+    max_threads,
     quantize_rows,
     quantize_weights,
 )

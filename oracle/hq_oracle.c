@@ -38,6 +38,19 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Threads the row loops below run on (for reporting next to timings). */
+int hqo_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 /* Sylvester recursion without the 1/sqrt(2): h is n x n with entries +-1,
  * n a power of two.  (Background, "Hadamard Transformation".) */

@@ -59,6 +59,8 @@ def _load():
         lib.hqo_dequant_linear.restype = None
         lib.hqo_int_conv2d.argtypes = [c_i8p, c_dp, c_i8p, c_dp, c_dp] + [i32] * 9 + [c_i64p, c_dp]
         lib.hqo_int_conv2d.restype = i32
+        lib.hqo_max_threads.argtypes = []
+        lib.hqo_max_threads.restype = i32
         _lib = lib
     return _lib
 
@@ -77,6 +79,11 @@ def _i64p(a):
 
 def _f64(a):
     return np.ascontiguousarray(np.asarray(a), dtype=np.float64)
+
+
+def max_threads() -> int:
+    """Threads the oracle's row loops use."""
+    return int(_load().hqo_max_threads())
 
 
 def hadamard_raw(n: int) -> np.ndarray:
