@@ -17,6 +17,19 @@ inline int ilog2(int v) {
     return l;
 }
 
+// Compute units of the current device (queried once per device; 256 on MI355X).
+inline int compute_units() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
 // Maps the sticky launch error (if any) of the calling thread to a status.
 inline hq_status launch_status() {
     return hipGetLastError() == hipSuccess ? HQ_OK : HQ_ERR_LAUNCH;

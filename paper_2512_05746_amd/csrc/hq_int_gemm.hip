@@ -8,22 +8,25 @@
 // the per-pixel activation scale of a tap is a single per-lane register and the
 // 16 channels of a lane are contiguous in the NHWC output.
 //
-// Nibble handling.  Codes are packed (two per byte) in HBM.  They are expanded
-// to int8 once per workgroup, on the way from global memory to LDS: a packed
+// Nibble handling.  Codes stay packed (two per byte) in HBM and in LDS; the copy
+// from global memory to LDS is a direct-to-LDS load that touches no register.
+// A wave expands the packed operands it has read from LDS in registers: a packed
 // dword w becomes the two int8x4 vectors
 //     lo = (w << 4) & 0xF0F0F0F0,   hi = w & 0xF0F0F0F0,
 // each byte holding 16 * code exactly (two's complement).  Both operands are
-// stored that way, so the MFMA accumulates 256 * sum(xq * wq); the factor is
-// exact and is removed by an arithmetic shift (int32 output) or folded into the
+// fed that way, so the MFMA accumulates 256 * sum(xq * wq); the factor is exact
+// and is removed by an arithmetic shift (int32 output) or folded into the
 // activation scale (floating-point output).  The order in which the codes of a
 // 64-wide K step reach the MFMA lanes is a permutation applied identically to
 // both operands, which leaves the sum unchanged.
 //
-// The kernel is bound by vector-ALU issue slots, not by the matrix pipe (one
-// 32x32x32 MFMA leaves room for about seven other vector instructions), so the
-// expansion is shared by all waves of a workgroup instead of being repeated by
-// every wave on its own operands, and the accumulators are never cleared by
-// moves: the first MFMA of a tap takes the constant 0 as its addend.
+// Why packed in LDS: measured on MI355X, LDS accepts writes at about 64 bytes per
+// clock per CU (reads: about 256), and one 32x32x32 int8 MFMA leaves issue room
+// for about seven other vector instructions.  Expanding to int8 before LDS
+// doubles the LDS write volume and made that the bound; expanding after the read
+// costs three vector instructions per packed dword instead.  The accumulators
+// are never cleared by moves: the first MFMA of a tap takes the constant 0 as
+// its addend.
 #include <hip/hip_fp16.h>
 
 #include "hq_common.h"
@@ -47,6 +50,7 @@ struct GemmArgs {
     int k;               // input channels (codes per tap)
     int h, w;            // image size (convolution only)
     int n_co_tiles;
+    uint32_t n_tiles;    // pixel tiles * channel tiles
 };
 
 // Output channel handled by row i of a 32-row MFMA tile.  Chosen so that the
@@ -63,20 +67,44 @@ __device__ __forceinline__ void expand(const v4i &p, v4i &first, v4i &second) {
     second = v4i{(p.z << 4) & m, p.z & m, (p.w << 4) & m, p.w & m};
 }
 
-// Asynchronous 16-byte global load, written as inline asm so that the waits can be
-// placed by hand: requests are issued four K steps ahead and the compiler's own
-// wait-count bookkeeping, which is conservative across the loop back-edge, would
-// drain them one step after issue.  `base` is wave-uniform, `offset` per lane.
-// The result may only be read after wait_vmem<N>() + pin().
-__device__ __forceinline__ void load16_async(v4i &dst, const uint8_t *base, uint32_t offset) {
-    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(offset), "s"(base) : "memory");
-}
-
 // Waits until at most N of this wave's vector-memory operations are outstanding.
 template <int N>
 __device__ __forceinline__ void wait_vmem() {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);
+}
+
+// Waits until at most N of this wave's LDS / scalar-memory operations are outstanding.
+template <int N>
+__device__ __forceinline__ void wait_lds() {
+    static_assert(N >= 0 && N < 16, "lgkmcnt is a 4-bit counter");
+    __builtin_amdgcn_s_waitcnt(0xC07F | (N << 8));
+}
+
+// Direct-to-LDS load: lane i's 16 bytes land at lds_wave_base + 16 * i (the LDS base is
+// wave-uniform).  Completion is tracked by vmcnt only.
+__device__ __forceinline__ void load_to_lds16(const uint8_t *src, uint8_t *lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+
+// LDS reads of the DMA-filled stages are inline asm: the compiler cannot tell which
+// stage a direct-to-LDS load targets and would drain every outstanding load (vmcnt(0))
+// before each LDS read it knows of, which serialises the pipeline.  The waits these
+// reads need (wait_lds) and the register pinning after them are placed by hand.
+__device__ __forceinline__ uint32_t lds_address(const void *p) {
+    return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((const __attribute__((address_space(3))) void *)p));
+}
+
+template <int OFFSET>
+__device__ __forceinline__ void lds_read16(v4i &dst, uint32_t addr) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFFSET) : "memory");
+}
+
+__device__ __forceinline__ float lds_read_f32_now(uint32_t addr) {
+    float r;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(r) : "v"(addr) : "memory");
+    return r;
 }
 
 // Ties a register to the point after the preceding hand-placed wait.
@@ -98,6 +126,24 @@ __device__ __forceinline__ int tap_mask(uint32_t pix, int h, int w) {
             mask |= (ih >= 0 && ih < h && iw >= 0 && iw < w) ? (1 << t) : 0;
         }
         return mask;
+    }
+}
+
+// Packed MFMA operands of one 64-code K step, as read from LDS.
+template <int TM, int TN>
+struct Packed {
+    v4i a[TM];
+    v4i b[TN];
+};
+
+template <int TM, int TN, int ROWB, int I = 0>
+__device__ __forceinline__ void read_packed(Packed<TM, TN> &o, uint32_t addr_a, uint32_t addr_b) {
+    if constexpr (I < TM) {
+        lds_read16<I * 32 * ROWB>(o.a[I], addr_a);
+        read_packed<TM, TN, ROWB, I + 1>(o, addr_a, addr_b);
+    } else if constexpr (I < TM + TN) {
+        lds_read16<(I - TM) * 32 * ROWB>(o.b[I - TM], addr_b);
+        read_packed<TM, TN, ROWB, I + 1>(o, addr_a, addr_b);
     }
 }
 
@@ -131,39 +177,45 @@ __device__ __forceinline__ void store16(float *dst, const float (&v)[16]) {
 // TM x TN MFMA tiles of 32x32 per wave, WAVES_M x WAVES_N waves per workgroup.
 // TAPS = 1 (linear / 1x1) or 9 (3x3, stride 1, pad 1).
 //
-// One K step is 64 codes (32 packed bytes per row, two 16-byte pieces).  While
-// step s is being multiplied from registers, the MFMA operands of step s+1 are
-// read from LDS, the packed pieces of step s+2 (fetched two steps earlier) are
-// expanded into a third LDS stage, and the pieces of step s+4 are requested
-// from global memory; one barrier per step.  LDS stage layout per operand:
-// [unit 0..3][row][16 bytes] with unit = 2 * (k slice) + (lane half).  A thread
-// writes units u and u+2 of its row with one instruction each, so the unit
-// stride is padded by 64 bytes: two units apart is then half a bank cycle away,
-// and both the expanding writes and the operand reads are conflict free.
+// K is consumed in chunks of KCH 16-byte pieces per row (KCH * 32 codes); NSTAGE
+// chunks of both operands live in LDS, filled by direct-to-LDS loads issued
+// NSTAGE-1 chunks ahead of the MFMAs; one barrier per chunk.  Inside a wave-wide
+// load, KCH consecutive lanes fetch one row's contiguous KCH*16 bytes and
+// consecutive lane groups fetch consecutive rows, so a load of activation rows
+// reads one contiguous KiB.  The LDS image of a stage is row-major
+// [row][KCH*16 bytes]; in rows 8..15 (mod 16) adjacent pieces are swapped, which
+// makes the 16-byte operand reads of 16 consecutive rows hit 16 different bank
+// groups.  Inside a chunk the packed operands of K step k+1 are read from LDS
+// while the MFMAs of step k run.
 //
 // Rows that do not exist (channels >= n, pixels >= pixels, taps outside the
 // image) are loaded from a clamped in-bounds address instead of being zeroed:
 // their sums are never stored, and a tap outside the image has scale 0.
-template <int TM, int TN, int WAVES_M, int WAVES_N, int TAPS, int OUT, int OCC>
+template <int TM, int TN, int WAVES_M, int WAVES_N, int TAPS, int OUT, int KCH, int NSTAGE, int OCC>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(GemmArgs a) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int NT = 64 * NW;
     constexpr int BCO = 32 * TM * WAVES_M;   // output channels per workgroup
     constexpr int BP = 32 * TN * WAVES_N;    // pixels per workgroup
-    constexpr int A_PIECES = 2 * BCO, B_PIECES = 2 * BP;
-    constexpr int A_PER_T = (A_PIECES + NT - 1) / NT, B_PER_T = (B_PIECES + NT - 1) / NT;
-    static_assert(A_PIECES % 64 == 0 && B_PIECES % 64 == 0, "piece guards must be wave-uniform");
-    static_assert(2 * (A_PER_T + B_PER_T) < 64, "vmcnt range");
-    constexpr int A_US = BCO * 16 + 64, B_US = BP * 16 + 64;   // unit strides (see below)
-    constexpr int A_BYTES = 4 * A_US, STAGE_BYTES = 4 * (A_US + B_US);
+    constexpr int ROWB = KCH * 16;           // bytes per row per chunk
+    constexpr int KS = KCH / 2;              // 64-code K steps per chunk
+    static_assert(KCH % 2 == 0, "a 64-code K step is two pieces");
+    static_assert((BCO * KCH) % 64 == 0 && (BP * KCH) % 64 == 0, "whole wave-wide loads only");
+    constexpr int A_INSTR = BCO * KCH / 64, B_INSTR = BP * KCH / 64;   // 1 KiB loads per chunk
+    static_assert((A_INSTR + B_INSTR) % NW == 0, "loads must split evenly over the waves");
+    constexpr int LPW = (A_INSTR + B_INSTR) / NW;
+    static_assert((NSTAGE - 2) * LPW < 64, "vmcnt range");
+    static_assert(TM + TN < 16, "lgkmcnt range");
+    constexpr int STAGE_BYTES = (BCO + BP) * ROWB;
     using Out = typename OutT<OUT>::type;
+    using Ops = Packed<TM, TN>;
 
-    __shared__ __attribute__((aligned(16))) uint8_t lds[3 * STAGE_BYTES];
+    // [stage][operand][row][ROWB bytes]
+    __shared__ __attribute__((aligned(16))) uint8_t lds[NSTAGE * STAGE_BYTES];
     __shared__ float s_sx[TAPS][BP];   // x_scale / 256 of the input pixel under tap t; 0 outside
     __shared__ int s_mask[BP];         // bit t: tap t of this output pixel is inside the image
     __shared__ __attribute__((aligned(16))) float s_sw[BCO];     // w_scale of the tile's channels
     __shared__ __attribute__((aligned(16))) float s_bias[BCO];   // bias (0 if absent)
-    constexpr int NL = A_PER_T + B_PER_T;   // loads every thread issues per K step
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -171,103 +223,90 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
     const int lrow = lane & 31, lhalf = lane >> 5;
 
-    const int tile_co = blockIdx.x % a.n_co_tiles;
-    const uint32_t tile_p = blockIdx.x / a.n_co_tiles;
+    const int kbytes = a.k >> 1;                 // packed bytes per (row, tap)
+    const int chunks_per_tap = kbytes / ROWB;    // host guarantees divisibility
+    const int total_chunks = TAPS * chunks_per_tap;
+    const uint32_t lds_a = lds_address(lds) + (wave_m * TM * 32 + lrow) * ROWB + (lhalf ^ ((lrow >> 3) & 1)) * 16;
+    const uint32_t lds_b = lds_a + (BCO + (wave_n * TN - wave_m * TM) * 32) * ROWB;
+    const uint32_t lds_sx = lds_address(&s_sx[0][0]) + (wave_n * TN * 32 + lrow) * 4;
+
+    // Persistent workgroups: the grid is sized to the machine and every workgroup walks the
+    // tile list with the grid as stride (output-channel tiles of one pixel tile are adjacent).
+    for (uint32_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
+    const int tile_co = tile % a.n_co_tiles;
+    const uint32_t tile_p = tile / a.n_co_tiles;
     const int co0 = tile_co * BCO;
     const uint32_t p0 = tile_p * BP;
-    const int kbytes = a.k >> 1;      // packed bytes per (row, tap)
-    const int kc_steps = a.k >> 6;    // 64-code steps per tap
-    const int total_steps = TAPS * kc_steps;
 
-    // ---- this thread's pieces of a K step -----------------------------------------------------
-    // Piece = 16 packed bytes of one row: (row, pc) with pc = 0, 1.  Every thread issues the
-    // same number of loads per step (the hand-placed wait counts rely on it); with fewer
-    // pieces than threads the surplus threads re-load a piece and do not store it.
-    uint32_t a_off[A_PER_T];   // byte offset of the piece at flattened step 0
-    int a_lds[A_PER_T];
-#pragma unroll
-    for (int j = 0; j < A_PER_T; ++j) {
-        const int piece = (tid + j * NT) % A_PIECES;
-        const int row = piece >> 1, pc = piece & 1;
-        int co = co0 + (row & ~31) + tile_row_to_channel(row & 31);
-        co = co < a.n ? co : a.n - 1;
-        a_off[j] = static_cast<uint32_t>(co) * TAPS * kbytes + pc * 16;
-        a_lds[j] = (2 * pc) * A_US + row * 16;
-    }
-    uint32_t b_off[B_PER_T];   // byte offset of the piece at tap "own pixel", k 0
-    int b_mask[B_PER_T];       // bit t: tap t of the row's pixel is inside the image
-    int b_lds[B_PER_T];
-#pragma unroll
-    for (int j = 0; j < B_PER_T; ++j) {
-        const int piece = (tid + j * NT) % B_PIECES;
-        const int row = piece >> 1, pc = piece & 1;
-        uint32_t pix = p0 + row;
-        pix = pix < a.pixels ? pix : a.pixels - 1;
-        b_off[j] = pix * kbytes + pc * 16;
-        b_mask[j] = tap_mask<TAPS>(pix, a.h, a.w);
-        b_lds[j] = A_BYTES + (2 * pc) * B_US + row * 16;
-    }
-
-    v4i ga[2][A_PER_T], gb[2][B_PER_T];   // two register stages of packed pieces
-    int ftap = 0, fkc = 0, fstep = 0;     // step being fetched
-    // Issues the loads of the next step to fetch (asynchronous; see wait_vmem below).
-    auto fetch = [&](v4i(&ra)[A_PER_T], v4i(&rb)[B_PER_T]) {
-        if (fstep >= total_steps) return;
-        const uint8_t *wbase = a.wq + fstep * 32;      // taps are contiguous in a weight row
-        int shift = 0;
-        if constexpr (TAPS > 1) shift = ((ftap / 3 - 1) * a.w + (ftap % 3 - 1)) * kbytes;
-        const uint8_t *xbase = a.xq + fkc * 32;
-#pragma unroll
-        for (int j = 0; j < A_PER_T; ++j) load16_async(ra[j], wbase, a_off[j]);
-#pragma unroll
-        for (int j = 0; j < B_PER_T; ++j)
-            load16_async(rb[j], xbase, b_off[j] + (((b_mask[j] >> ftap) & 1) ? shift : 0));
-        ++fstep;
-        if (++fkc == kc_steps) { fkc = 0; ++ftap; }
-    };
-    auto expand_to_lds = [&](int stage, v4i(&ra)[A_PER_T], v4i(&rb)[B_PER_T]) {
-        uint8_t *base = lds + stage * STAGE_BYTES;
-#pragma unroll
-        for (int j = 0; j < A_PER_T; ++j) {
-            pin(ra[j]);
-            if ((j + 1) * NT <= A_PIECES || tid + j * NT < A_PIECES) {
-                v4i u0, u1;
-                expand(ra[j], u0, u1);
-                *reinterpret_cast<v4i *>(base + a_lds[j]) = u0;
-                *reinterpret_cast<v4i *>(base + a_lds[j] + A_US) = u1;
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < B_PER_T; ++j) {
-            pin(rb[j]);
-            if ((j + 1) * NT <= B_PIECES || tid + j * NT < B_PIECES) {
-                v4i u0, u1;
-                expand(rb[j], u0, u1);
-                *reinterpret_cast<v4i *>(base + b_lds[j]) = u0;
-                *reinterpret_cast<v4i *>(base + b_lds[j] + B_US) = u1;
-            }
-        }
-    };
-
-    // ---- prologue, part 1: the first four steps are requested before anything else ---------
-    fetch(ga[0], gb[0]);
-    fetch(ga[1], gb[1]);
-
-    // ---- per-pixel and per-channel tables (their loads overlap the requests above) ----------
+    // ---- tap masks first: the activation loads need them ---------------------------------------
     for (int p = tid; p < BP; p += NT) {
         const uint32_t pix = p0 + p;
-        const bool valid = pix < a.pixels;
-        const int mask = valid ? tap_mask<TAPS>(pix, a.h, a.w) : 0;
-        if constexpr (OUT != kOutI32) {
+        s_mask[p] = pix < a.pixels ? tap_mask<TAPS>(pix, a.h, a.w) : 0;
+    }
+    __syncthreads();
+
+    // ---- this wave's share of the direct-to-LDS loads -------------------------------------------
+    uint32_t ld_off[LPW];     // byte offset of this lane's piece at tap 0, chunk 0
+    int ld_mask[LPW];         // activation rows: taps inside the image
+#pragma unroll
+    for (int j = 0; j < LPW; ++j) {
+        const int ii = j * NW + wave;          // wave-uniform index of the 1 KiB load
+        const int q = (ii < A_INSTR ? ii : ii - A_INSTR) * 64 + lane;   // 16-byte slot in the tile image
+        const int row = q / KCH;
+        const int piece = (q % KCH) ^ ((row >> 3) & 1);                 // swizzle, see above
+        if (ii < A_INSTR) {
+            int co = co0 + (row & ~31) + tile_row_to_channel(row & 31);
+            co = co < a.n ? co : a.n - 1;
+            ld_off[j] = static_cast<uint32_t>(co) * TAPS * kbytes + piece * 16;
+            ld_mask[j] = 0;
+        } else {
+            uint32_t pix = p0 + row;
+            pix = pix < a.pixels ? pix : a.pixels - 1;
+            ld_off[j] = pix * kbytes + piece * 16;
+            ld_mask[j] = s_mask[row];
+        }
+    }
+    uint32_t ld_cur[LPW];     // ld_off + the term of the tap being fetched
+    auto set_fetch_tap = [&](int t) {
+        const int shift = TAPS > 1 ? ((t / 3 - 1) * a.w + (t % 3 - 1)) * kbytes : 0;
+#pragma unroll
+        for (int j = 0; j < LPW; ++j) {
+            if (j * NW + wave < A_INSTR) ld_cur[j] = ld_off[j] + t * kbytes;
+            else ld_cur[j] = ld_off[j] + (((ld_mask[j] >> t) & 1) ? shift : 0);
+        }
+    };
+    int ftap = 0, fch = 0, fetched = 0;   // chunk being fetched
+    auto issue_loads = [&](int stage) {
+#pragma unroll
+        for (int j = 0; j < LPW; ++j) {
+            const int ii = j * NW + wave;
+            const uint8_t *base = (ii < A_INSTR ? a.wq : a.xq) + fch * ROWB;
+            // stage image: A rows then B rows, each wave-wide load fills the next 1 KiB
+            load_to_lds16(base + ld_cur[j], lds + stage * STAGE_BYTES + ii * 1024);
+        }
+        ++fetched;
+        if (++fch == chunks_per_tap) {
+            fch = 0;
+            if (++ftap < TAPS) set_fetch_tap(ftap);
+        }
+    };
+
+    // ---- prologue: fill NSTAGE-1 stages, then build the scale tables under their latency --------
+    set_fetch_tap(0);
+#pragma unroll
+    for (int st = 0; st < NSTAGE - 1; ++st)
+        if (fetched < total_chunks) issue_loads(st);
+
+    if constexpr (OUT != kOutI32) {
+        for (int p = tid; p < BP; p += NT) {
+            const uint32_t pix = p0 + p;
+            const int mask = s_mask[p];
 #pragma unroll
             for (int t = 0; t < TAPS; ++t) {
                 const int delta = TAPS > 1 ? (t / 3 - 1) * a.w + (t % 3 - 1) : 0;
                 s_sx[t][p] = ((mask >> t) & 1) ? a.sx[static_cast<int64_t>(pix) + delta] * (1.0f / 256.0f) : 0.f;
             }
         }
-        s_mask[p] = mask;
-    }
-    if constexpr (OUT != kOutI32) {
         const Out *bias = static_cast<const Out *>(a.bias);
         for (int c = tid; c < BCO; c += NT) {
             const int co = co0 + c;
@@ -275,6 +314,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
             s_bias[c] = (co < a.n && bias) ? to_float(bias[co]) : 0.f;
         }
     }
+    __syncthreads();   // tables visible to every wave before the first raw barrier below
 
     v16i acc[TM][TN];
     float facc[TAPS > 1 ? TM : 1][TAPS > 1 ? TN : 1][16];
@@ -287,64 +327,59 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
                 for (int r = 0; r < 16; ++r) facc[tm][tn][r] = 0.f;
     }
 
-    const int rd_a = lhalf * A_US + (wave_m * TM * 32 + lrow) * 16;
-    const int rd_b = A_BYTES + lhalf * B_US + (wave_n * TN * 32 + lrow) * 16;
-
-    // MFMA operands of one K step: [k slice][tile]
-    struct Operands { v4i a[2][TM]; v4i b[2][TN]; };
-    auto read_operands = [&](int stage, Operands &o) {
-        const uint8_t *sa = lds + stage * STAGE_BYTES + rd_a;
-        const uint8_t *sb = lds + stage * STAGE_BYTES + rd_b;
+    // MFMAs of one K step; FIRST: the sums of a tap start from 0
+    auto multiply = [&](Ops &o, bool first) {
+        v4i a0[TM], a1[TM], b0[TN], b1[TN];
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        for (int tm = 0; tm < TM; ++tm) { pin(o.a[tm]); expand(o.a[tm], a0[tm], a1[tm]); }
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-                o.a[ks][tm] = *reinterpret_cast<const v4i *>(sa + tm * 512 + 2 * ks * A_US);
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-                o.b[ks][tn] = *reinterpret_cast<const v4i *>(sb + tn * 512 + 2 * ks * B_US);
-        }
-    };
-
-    int tap = 0, kc = 0;   // step being multiplied
-    int st_cur = 0;        // LDS stage of the step being multiplied (step % 3)
-    // One K step s.  On entry `cur` holds the operands of s, LDS stage (s+1)%3 holds step
-    // s+1, and `g` holds the packed pieces of step s+2 (requested two iterations ago; the
-    // only requests issued since are the NL of the previous iteration).
-    auto iteration = [&](int step, const Operands &cur, Operands &nxt, v4i(&g_a)[A_PER_T],
-                         v4i(&g_b)[B_PER_T]) {
-        const int st_next = st_cur == 2 ? 0 : st_cur + 1;
-        const int st_far = st_next == 2 ? 0 : st_next + 1;
-        if (step + 1 < total_steps) read_operands(st_next, nxt);
-
-        if (kc == 0) {
+        for (int tn = 0; tn < TN; ++tn) { pin(o.b[tn]); expand(o.b[tn], b0[tn], b1[tn]); }
+        if (first) {
             const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.a[0][tm], cur.b[0][tn], zero, 0, 0, 0);
+                    acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[tm], b0[tn], zero, 0, 0, 0);
         } else {
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.a[0][tm], cur.b[0][tn], acc[tm][tn], 0, 0, 0);
+                    acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[tm], b0[tn], acc[tm][tn], 0, 0, 0);
         }
-        if (step + 2 < total_steps) {
-            if (step + 3 < total_steps) wait_vmem<NL>();   // the previous iteration's requests may stay pending
-            else wait_vmem<0>();
-            expand_to_lds(st_far, g_a, g_b);
-        }
-        fetch(g_a, g_b);   // step + 4
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn)
-                acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.a[1][tm], cur.b[1][tn], acc[tm][tn], 0, 0, 0);
+                acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[tm], b1[tn], acc[tm][tn], 0, 0, 0);
+    };
 
-        if (++kc == kc_steps) {
-            kc = 0;
+    int tap = 0, ch = 0;
+    int stage = 0;
+    for (int chunk = 0; chunk < total_chunks; ++chunk) {
+        // this chunk has landed once at most the later (NSTAGE-2) chunks' loads are pending
+        if (chunk + NSTAGE - 2 < total_chunks) wait_vmem<(NSTAGE - 2) * LPW>();
+        else wait_vmem<0>();
+        __builtin_amdgcn_s_barrier();   // every wave's share has landed; the previous stage is free
+        if (fetched < total_chunks) issue_loads(stage == 0 ? NSTAGE - 1 : stage - 1);
+
+        const uint32_t sa = lds_a + stage * STAGE_BYTES, sb = lds_b + stage * STAGE_BYTES;
+        Ops op[2];
+        read_packed<TM, TN, ROWB>(op[0], sa, sb);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            if (ks + 1 < KS) {
+                read_packed<TM, TN, ROWB>(op[(ks + 1) & 1], sa + (ks + 1) * 32, sb + (ks + 1) * 32);
+                wait_lds<TM + TN>();   // everything but the reads just issued
+            } else {
+                wait_lds<0>();
+            }
+            multiply(op[ks & 1], ks == 0 && ch == 0);
+        }
+
+        if (++ch == chunks_per_tap) {
+            ch = 0;
             // ---- end of a tap: fold the integer sums into the result ----------------------
             if constexpr (OUT == kOutI32) {
                 int *yi = static_cast<int *>(a.y);
@@ -367,7 +402,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
             } else if constexpr (TAPS > 1) {
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn) {
-                    const float s = s_sx[tap][(wave_n * TN + tn) * 32 + lrow];
+                    const float s = lds_read_f32_now(lds_sx + (tap * BP + tn * 32) * 4);
 #pragma unroll
                     for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -377,22 +412,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
             }
             ++tap;
         }
-        st_cur = st_next;
-        __syncthreads();
-    };
-
-    // ---- prologue, part 2: steps 0 and 1 into LDS, steps 2 and 3 requested ----------------------
-    wait_vmem<0>();
-    expand_to_lds(0, ga[0], gb[0]);
-    if (total_steps > 1) expand_to_lds(1, ga[1], gb[1]);
-    fetch(ga[0], gb[0]);
-    fetch(ga[1], gb[1]);
-    __syncthreads();
-    Operands op0, op1;
-    read_operands(0, op0);
-    for (int step = 0; step < total_steps; step += 2) {
-        iteration(step, op0, op1, ga[0], gb[0]);
-        if (step + 1 < total_steps) iteration(step + 1, op1, op0, ga[1], gb[1]);
+        stage = stage + 1 == NSTAGE ? 0 : stage + 1;
     }
 
     // ---- dequantising epilogue -------------------------------------------------------------
@@ -435,23 +455,30 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
             }
         }
     }
+    __syncthreads();   // LDS (stages and tables) is reused by the next tile
+    }
 }
 
-template <int TM, int TN, int WAVES_M, int WAVES_N, int TAPS, int OUT, int OCC>
+template <int TM, int TN, int WAVES_M, int WAVES_N, int TAPS, int OUT, int KCH, int NSTAGE, int OCC>
 hq_status launch_tile(GemmArgs a, hipStream_t stream) {
     constexpr int BCO = 32 * TM * WAVES_M, BP = 32 * TN * WAVES_N;
     a.n_co_tiles = (a.n + BCO - 1) / BCO;
     const int64_t p_tiles = (static_cast<int64_t>(a.pixels) + BP - 1) / BP;
-    const int64_t grid = p_tiles * a.n_co_tiles;
-    if (grid > 0x7fffffffLL) return HQ_ERR_SHAPE;
-    hipLaunchKernelGGL((int_gemm_kernel<TM, TN, WAVES_M, WAVES_N, TAPS, OUT, OCC>),
-                       dim3(static_cast<unsigned>(grid)), dim3(64 * WAVES_M * WAVES_N), 0, stream, a);
+    const int64_t tiles = p_tiles * a.n_co_tiles;
+    if (tiles > 0x7fffffffLL) return HQ_ERR_SHAPE;
+    a.n_tiles = static_cast<uint32_t>(tiles);
+    const int64_t slots = static_cast<int64_t>(hq::compute_units()) * OCC;   // co-resident workgroups
+    const unsigned grid = static_cast<unsigned>(tiles < slots ? tiles : slots);
+    hipLaunchKernelGGL((int_gemm_kernel<TM, TN, WAVES_M, WAVES_N, TAPS, OUT, KCH, NSTAGE, OCC>),
+                       dim3(grid), dim3(64 * WAVES_M * WAVES_N), 0, stream, a);
     return hq::launch_status();
 }
 
 template <int TAPS, int OUT>
 hq_status launch_shape(const GemmArgs &a, hipStream_t stream) {
-    return launch_tile<2, 2, 2, 2, TAPS, OUT, 2>(a, stream);
+    // chunks of 192 codes (96 contiguous bytes per row) whenever the channel count allows
+    if (a.k % 192 == 0) return launch_tile<2, 2, 2, 2, TAPS, OUT, 6, 2, 2>(a, stream);
+    return launch_tile<2, 2, 2, 2, TAPS, OUT, 2, 4, 2>(a, stream);
 }
 
 template <int TAPS>
@@ -493,7 +520,7 @@ extern "C" hq_status hq_int_linear(const uint8_t *xq, const float *x_scale, cons
     hq_status st = check_common(xq, x_scale, wq, w_scale, bias, m, n, k, y, y_dtype);
     if (st != HQ_OK) return st;
     if (!fits_32bit(m, n, 1, k)) return HQ_ERR_UNSUPPORTED;
-    GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(m), n, k, 1, 1, 0};
+    GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(m), n, k, 1, 1, 0, 0};
     return launch_out<1>(a, y_dtype, static_cast<hipStream_t>(stream));
 }
 
@@ -510,7 +537,7 @@ extern "C" hq_status hq_int_conv2d(const uint8_t *xq, const float *x_scale, cons
     if (st != HQ_OK) return st;
     if (r != s || (r != 1 && r != 3) || stride != 1 || pad != (r - 1) / 2) return HQ_ERR_UNSUPPORTED;
     if (!fits_32bit(pixels, c_out, r * s, c_in)) return HQ_ERR_UNSUPPORTED;
-    GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(pixels), c_out, c_in, h, w, 0};
+    GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(pixels), c_out, c_in, h, w, 0, 0};
     hipStream_t st_ = static_cast<hipStream_t>(stream);
     return r == 1 ? launch_out<1>(a, y_dtype, st_) : launch_out<9>(a, y_dtype, st_);
 }
