@@ -177,6 +177,13 @@ __device__ __forceinline__ void store16(float *dst, const float (&v)[16]) {
 // TM x TN MFMA tiles of 32x32 per wave, WAVES_M x WAVES_N waves per workgroup.
 // TAPS = 1 (linear / 1x1) or 9 (3x3, stride 1, pad 1).
 //
+// Persistent workgroups: the grid is sized to the machine and every workgroup
+// walks its tiles (grid stride; output-channel tiles of one pixel tile are
+// adjacent).  All chunks of all its tiles form ONE stream through the LDS
+// stages, so the loads of the next tile's first chunks are in flight while the
+// current tile is finished and written out, and the scale tables of the next
+// tile are built during the current one (two table sets).
+//
 // K is consumed in chunks of KCH 16-byte pieces per row (KCH * 32 codes); NSTAGE
 // chunks of both operands live in LDS, filled by direct-to-LDS loads issued
 // NSTAGE-1 chunks ahead of the MFMAs; one barrier per chunk.  Inside a wave-wide
@@ -206,16 +213,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     constexpr int LPW = (A_INSTR + B_INSTR) / NW;
     static_assert((NSTAGE - 2) * LPW < 64, "vmcnt range");
     static_assert(TM + TN < 16, "lgkmcnt range");
+    static_assert(BP <= NT && BCO <= NT, "one table entry per thread");
     constexpr int STAGE_BYTES = (BCO + BP) * ROWB;
+    constexpr int SX_PER_T = (TAPS * BP + NT - 1) / NT;   // scale-table entries per thread
     using Out = typename OutT<OUT>::type;
     using Ops = Packed<TM, TN>;
 
     // [stage][operand][row][ROWB bytes]
     __shared__ __attribute__((aligned(16))) uint8_t lds[NSTAGE * STAGE_BYTES];
-    __shared__ float s_sx[TAPS][BP];   // x_scale / 256 of the input pixel under tap t; 0 outside
-    __shared__ int s_mask[BP];         // bit t: tap t of this output pixel is inside the image
-    __shared__ __attribute__((aligned(16))) float s_sw[BCO];     // w_scale of the tile's channels
-    __shared__ __attribute__((aligned(16))) float s_bias[BCO];   // bias (0 if absent)
+    // two sets of per-tile tables: the set of tile k+1 is built while tile k is multiplied
+    __shared__ float s_sx[2][TAPS][BP];   // x_scale / 256 of the input pixel under tap t; 0 outside
+    __shared__ int s_mask[2][BP];         // bit t: tap t of this output pixel is inside the image
+    __shared__ __attribute__((aligned(16))) float s_sw[2][BCO];     // w_scale of the tile's channels
+    __shared__ __attribute__((aligned(16))) float s_bias[2][BCO];   // bias (0 if absent)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -228,45 +238,72 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     const int total_chunks = TAPS * chunks_per_tap;
     const uint32_t lds_a = lds_address(lds) + (wave_m * TM * 32 + lrow) * ROWB + (lhalf ^ ((lrow >> 3) & 1)) * 16;
     const uint32_t lds_b = lds_a + (BCO + (wave_n * TN - wave_m * TM) * 32) * ROWB;
-    const uint32_t lds_sx = lds_address(&s_sx[0][0]) + (wave_n * TN * 32 + lrow) * 4;
+    const uint32_t lds_sx = lds_address(&s_sx[0][0][0]) + (wave_n * TN * 32 + lrow) * 4;
 
-    // Persistent workgroups: the grid is sized to the machine and every workgroup walks the
-    // tile list with the grid as stride (output-channel tiles of one pixel tile are adjacent).
-    for (uint32_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
-    const int tile_co = tile % a.n_co_tiles;
-    const uint32_t tile_p = tile / a.n_co_tiles;
-    const int co0 = tile_co * BCO;
-    const uint32_t p0 = tile_p * BP;
+    if (blockIdx.x >= a.n_tiles) return;
+    const uint32_t my_tiles = (a.n_tiles - blockIdx.x + gridDim.x - 1) / gridDim.x;
+    const uint32_t stream_chunks = my_tiles * total_chunks;   // < 2^31, checked on the host
+    auto tile_origin = [&](uint32_t k, int &co0, uint32_t &p0) {
+        const uint32_t tile = blockIdx.x + k * gridDim.x;
+        co0 = static_cast<int>(tile % a.n_co_tiles) * BCO;
+        p0 = (tile / a.n_co_tiles) * BP;
+    };
 
-    // ---- tap masks first: the activation loads need them ---------------------------------------
-    for (int p = tid; p < BP; p += NT) {
-        const uint32_t pix = p0 + p;
-        s_mask[p] = pix < a.pixels ? tap_mask<TAPS>(pix, a.h, a.w) : 0;
-    }
-    __syncthreads();
+    // ---- per-tile tables ---------------------------------------------------------------------
+    auto build_masks = [&](uint32_t k) {   // no memory reads
+        int co0; uint32_t p0;
+        tile_origin(k, co0, p0);
+        if (tid < BP) {
+            const uint32_t pix = p0 + tid;
+            s_mask[k & 1][tid] = pix < a.pixels ? tap_mask<TAPS>(pix, a.h, a.w) : 0;
+        }
+    };
+    float t_sx[SX_PER_T], t_sw = 0.f, t_bias = 0.f;
+    auto load_scales = [&](uint32_t k) {   // needs the masks of tile k to be visible
+        if constexpr (OUT != kOutI32) {
+            int co0; uint32_t p0;
+            tile_origin(k, co0, p0);
+#pragma unroll
+            for (int j = 0; j < SX_PER_T; ++j) {
+                const int e = tid + j * NT;
+                const int t = e / BP, p = e % BP;
+                t_sx[j] = 0.f;
+                if (e < TAPS * BP && ((s_mask[k & 1][p] >> t) & 1)) {
+                    const int delta = TAPS > 1 ? (t / 3 - 1) * a.w + (t % 3 - 1) : 0;
+                    t_sx[j] = a.sx[static_cast<int64_t>(p0 + p) + delta];
+                }
+            }
+            if (tid < BCO && co0 + tid < a.n) {
+                t_sw = a.sw[co0 + tid];
+                const Out *bias = static_cast<const Out *>(a.bias);
+                t_bias = bias ? to_float(bias[co0 + tid]) : 0.f;
+            } else {
+                t_sw = 0.f;
+                t_bias = 0.f;
+            }
+        }
+    };
+    auto store_scales = [&](uint32_t k) {
+        if constexpr (OUT != kOutI32) {
+#pragma unroll
+            for (int j = 0; j < SX_PER_T; ++j) {
+                const int e = tid + j * NT;
+                if (e < TAPS * BP) (&s_sx[k & 1][0][0])[e] = t_sx[j] * (1.0f / 256.0f);
+            }
+            if (tid < BCO) {
+                s_sw[k & 1][tid] = t_sw;
+                s_bias[k & 1][tid] = t_bias;
+            }
+        }
+    };
 
     // ---- this wave's share of the direct-to-LDS loads -------------------------------------------
-    uint32_t ld_off[LPW];     // byte offset of this lane's piece at tap 0, chunk 0
+    uint32_t ld_off[LPW];     // byte offset of this lane's piece at tap 0, chunk 0 of the tile being fetched
     int ld_mask[LPW];         // activation rows: taps inside the image
-#pragma unroll
-    for (int j = 0; j < LPW; ++j) {
-        const int ii = j * NW + wave;          // wave-uniform index of the 1 KiB load
-        const int q = (ii < A_INSTR ? ii : ii - A_INSTR) * 64 + lane;   // 16-byte slot in the tile image
-        const int row = q / KCH;
-        const int piece = (q % KCH) ^ ((row >> 3) & 1);                 // swizzle, see above
-        if (ii < A_INSTR) {
-            int co = co0 + (row & ~31) + tile_row_to_channel(row & 31);
-            co = co < a.n ? co : a.n - 1;
-            ld_off[j] = static_cast<uint32_t>(co) * TAPS * kbytes + piece * 16;
-            ld_mask[j] = 0;
-        } else {
-            uint32_t pix = p0 + row;
-            pix = pix < a.pixels ? pix : a.pixels - 1;
-            ld_off[j] = pix * kbytes + piece * 16;
-            ld_mask[j] = s_mask[row];
-        }
-    }
     uint32_t ld_cur[LPW];     // ld_off + the term of the tap being fetched
+    uint32_t fk = 0;          // tile (index in this workgroup's list) being fetched
+    int ftap = 0, fch = 0;
+    uint32_t fetched = 0;     // chunks of the stream requested so far
     auto set_fetch_tap = [&](int t) {
         const int shift = TAPS > 1 ? ((t / 3 - 1) * a.w + (t % 3 - 1)) * kbytes : 0;
 #pragma unroll
@@ -275,7 +312,29 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
             else ld_cur[j] = ld_off[j] + (((ld_mask[j] >> t) & 1) ? shift : 0);
         }
     };
-    int ftap = 0, fch = 0, fetched = 0;   // chunk being fetched
+    auto set_fetch_tile = [&](uint32_t k) {   // needs the masks of tile k to be visible
+        int co0; uint32_t p0;
+        tile_origin(k, co0, p0);
+#pragma unroll
+        for (int j = 0; j < LPW; ++j) {
+            const int ii = j * NW + wave;          // wave-uniform index of the 1 KiB load
+            const int q = (ii < A_INSTR ? ii : ii - A_INSTR) * 64 + lane;   // 16-byte slot in the tile image
+            const int row = q / KCH;
+            const int piece = (q % KCH) ^ ((row >> 3) & 1);                 // swizzle, see above
+            if (ii < A_INSTR) {
+                int co = co0 + (row & ~31) + tile_row_to_channel(row & 31);
+                co = co < a.n ? co : a.n - 1;
+                ld_off[j] = static_cast<uint32_t>(co) * TAPS * kbytes + piece * 16;
+                ld_mask[j] = 0;
+            } else {
+                uint32_t pix = p0 + row;
+                pix = pix < a.pixels ? pix : a.pixels - 1;
+                ld_off[j] = pix * kbytes + piece * 16;
+                ld_mask[j] = TAPS > 1 ? s_mask[k & 1][row] : 1;
+            }
+        }
+        set_fetch_tap(0);
+    };
     auto issue_loads = [&](int stage) {
 #pragma unroll
         for (int j = 0; j < LPW; ++j) {
@@ -287,175 +346,189 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
         ++fetched;
         if (++fch == chunks_per_tap) {
             fch = 0;
-            if (++ftap < TAPS) set_fetch_tap(ftap);
+            if (++ftap < TAPS) {
+                set_fetch_tap(ftap);
+            } else {
+                ftap = 0;
+                if (++fk < my_tiles) set_fetch_tile(fk);   // the stream runs on into the next tile
+            }
         }
     };
 
-    // ---- prologue: fill NSTAGE-1 stages, then build the scale tables under their latency --------
-    set_fetch_tap(0);
+    // ---- prologue of the stream ---------------------------------------------------------------
+    build_masks(0);
+    if (my_tiles > 1) build_masks(1);
+    __syncthreads();
+    set_fetch_tile(0);
 #pragma unroll
     for (int st = 0; st < NSTAGE - 1; ++st)
-        if (fetched < total_chunks) issue_loads(st);
-
-    if constexpr (OUT != kOutI32) {
-        for (int p = tid; p < BP; p += NT) {
-            const uint32_t pix = p0 + p;
-            const int mask = s_mask[p];
-#pragma unroll
-            for (int t = 0; t < TAPS; ++t) {
-                const int delta = TAPS > 1 ? (t / 3 - 1) * a.w + (t % 3 - 1) : 0;
-                s_sx[t][p] = ((mask >> t) & 1) ? a.sx[static_cast<int64_t>(pix) + delta] * (1.0f / 256.0f) : 0.f;
-            }
-        }
-        const Out *bias = static_cast<const Out *>(a.bias);
-        for (int c = tid; c < BCO; c += NT) {
-            const int co = co0 + c;
-            s_sw[c] = co < a.n ? a.sw[co] : 0.f;
-            s_bias[c] = (co < a.n && bias) ? to_float(bias[co]) : 0.f;
-        }
-    }
+        if (fetched < stream_chunks) issue_loads(st);
+    load_scales(0);
+    store_scales(0);
     __syncthreads();   // tables visible to every wave before the first raw barrier below
 
-    v16i acc[TM][TN];
-    float facc[TAPS > 1 ? TM : 1][TAPS > 1 ? TN : 1][16];
-    if constexpr (TAPS > 1) {
-#pragma unroll
-        for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) facc[tm][tn][r] = 0.f;
-    }
-
-    // MFMAs of one K step; FIRST: the sums of a tap start from 0
-    auto multiply = [&](Ops &o, bool first) {
-        v4i a0[TM], a1[TM], b0[TN], b1[TN];
-#pragma unroll
-        for (int tm = 0; tm < TM; ++tm) { pin(o.a[tm]); expand(o.a[tm], a0[tm], a1[tm]); }
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn) { pin(o.b[tn]); expand(o.b[tn], b0[tn], b1[tn]); }
-        if (first) {
-            const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[tm], b0[tn], zero, 0, 0, 0);
-        } else {
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[tm], b0[tn], acc[tm][tn], 0, 0, 0);
-        }
-#pragma unroll
-        for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-                acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[tm], b1[tn], acc[tm][tn], 0, 0, 0);
-    };
-
-    int tap = 0, ch = 0;
     int stage = 0;
-    for (int chunk = 0; chunk < total_chunks; ++chunk) {
-        // this chunk has landed once at most the later (NSTAGE-2) chunks' loads are pending
-        if (chunk + NSTAGE - 2 < total_chunks) wait_vmem<(NSTAGE - 2) * LPW>();
-        else wait_vmem<0>();
-        __builtin_amdgcn_s_barrier();   // every wave's share has landed; the previous stage is free
-        if (fetched < total_chunks) issue_loads(stage == 0 ? NSTAGE - 1 : stage - 1);
+    uint32_t g = 0;    // position in the chunk stream
+    for (uint32_t k = 0; k < my_tiles; ++k) {
+        int co0; uint32_t p0;
+        tile_origin(k, co0, p0);
+        const int tb = k & 1;   // table set of this tile
 
-        const uint32_t sa = lds_a + stage * STAGE_BYTES, sb = lds_b + stage * STAGE_BYTES;
-        Ops op[2];
-        read_packed<TM, TN, ROWB>(op[0], sa, sb);
+        v16i acc[TM][TN];
+        float facc[TAPS > 1 ? TM : 1][TAPS > 1 ? TN : 1][16];
+        if constexpr (TAPS > 1) {
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            if (ks + 1 < KS) {
-                read_packed<TM, TN, ROWB>(op[(ks + 1) & 1], sa + (ks + 1) * 32, sb + (ks + 1) * 32);
-                wait_lds<TM + TN>();   // everything but the reads just issued
-            } else {
-                wait_lds<0>();
-            }
-            multiply(op[ks & 1], ks == 0 && ch == 0);
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) facc[tm][tn][r] = 0.f;
         }
 
-        if (++ch == chunks_per_tap) {
-            ch = 0;
-            // ---- end of a tap: fold the integer sums into the result ----------------------
-            if constexpr (OUT == kOutI32) {
-                int *yi = static_cast<int *>(a.y);
+        // MFMAs of one K step; first: the sums of a tap start from 0
+        auto multiply = [&](Ops &o, bool first) {
+            v4i a0[TM], a1[TM], b0[TN], b1[TN];
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) { pin(o.a[tm]); expand(o.a[tm], a0[tm], a1[tm]); }
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) { pin(o.b[tn]); expand(o.b[tn], b0[tn], b1[tn]); }
+            if (first) {
+                const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn)
+                        acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[tm], b0[tn], zero, 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn)
+                        acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[tm], b0[tn], acc[tm][tn], 0, 0, 0);
+            }
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[tm], b1[tn], acc[tm][tn], 0, 0, 0);
+        };
+
+        // this lane's tap masks, taken before chunk 0 lets the masks of tile k+2 into this set
+        int my_mask[TN];
+        if constexpr (OUT == kOutI32) {
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) my_mask[tn] = s_mask[tb][(wave_n * TN + tn) * 32 + lrow];
+        }
+
+        int tap = 0, ch = 0;
+        for (int chunk = 0; chunk < total_chunks; ++chunk, ++g) {
+            // this chunk has landed once at most the later (NSTAGE-2) chunks' loads are pending
+            if (g + NSTAGE - 2 < stream_chunks) wait_vmem<(NSTAGE - 2) * LPW>();
+            else wait_vmem<0>();
+            __builtin_amdgcn_s_barrier();   // every wave's share has landed; the previous stage is free
+            if (fetched < stream_chunks) issue_loads(stage == 0 ? NSTAGE - 1 : stage - 1);
+
+            // tables of the next tile, spread over this tile's first chunks: the masks of tile
+            // k+1 are already there (built one tile ahead); its scales are loaded in chunk 0
+            // and stored at the end of it; the masks of tile k+2 follow.
+            const bool tables_now = chunk == 0 && k + 1 < my_tiles;
+            if (tables_now) load_scales(k + 1);
+
+            const uint32_t sa = lds_a + stage * STAGE_BYTES, sb = lds_b + stage * STAGE_BYTES;
+            Ops op[2];
+            read_packed<TM, TN, ROWB>(op[0], sa, sb);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks + 1 < KS) {
+                    read_packed<TM, TN, ROWB>(op[(ks + 1) & 1], sa + (ks + 1) * 32, sb + (ks + 1) * 32);
+                    wait_lds<TM + TN>();   // everything but the reads just issued
+                } else {
+                    wait_lds<0>();
+                }
+                multiply(op[ks & 1], ks == 0 && ch == 0);
+            }
+
+            if (++ch == chunks_per_tap) {
+                ch = 0;
+                // ---- end of a tap: fold the integer sums into the result ----------------------
+                if constexpr (OUT == kOutI32) {
+                    int *yi = static_cast<int *>(a.y);
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn) {
+                        const int prow = (wave_n * TN + tn) * 32 + lrow;
+                        const uint32_t pix = p0 + prow;
+                        const bool inside = (my_mask[tn] >> tap) & 1;   // also false for pixels >= pixels
+#pragma unroll
+                        for (int tm = 0; tm < TM; ++tm) {
+                            const int cbase = co0 + (wave_m * TM + tm) * 32 + 16 * lhalf;
+                            if (pix < a.pixels) {
+                                int *dst = yi + (static_cast<int64_t>(pix) * TAPS + tap) * a.n + cbase;
+#pragma unroll
+                                for (int r = 0; r < 16; ++r)
+                                    if (cbase + r < a.n) dst[r] = inside ? (acc[tm][tn][r] >> 8) : 0;
+                            }
+                        }
+                    }
+                } else if constexpr (TAPS > 1) {
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn) {
+                        const float s = lds_read_f32_now(lds_sx + ((tb * TAPS + tap) * BP + tn * 32) * 4);
+#pragma unroll
+                        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r)
+                                facc[tm][tn][r] += s * static_cast<float>(acc[tm][tn][r]);
+                    }
+                }
+                ++tap;
+            }
+            if (tables_now) {
+                store_scales(k + 1);
+                if (k + 2 < my_tiles) build_masks(k + 2);   // into this tile's own set: no longer read
+            }
+            stage = stage + 1 == NSTAGE ? 0 : stage + 1;
+        }
+
+        // ---- dequantising epilogue -------------------------------------------------------------
+        if constexpr (OUT != kOutI32) {
+            Out *y = static_cast<Out *>(a.y);
+            const bool vec_ok = (a.n & 15) == 0;
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                const int clocal = (wave_m * TM + tm) * 32 + 16 * lhalf;
+                const int cbase = co0 + clocal;
+                float swv[16], bv[16];
+#pragma unroll
+                for (int r = 0; r < 16; r += 4) {
+                    const float4 s4 = *reinterpret_cast<const float4 *>(&s_sw[tb][clocal + r]);
+                    const float4 b4 = *reinterpret_cast<const float4 *>(&s_bias[tb][clocal + r]);
+                    swv[r] = s4.x; swv[r + 1] = s4.y; swv[r + 2] = s4.z; swv[r + 3] = s4.w;
+                    bv[r] = b4.x; bv[r + 1] = b4.y; bv[r + 2] = b4.z; bv[r + 3] = b4.w;
+                }
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn) {
                     const int prow = (wave_n * TN + tn) * 32 + lrow;
                     const uint32_t pix = p0 + prow;
-                    const bool inside = (s_mask[prow] >> tap) & 1;   // also false for pixels >= pixels
+                    if (pix >= a.pixels) continue;
+                    float out[16];
 #pragma unroll
-                    for (int tm = 0; tm < TM; ++tm) {
-                        const int cbase = co0 + (wave_m * TM + tm) * 32 + 16 * lhalf;
-                        if (pix < a.pixels) {
-                            int *dst = yi + (static_cast<int64_t>(pix) * TAPS + tap) * a.n + cbase;
-#pragma unroll
-                            for (int r = 0; r < 16; ++r)
-                                if (cbase + r < a.n) dst[r] = inside ? (acc[tm][tn][r] >> 8) : 0;
-                        }
+                    for (int r = 0; r < 16; ++r) {
+                        float s;
+                        if constexpr (TAPS > 1) s = facc[tm][tn][r];
+                        else s = s_sx[tb][0][prow] * static_cast<float>(acc[tm][tn][r]);
+                        out[r] = s * swv[r] + bv[r];
                     }
-                }
-            } else if constexpr (TAPS > 1) {
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn) {
-                    const float s = lds_read_f32_now(lds_sx + (tap * BP + tn * 32) * 4);
-#pragma unroll
-                    for (int tm = 0; tm < TM; ++tm)
+                    Out *dst = y + static_cast<int64_t>(pix) * a.n + cbase;
+                    if (vec_ok && cbase + 16 <= a.n) {
+                        store16(dst, out);
+                    } else {
 #pragma unroll
                         for (int r = 0; r < 16; ++r)
-                            facc[tm][tn][r] += s * static_cast<float>(acc[tm][tn][r]);
-                }
-            }
-            ++tap;
-        }
-        stage = stage + 1 == NSTAGE ? 0 : stage + 1;
-    }
-
-    // ---- dequantising epilogue -------------------------------------------------------------
-    if constexpr (OUT != kOutI32) {
-        Out *y = static_cast<Out *>(a.y);
-        const bool vec_ok = (a.n & 15) == 0;
-#pragma unroll
-        for (int tm = 0; tm < TM; ++tm) {
-            const int clocal = (wave_m * TM + tm) * 32 + 16 * lhalf;
-            const int cbase = co0 + clocal;
-            float swv[16], bv[16];
-#pragma unroll
-            for (int r = 0; r < 16; r += 4) {
-                const float4 s4 = *reinterpret_cast<const float4 *>(&s_sw[clocal + r]);
-                const float4 b4 = *reinterpret_cast<const float4 *>(&s_bias[clocal + r]);
-                swv[r] = s4.x; swv[r + 1] = s4.y; swv[r + 2] = s4.z; swv[r + 3] = s4.w;
-                bv[r] = b4.x; bv[r + 1] = b4.y; bv[r + 2] = b4.z; bv[r + 3] = b4.w;
-            }
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-                const int prow = (wave_n * TN + tn) * 32 + lrow;
-                const uint32_t pix = p0 + prow;
-                if (pix >= a.pixels) continue;
-                float out[16];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float s;
-                    if constexpr (TAPS > 1) s = facc[tm][tn][r];
-                    else s = s_sx[0][prow] * static_cast<float>(acc[tm][tn][r]);
-                    out[r] = s * swv[r] + bv[r];
-                }
-                Out *dst = y + static_cast<int64_t>(pix) * a.n + cbase;
-                if (vec_ok && cbase + 16 <= a.n) {
-                    store16(dst, out);
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (cbase + r < a.n) dst[r] = static_cast<Out>(out[r]);
+                            if (cbase + r < a.n) dst[r] = static_cast<Out>(out[r]);
+                    }
                 }
             }
         }
-    }
-    __syncthreads();   // LDS (stages and tables) is reused by the next tile
     }
 }
 
@@ -465,7 +538,7 @@ hq_status launch_tile(GemmArgs a, hipStream_t stream) {
     a.n_co_tiles = (a.n + BCO - 1) / BCO;
     const int64_t p_tiles = (static_cast<int64_t>(a.pixels) + BP - 1) / BP;
     const int64_t tiles = p_tiles * a.n_co_tiles;
-    if (tiles > 0x7fffffffLL) return HQ_ERR_SHAPE;
+    if (tiles * (a.k / 64) * TAPS > 0x7fffffffLL) return HQ_ERR_SHAPE;   // chunk-stream counters are 32 bit
     a.n_tiles = static_cast<uint32_t>(tiles);
     const int64_t slots = static_cast<int64_t>(hq::compute_units()) * OCC;   // co-resident workgroups
     const unsigned grid = static_cast<unsigned>(tiles < slots ? tiles : slots);
