@@ -11,8 +11,8 @@ resident in HBM before timing starts.
 Prints ONE JSON line.  `value` is the aggregate integer throughput of the sweep
 (2*M*N*K_total operations per layer, summed, divided by the wall time of a
 step).  `roofline` is for the dominant kernel (the 3x3 implicit-GEMM
-convolutions) from HIP-event durations taken around every launch in a second,
-instrumented pass over the same steps.  `hadamard_quant` reports the standalone
+convolutions) from HIP-event durations taken around runs of identical launches
+in a second, instrumented pass over the same kernels and buffers.  `hadamard_quant` reports the standalone
 transform+quantise kernel on the largest activation, rotating through enough
 buffers to defeat the 256 MB last-level cache.  `cpu_baseline` is the CPU oracle
 on a bounded sample of the same workload.
@@ -38,6 +38,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--eager", action="store_true", help="time the Python launch loop instead of a HIP graph replay")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1", file=sys.stderr)
@@ -85,35 +86,51 @@ def main():
 
     total_ops = sum(l.ops for l in layers)
 
+    # One step = 18 launches of 5..45 us each.  They are captured once into a HIP graph (no
+    # memset nodes: the kernels clear nothing) and the timed region replays it, so the step
+    # time is the device's, not the Python launch loop's.  --eager times the plain loop.
+    graph = None
+    if not args.eager:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+    run_step = graph.replay if graph is not None else step
+
     for _ in range(args.warmup):
-        step()
+        run_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run_step()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall / args.steps * 1e3
     value = total_ops / (wall / args.steps) / 1e12
 
-    # ---- instrumented pass: HIP events around every launch ----------------------------------
+    # ---- instrumented pass: HIP events around runs of identical launches ----------------------
+    # A single 5 us launch bracketed by its own events mostly measures the gap to the next
+    # launch, so every kernel of every layer is launched `reps` times back to back between two
+    # events on the stream the kernels run on.
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    records = []
-    for _ in range(args.steps):
-        for i, s in enumerate(state):
-            e0, e1, e2 = ev(), ev(), ev()
-            e0.record()
-            run_quant(s)
-            e1.record()
-            run_int(s)
-            e2.record()
-            records.append((i, e0, e1, e2))
-    torch.cuda.synchronize()
+    reps = max(args.steps, 20)
     quant_us = np.zeros(len(state))
     int_us = np.zeros(len(state))
-    for i, e0, e1, e2 in records:
-        quant_us[i] += e0.elapsed_time(e1) * 1e3 / args.steps
-        int_us[i] += e1.elapsed_time(e2) * 1e3 / args.steps
+    for i, s in enumerate(state):
+        for fn, out in ((run_quant, quant_us), (run_int, int_us)):
+            fn(s)
+            e0, e1 = ev(), ev()
+            e0.record()
+            for _ in range(reps):
+                fn(s)
+            e1.record()
+            torch.cuda.synchronize()
+            out[i] = e0.elapsed_time(e1) * 1e3 / reps
 
     per_layer = []
     for i, (layer, *_r) in enumerate(state):
@@ -148,15 +165,14 @@ def main():
         for j in range(len(bufs)):
             hq.hq_act_hadamard_quant(bufs[j], workloads.HAD_BLOCK, layer_b.a_bits, out=outs[j])
         torch.cuda.synchronize()
-        es = [ev() for _ in range(reps + 1)]
-        es[0].record()
+        e0, e1 = ev(), ev()
+        e0.record()
         for r in range(reps):
             j = r % len(bufs)
             hq.hq_act_hadamard_quant(bufs[j], workloads.HAD_BLOCK, layer_b.a_bits, out=outs[j])
-            es[r + 1].record()
+        e1.record()
         torch.cuda.synchronize()
-        d = [es[r].elapsed_time(es[r + 1]) * 1e3 for r in range(reps)]
-        return float(np.mean(d))
+        return e0.elapsed_time(e1) * 1e3 / reps
 
     hq_us_hbm = time_quant(xs, 8 * nrot)
     hq_us_cached = time_quant(xs[:1], 64)
@@ -171,6 +187,7 @@ def main():
             "workload": "configs[4]: LDM-4-shaped UNet layer sweep, batch 16, W4A4, fp16 I/O, "
                         "block-64 Hadamard; 9 layers, act-quant + integer conv/linear each",
             "total_gop": round(total_ops / 1e9, 2), "launches_per_step": 2 * len(state),
+            "launch": "hipgraph replay" if graph is not None else "eager",
         },
         "frac_int8_mfma_peak_wall": round(value / INT8_MFMA_PEAK_TOPS, 4),
         "int_stage_tops_kernel_time": round(int_all_tops, 1),
@@ -198,14 +215,14 @@ def main():
 
 
 def cpu_baseline(layers):
-    """The oracle, as it stands, on the first 2 images of each layer of the sweep."""
+    """The oracle, as it stands, on the first 8 of the 16 images of each layer of the sweep."""
     import numpy as np
 
     import oracle
     import workloads
 
     oracle.build()
-    take = 2
+    take = 8
     ops = 0
     prepared = []
     for layer in layers:

@@ -221,6 +221,127 @@ __global__ __launch_bounds__(kThreads) void rowquant_large(const T *__restrict__
     if (tid == 0) scale[blockIdx.x] = amax > 0.f ? (amax * a.norm) / a.qmax : 1.0f;
 }
 
+// ---- fp16 input, block 64: the transform on the matrix cores ---------------------------------
+//
+// For the streaming activation path the butterfly above is bound by vector-ALU work
+// (about 14 instructions per element), not by HBM.  Here the same product x * H64 is
+// evaluated as an MFMA: out^T = H^T x^T with H (entries +-1, exact in fp16) as the "A"
+// operand and 32 tokens as the columns of "B", accumulated in fp32; the products are exact,
+// so only the summation order differs from the butterfly.  A lane owns one token
+// (column lane%32); the rows of H are permuted so that the 32 results a lane holds per block
+// are 32 consecutive channels, i.e. 16 contiguous packed bytes.  The B operand of a
+// 32x32x16 MFMA is 8 consecutive fp16 of a token row, i.e. exactly one 16-byte global load,
+// so the activations go from HBM to the matrix core without touching LDS.
+//
+// Quantisation: m = fma(v, qmax / amax, 1.5 * 2^23 + 8) rounds v * inv to the nearest
+// integer (ties to even, one rounding) and leaves code + 8 (1..15) in the low nibble of the
+// float's bit pattern.  Eight such patterns are merged by w = (w << 4) + m; the known
+// constant contributed by the upper bits is subtracted and the offset removed by
+// xor 0x88888888, which yields the eight two's-complement nibbles.
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr float kMagic = 12582920.0f;                                 // 1.5 * 2^23 + 8
+constexpr uint32_t kMagicSum = 0x4B400000u * 0x11111111u;             // sum_i 0x4B400000 << 4i (mod 2^32)
+
+// Channel (inside a 64-block) produced by row i of H tile mt: lane half h = (i>>2)&1 ends up
+// with the consecutive channels 32h + 16mt + (0..15) in its 16 result registers.
+__device__ __forceinline__ int h_row_channel(int mt, int i) {
+    return 32 * ((i >> 2) & 1) + 16 * mt + 4 * (i >> 3) + (i & 3);
+}
+
+__device__ __forceinline__ uint32_t pack8_magic(const float *v, float inv) {
+    uint32_t w = __float_as_uint(__builtin_fmaf(v[7], inv, kMagic));
+#pragma unroll
+    for (int i = 6; i >= 0; --i) w = (w << 4) + __float_as_uint(__builtin_fmaf(v[i], inv, kMagic));
+    return (w - kMagicSum) ^ 0x88888888u;
+}
+
+// NB = k / 64 blocks per token, all held in registers (k <= 384).
+template <int NB>
+__global__ __launch_bounds__(256) void hadamard64_quant_f16(const __half *__restrict__ x, int64_t m,
+                                                            float qmax, uint8_t *__restrict__ xq,
+                                                            float *__restrict__ scale) {
+    constexpr int K = 64 * NB;
+    __shared__ uint4 s_h[8][64];   // MFMA "A" operands of H: [tile mt * 4 + k slice][lane]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int idx = tid; idx < 512; idx += 256) {
+        const int combo = idx >> 6, ln = idx & 63;
+        const int c = h_row_channel(combo >> 2, ln & 31);
+        const int k0 = 16 * (combo & 3) + 8 * (ln >> 5);
+        uint32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t s0 = __popc(c & (k0 + 2 * e)) & 1, s1 = __popc(c & (k0 + 2 * e + 1)) & 1;
+            w[e] = 0x3C003C00u ^ (s0 << 15) ^ (s1 << 31);   // +-1.0 in fp16, Sylvester sign (-1)^popcount(c & k)
+        }
+        s_h[combo][ln] = uint4{w[0], w[1], w[2], w[3]};
+    }
+    __syncthreads();
+    v8h hmat[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) hmat[i] = __builtin_bit_cast(v8h, s_h[i][lane]);
+
+    const int col = lane & 31, half = lane >> 5;
+    const int64_t wave_stride = static_cast<int64_t>(gridDim.x) * 4 * 32;
+    for (int64_t t0 = (static_cast<int64_t>(blockIdx.x) * 4 + wave) * 32; t0 < m; t0 += wave_stride) {
+        const int64_t token = t0 + col;
+        const bool valid = token < m;
+        const __half *row = x + (valid ? token : m - 1) * K + 8 * half;
+        v8h b[NB][4];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                b[nb][ks] = *reinterpret_cast<const v8h *>(row + 64 * nb + 16 * ks);
+
+        v16f o[NB][2];
+        float amax = 0.f;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+                v16f acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(hmat[mt * 4 + ks], b[nb][ks], acc, 0, 0, 0);
+                o[nb][mt] = acc;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) amax = fmaxf(amax, fabsf(acc[r]));
+            }
+        amax = fmaxf(amax, __shfl_xor(amax, 32));   // the token's other 32 channels of every block
+        const float inv = amax > 0.f ? qmax / amax : 0.f;
+        if (valid) {
+            if (half == 0) scale[token] = amax > 0.f ? (amax * 0.125f) / qmax : 1.0f;
+            uint8_t *dst = xq + token * (K / 2) + 16 * half;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                float v[32];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) { v[r] = o[nb][0][r]; v[16 + r] = o[nb][1][r]; }
+                uint4 w;
+                w.x = pack8_magic(v, inv);
+                w.y = pack8_magic(v + 8, inv);
+                w.z = pack8_magic(v + 16, inv);
+                w.w = pack8_magic(v + 24, inv);
+                *reinterpret_cast<uint4 *>(dst + 32 * nb) = w;
+            }
+        }
+    }
+}
+
+template <int NB>
+hq_status launch_hadamard64(const __half *x, int64_t m, int bits, uint8_t *xq, float *scale, hipStream_t stream) {
+    const float qmax = static_cast<float>((1 << (bits - 1)) - 1);
+    const int64_t waves = (m + 31) / 32;
+    int64_t grid = (waves + 3) / 4;
+    const int64_t cap = static_cast<int64_t>(hq::compute_units()) * 8;
+    if (grid > cap) grid = cap;
+    hipLaunchKernelGGL((hadamard64_quant_f16<NB>), dim3(static_cast<unsigned>(grid)), dim3(256), 0, stream, x, m,
+                       qmax, xq, scale);
+    return hq::launch_status();
+}
+
 template <typename T, int LOGB>
 hq_status launch_rowquant(const T *x, int64_t m, int row_len, int bits, uint32_t *xq, float *scale,
                           hipStream_t stream) {
@@ -295,6 +416,17 @@ extern "C" hq_status hq_act_hadamard_quant(const void *x, hq_dtype x_dtype, int6
     if (st != HQ_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint32_t *out = reinterpret_cast<uint32_t *>(xq);
+    if (x_dtype == HQ_F16 && had_block == 64 && k <= 384) {
+        const __half *xh = static_cast<const __half *>(x);
+        switch (k / 64) {
+            case 1: return launch_hadamard64<1>(xh, m, a_bits, xq, x_scale, s);
+            case 2: return launch_hadamard64<2>(xh, m, a_bits, xq, x_scale, s);
+            case 3: return launch_hadamard64<3>(xh, m, a_bits, xq, x_scale, s);
+            case 4: return launch_hadamard64<4>(xh, m, a_bits, xq, x_scale, s);
+            case 5: return launch_hadamard64<5>(xh, m, a_bits, xq, x_scale, s);
+            case 6: return launch_hadamard64<6>(xh, m, a_bits, xq, x_scale, s);
+        }
+    }
     if (x_dtype == HQ_F16)
         return dispatch_block(static_cast<const __half *>(x), m, k, had_block, a_bits, out, x_scale, s);
     return dispatch_block(static_cast<const float *>(x), m, k, had_block, a_bits, out, x_scale, s);

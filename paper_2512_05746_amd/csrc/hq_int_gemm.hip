@@ -209,8 +209,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     static_assert(KCH % 2 == 0, "a 64-code K step is two pieces");
     static_assert((BCO * KCH) % 64 == 0 && (BP * KCH) % 64 == 0, "whole wave-wide loads only");
     constexpr int A_INSTR = BCO * KCH / 64, B_INSTR = BP * KCH / 64;   // 1 KiB loads per chunk
-    static_assert((A_INSTR + B_INSTR) % NW == 0, "loads must split evenly over the waves");
-    constexpr int LPW = (A_INSTR + B_INSTR) / NW;
+    // every wave issues the same number of loads (the hand-placed wait counts rely on it); if
+    // the loads do not split evenly, the surplus slots repeat an earlier load (same bytes, same
+    // destination)
+    constexpr int NI = A_INSTR + B_INSTR;
+    constexpr int LPW = (NI + NW - 1) / NW;
     static_assert((NSTAGE - 2) * LPW < 64, "vmcnt range");
     static_assert(TM + TN < 16, "lgkmcnt range");
     static_assert(BP <= NT && BCO <= NT, "one table entry per thread");
@@ -308,7 +311,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
         const int shift = TAPS > 1 ? ((t / 3 - 1) * a.w + (t % 3 - 1)) * kbytes : 0;
 #pragma unroll
         for (int j = 0; j < LPW; ++j) {
-            if (j * NW + wave < A_INSTR) ld_cur[j] = ld_off[j] + t * kbytes;
+            if ((j * NW + wave) % NI < A_INSTR) ld_cur[j] = ld_off[j] + t * kbytes;
             else ld_cur[j] = ld_off[j] + (((ld_mask[j] >> t) & 1) ? shift : 0);
         }
     };
@@ -317,7 +320,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
         tile_origin(k, co0, p0);
 #pragma unroll
         for (int j = 0; j < LPW; ++j) {
-            const int ii = j * NW + wave;          // wave-uniform index of the 1 KiB load
+            const int ii = (j * NW + wave) % NI;   // wave-uniform index of the 1 KiB load
             const int q = (ii < A_INSTR ? ii : ii - A_INSTR) * 64 + lane;   // 16-byte slot in the tile image
             const int row = q / KCH;
             const int piece = (q % KCH) ^ ((row >> 3) & 1);                 // swizzle, see above
@@ -338,7 +341,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     auto issue_loads = [&](int stage) {
 #pragma unroll
         for (int j = 0; j < LPW; ++j) {
-            const int ii = j * NW + wave;
+            const int ii = (j * NW + wave) % NI;
             const uint8_t *base = (ii < A_INSTR ? a.wq : a.xq) + fch * ROWB;
             // stage image: A rows then B rows, each wave-wide load fills the next 1 KiB
             load_to_lds16(base + ld_cur[j], lds + stage * STAGE_BYTES + ii * 1024);
@@ -550,6 +553,9 @@ hq_status launch_tile(GemmArgs a, hipStream_t stream) {
 template <int TAPS, int OUT>
 hq_status launch_shape(const GemmArgs &a, hipStream_t stream) {
     // chunks of 192 codes (96 contiguous bytes per row) whenever the channel count allows
+#ifdef HQ_TUNE_WIDE
+    if (a.k % 192 == 0) return launch_tile<2, 2, 1, 4, TAPS, OUT, 6, 2, 2>(a, stream);
+#endif
     if (a.k % 192 == 0) return launch_tile<2, 2, 2, 2, TAPS, OUT, 6, 2, 2>(a, stream);
     return launch_tile<2, 2, 2, 2, TAPS, OUT, 2, 4, 2>(a, stream);
 }

@@ -210,3 +210,38 @@ def test_errors_raise(hq):
         hq.hq_act_hadamard_quant(x, 64, 4)
     with pytest.raises(hq.HqError):
         hq.hq_act_hadamard_quant(x[:, :64].contiguous(), 64, 8)
+
+
+def test_hip_graph_replay_matches_eager(hq):
+    """The whole layer captured into a HIP graph: every replay (with eager work and
+    synchronisations in between) must reproduce the eager result bit for bit."""
+    layer = workloads.tiny_layers()[4]
+    x = dev(workloads.make_x(layer))
+    wq, sw = hq.hq_quantize_weights(dev(workloads.make_w(layer)), 64, 4)
+    xq = torch.empty(x.shape[:-1] + (layer.k_in // 2,), dtype=torch.uint8, device="cuda")
+    sx = torch.empty(x.shape[:-1], dtype=torch.float32, device="cuda")
+    y = torch.empty(x.shape[:-1] + (layer.n_out,), dtype=torch.float16, device="cuda")
+
+    def run():
+        hq.hq_act_hadamard_quant(x, 64, 4, out=(xq, sx))
+        hq.hq_int_conv2d(xq, sx, wq, sw, None, ksize=3, y_dtype=torch.float16, out=y)
+
+    run()
+    want = host(y).copy()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for i in range(4):
+        y.zero_()
+        xq.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        assert np.array_equal(host(y).view(np.uint16), want.view(np.uint16)), "replay %d" % i
+        run()   # eager work between replays
+        torch.cuda.synchronize()
