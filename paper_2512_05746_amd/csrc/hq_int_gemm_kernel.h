@@ -1,0 +1,584 @@
+// Integer GEMM / implicit-GEMM NHWC convolution on int8 MFMA with a dequantising
+// epilogue (gfx950).  Method, linear-layer and "Convolution" equations: an
+// integer product of the quantised operands, then the product of scales.
+//
+// Orientation.  The MFMA "A" operand (rows of the result tile) is the weight
+// tile, the "B" operand (columns) is the activation tile.  In the 32x32 result
+// layout a lane then owns ONE pixel (column lane%32) and 16 output channels, so
+// the per-pixel activation scale of a tap is a single per-lane register and the
+// 16 channels of a lane are contiguous in the NHWC output.
+//
+// Nibble handling.  Codes stay packed (two per byte) in HBM and in LDS; the copy
+// from global memory to LDS is a direct-to-LDS load that touches no register.
+// A wave expands the packed operands it has read from LDS in registers: a packed
+// dword w becomes the two int8x4 vectors
+//     lo = (w << 4) & 0xF0F0F0F0,   hi = w & 0xF0F0F0F0,
+// each byte holding 16 * code exactly (two's complement).  Both operands are
+// fed that way, so the MFMA accumulates 256 * sum(xq * wq); the factor is exact
+// and is removed by an arithmetic shift (int32 output) or folded into the
+// activation scale (floating-point output).  The order in which the codes of a
+// 64-wide K step reach the MFMA lanes is a permutation applied identically to
+// both operands, which leaves the sum unchanged.
+//
+// Why packed in LDS: measured on MI355X, LDS accepts writes at about 64 bytes per
+// clock per CU (reads: about 256), and one 32x32x32 int8 MFMA leaves issue room
+// for about seven other vector instructions.  Expanding to int8 before LDS
+// doubles the LDS write volume and made that the bound; expanding after the read
+// costs three vector instructions per packed dword instead.  The accumulators
+// are never cleared by moves: the first MFMA of a tap takes the constant 0 as
+// its addend.
+#pragma once
+#include <hip/hip_fp16.h>
+
+#include "hq_common.h"
+
+struct GemmArgs {
+    const uint8_t *xq;   // [pixels, k/2]
+    const float *sx;     // [pixels]
+    const uint8_t *wq;   // [n, taps, k/2]
+    const float *sw;     // [n]
+    const void *bias;    // [n] of the output dtype, or null
+    void *y;
+    uint32_t pixels;     // rows of the activation matrix (= nb*h*w for a convolution)
+    int n;               // output channels
+    int k;               // input channels (codes per tap)
+    int h, w;            // image size (convolution only)
+    int n_co_tiles;
+    uint32_t n_tiles;    // pixel tiles * channel tiles
+};
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kOutF16 = 0, kOutF32 = 1, kOutI32 = 2;
+
+
+// Output channel handled by row i of a 32-row MFMA tile.  Chosen so that the
+// 16 results of a lane (rows 8*(r/4) + 4*(lane/32) + r%4, r = 0..15) are the
+// consecutive channels 16*(lane/32) + r.
+__device__ __forceinline__ int tile_row_to_channel(int i) {
+    return 16 * ((i >> 2) & 1) + 4 * (i >> 3) + (i & 3);
+}
+
+// 16 packed bytes (32 codes) -> two 16-byte units of int8 (16 * code each)
+__device__ __forceinline__ void expand(const v4i &p, v4i &first, v4i &second) {
+    const int m = static_cast<int>(0xF0F0F0F0u);
+    first = v4i{(p.x << 4) & m, p.x & m, (p.y << 4) & m, p.y & m};
+    second = v4i{(p.z << 4) & m, p.z & m, (p.w << 4) & m, p.w & m};
+}
+
+// Waits until at most N of this wave's vector-memory operations are outstanding.
+template <int N>
+__device__ __forceinline__ void wait_vmem() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);
+}
+
+// Waits until at most N of this wave's LDS / scalar-memory operations are outstanding.
+template <int N>
+__device__ __forceinline__ void wait_lds() {
+    static_assert(N >= 0 && N < 16, "lgkmcnt is a 4-bit counter");
+    __builtin_amdgcn_s_waitcnt(0xC07F | (N << 8));
+}
+
+// Direct-to-LDS load: lane i's 16 bytes land at lds_wave_base + 16 * i (the LDS base is
+// wave-uniform).  Completion is tracked by vmcnt only.
+__device__ __forceinline__ void load_to_lds16(const uint8_t *src, uint8_t *lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+
+// LDS reads of the DMA-filled stages are inline asm: the compiler cannot tell which
+// stage a direct-to-LDS load targets and would drain every outstanding load (vmcnt(0))
+// before each LDS read it knows of, which serialises the pipeline.  The waits these
+// reads need (wait_lds) and the register pinning after them are placed by hand.
+__device__ __forceinline__ uint32_t lds_address(const void *p) {
+    return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((const __attribute__((address_space(3))) void *)p));
+}
+
+template <int OFFSET>
+__device__ __forceinline__ void lds_read16(v4i &dst, uint32_t addr) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFFSET) : "memory");
+}
+
+__device__ __forceinline__ float lds_read_f32_now(uint32_t addr) {
+    float r;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(r) : "v"(addr) : "memory");
+    return r;
+}
+
+// Ties a register to the point after the preceding hand-placed wait.
+__device__ __forceinline__ void pin(v4i &v) { asm volatile("" : "+v"(v)); }
+
+// Bit t set: tap t = (r, s) of a 3x3 / pad 1 window around pixel `pix` lies inside its image.
+template <int TAPS>
+__device__ __forceinline__ int tap_mask(uint32_t pix, int h, int w) {
+    if constexpr (TAPS == 1) {
+        return 1;
+    } else {
+        const uint32_t q = pix / static_cast<uint32_t>(w);
+        const int ow = static_cast<int>(pix - q * w);
+        const int oh = static_cast<int>(q % static_cast<uint32_t>(h));
+        int mask = 0;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const int ih = oh + t / 3 - 1, iw = ow + t % 3 - 1;
+            mask |= (ih >= 0 && ih < h && iw >= 0 && iw < w) ? (1 << t) : 0;
+        }
+        return mask;
+    }
+}
+
+// Packed MFMA operands of one 64-code K step, as read from LDS.
+template <int TM, int TN>
+struct Packed {
+    v4i a[TM];
+    v4i b[TN];
+};
+
+template <int TM, int TN, int ROWB, int I = 0>
+__device__ __forceinline__ void read_packed(Packed<TM, TN> &o, uint32_t addr_a, uint32_t addr_b) {
+    if constexpr (I < TM) {
+        lds_read16<I * 32 * ROWB>(o.a[I], addr_a);
+        read_packed<TM, TN, ROWB, I + 1>(o, addr_a, addr_b);
+    } else if constexpr (I < TM + TN) {
+        lds_read16<(I - TM) * 32 * ROWB>(o.b[I - TM], addr_b);
+        read_packed<TM, TN, ROWB, I + 1>(o, addr_a, addr_b);
+    }
+}
+
+template <int OUT> struct OutT;
+template <> struct OutT<kOutF16> { using type = __half; };
+template <> struct OutT<kOutF32> { using type = float; };
+template <> struct OutT<kOutI32> { using type = int; };
+
+__device__ __forceinline__ float to_float(__half v) { return __half2float(v); }
+__device__ __forceinline__ float to_float(float v) { return v; }
+
+__device__ __forceinline__ void store16(__half *dst, const float (&v)[16]) {
+    uint4 lo, hi;
+    __half2 *pl = reinterpret_cast<__half2 *>(&lo);
+    __half2 *ph = reinterpret_cast<__half2 *>(&hi);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        pl[i] = __floats2half2_rn(v[2 * i], v[2 * i + 1]);
+        ph[i] = __floats2half2_rn(v[8 + 2 * i], v[8 + 2 * i + 1]);
+    }
+    reinterpret_cast<uint4 *>(dst)[0] = lo;
+    reinterpret_cast<uint4 *>(dst)[1] = hi;
+}
+
+__device__ __forceinline__ void store16(float *dst, const float (&v)[16]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        reinterpret_cast<float4 *>(dst)[i] = float4{v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]};
+}
+
+// TM x TN MFMA tiles of 32x32 per wave, WAVES_M x WAVES_N waves per workgroup.
+// TAPS = 1 (linear / 1x1) or 9 (3x3, stride 1, pad 1).
+//
+// Persistent workgroups: the grid is sized to the machine and every workgroup
+// walks its tiles (grid stride; output-channel tiles of one pixel tile are
+// adjacent).  All chunks of all its tiles form ONE stream through the LDS
+// stages, so the loads of the next tile's first chunks are in flight while the
+// current tile is finished and written out, and the scale tables of the next
+// tile are built during the current one (two table sets).
+//
+// K is consumed in chunks of KCH 16-byte pieces per row (KCH * 32 codes); NSTAGE
+// chunks of both operands live in LDS, filled by direct-to-LDS loads issued
+// NSTAGE-1 chunks ahead of the MFMAs; one barrier per chunk.  Inside a wave-wide
+// load, KCH consecutive lanes fetch one row's contiguous KCH*16 bytes and
+// consecutive lane groups fetch consecutive rows, so a load of activation rows
+// reads one contiguous KiB.  The LDS image of a stage is row-major
+// [row][KCH*16 bytes]; in rows 8..15 (mod 16) adjacent pieces are swapped, which
+// makes the 16-byte operand reads of 16 consecutive rows hit 16 different bank
+// groups.  Inside a chunk the packed operands of K step k+1 are read from LDS
+// while the MFMAs of step k run.
+//
+// Rows that do not exist (channels >= n, pixels >= pixels, taps outside the
+// image) are loaded from a clamped in-bounds address instead of being zeroed:
+// their sums are never stored, and a tap outside the image has scale 0.
+template <int TM, int TN, int WAVES_M, int WAVES_N, int TAPS, int OUT, int KCH, int NSTAGE, int OCC>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(GemmArgs a) {
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int NT = 64 * NW;
+    constexpr int BCO = 32 * TM * WAVES_M;   // output channels per workgroup
+    constexpr int BP = 32 * TN * WAVES_N;    // pixels per workgroup
+    constexpr int ROWB = KCH * 16;           // bytes per row per chunk
+    constexpr int KS = KCH / 2;              // 64-code K steps per chunk
+    static_assert(KCH % 2 == 0, "a 64-code K step is two pieces");
+    static_assert((BCO * KCH) % 64 == 0 && (BP * KCH) % 64 == 0, "whole wave-wide loads only");
+    constexpr int A_INSTR = BCO * KCH / 64, B_INSTR = BP * KCH / 64;   // 1 KiB loads per chunk
+    // every wave issues the same number of loads (the hand-placed wait counts rely on it); if
+    // the loads do not split evenly, the surplus slots repeat an earlier load (same bytes, same
+    // destination)
+    constexpr int NI = A_INSTR + B_INSTR;
+    constexpr int LPW = (NI + NW - 1) / NW;
+    static_assert((NSTAGE - 2) * LPW < 64, "vmcnt range");
+    static_assert(TM + TN < 16, "lgkmcnt range");
+    static_assert(BP <= NT && BCO <= NT, "one table entry per thread");
+    constexpr int STAGE_BYTES = (BCO + BP) * ROWB;
+    constexpr int SX_PER_T = (TAPS * BP + NT - 1) / NT;   // scale-table entries per thread
+    using Out = typename OutT<OUT>::type;
+    using Ops = Packed<TM, TN>;
+
+    // [stage][operand][row][ROWB bytes]
+    __shared__ __attribute__((aligned(16))) uint8_t lds[NSTAGE * STAGE_BYTES];
+    // two sets of per-tile tables: the set of tile k+1 is built while tile k is multiplied
+    __shared__ float s_sx[2][TAPS][BP];   // x_scale / 256 of the input pixel under tap t; 0 outside
+    __shared__ int s_mask[2][BP];         // bit t: tap t of this output pixel is inside the image
+    __shared__ __attribute__((aligned(16))) float s_sw[2][BCO];     // w_scale of the tile's channels
+    __shared__ __attribute__((aligned(16))) float s_bias[2][BCO];   // bias (0 if absent)
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+
+    const int kbytes = a.k >> 1;                 // packed bytes per (row, tap)
+    const int chunks_per_tap = kbytes / ROWB;    // host guarantees divisibility
+    const int total_chunks = TAPS * chunks_per_tap;
+    const uint32_t lds_a = lds_address(lds) + (wave_m * TM * 32 + lrow) * ROWB + (lhalf ^ ((lrow >> 3) & 1)) * 16;
+    const uint32_t lds_b = lds_a + (BCO + (wave_n * TN - wave_m * TM) * 32) * ROWB;
+    const uint32_t lds_sx = lds_address(&s_sx[0][0][0]) + (wave_n * TN * 32 + lrow) * 4;
+
+    if (blockIdx.x >= a.n_tiles) return;
+    const uint32_t my_tiles = (a.n_tiles - blockIdx.x + gridDim.x - 1) / gridDim.x;
+    const uint32_t stream_chunks = my_tiles * total_chunks;   // < 2^31, checked on the host
+    auto tile_origin = [&](uint32_t k, int &co0, uint32_t &p0) {
+        const uint32_t tile = blockIdx.x + k * gridDim.x;
+        co0 = static_cast<int>(tile % a.n_co_tiles) * BCO;
+        p0 = (tile / a.n_co_tiles) * BP;
+    };
+
+    // ---- per-tile tables ---------------------------------------------------------------------
+    auto build_masks = [&](uint32_t k) {   // no memory reads
+        int co0; uint32_t p0;
+        tile_origin(k, co0, p0);
+        if (tid < BP) {
+            const uint32_t pix = p0 + tid;
+            s_mask[k & 1][tid] = pix < a.pixels ? tap_mask<TAPS>(pix, a.h, a.w) : 0;
+        }
+    };
+    float t_sx[SX_PER_T], t_sw = 0.f, t_bias = 0.f;
+    auto load_scales = [&](uint32_t k) {   // needs the masks of tile k to be visible
+        if constexpr (OUT != kOutI32) {
+            int co0; uint32_t p0;
+            tile_origin(k, co0, p0);
+#pragma unroll
+            for (int j = 0; j < SX_PER_T; ++j) {
+                const int e = tid + j * NT;
+                const int t = e / BP, p = e % BP;
+                t_sx[j] = 0.f;
+                if (e < TAPS * BP && ((s_mask[k & 1][p] >> t) & 1)) {
+                    const int delta = TAPS > 1 ? (t / 3 - 1) * a.w + (t % 3 - 1) : 0;
+                    t_sx[j] = a.sx[static_cast<int64_t>(p0 + p) + delta];
+                }
+            }
+            if (tid < BCO && co0 + tid < a.n) {
+                t_sw = a.sw[co0 + tid];
+                const Out *bias = static_cast<const Out *>(a.bias);
+                t_bias = bias ? to_float(bias[co0 + tid]) : 0.f;
+            } else {
+                t_sw = 0.f;
+                t_bias = 0.f;
+            }
+        }
+    };
+    auto store_scales = [&](uint32_t k) {
+        if constexpr (OUT != kOutI32) {
+#pragma unroll
+            for (int j = 0; j < SX_PER_T; ++j) {
+                const int e = tid + j * NT;
+                if (e < TAPS * BP) (&s_sx[k & 1][0][0])[e] = t_sx[j] * (1.0f / 256.0f);
+            }
+            if (tid < BCO) {
+                s_sw[k & 1][tid] = t_sw;
+                s_bias[k & 1][tid] = t_bias;
+            }
+        }
+    };
+
+    // ---- this wave's share of the direct-to-LDS loads -------------------------------------------
+    uint32_t ld_off[LPW];     // byte offset of this lane's piece at tap 0, chunk 0 of the tile being fetched
+    int ld_mask[LPW];         // activation rows: taps inside the image
+    uint32_t ld_cur[LPW];     // ld_off + the term of the tap being fetched
+    uint32_t fk = 0;          // tile (index in this workgroup's list) being fetched
+    int ftap = 0, fch = 0;
+    uint32_t fetched = 0;     // chunks of the stream requested so far
+    auto set_fetch_tap = [&](int t) {
+        const int shift = TAPS > 1 ? ((t / 3 - 1) * a.w + (t % 3 - 1)) * kbytes : 0;
+#pragma unroll
+        for (int j = 0; j < LPW; ++j) {
+            if ((j * NW + wave) % NI < A_INSTR) ld_cur[j] = ld_off[j] + t * kbytes;
+            else ld_cur[j] = ld_off[j] + (((ld_mask[j] >> t) & 1) ? shift : 0);
+        }
+    };
+    auto set_fetch_tile = [&](uint32_t k) {   // needs the masks of tile k to be visible
+        int co0; uint32_t p0;
+        tile_origin(k, co0, p0);
+#pragma unroll
+        for (int j = 0; j < LPW; ++j) {
+            const int ii = (j * NW + wave) % NI;   // wave-uniform index of the 1 KiB load
+            const int q = (ii < A_INSTR ? ii : ii - A_INSTR) * 64 + lane;   // 16-byte slot in the tile image
+            const int row = q / KCH;
+            const int piece = (q % KCH) ^ ((row >> 3) & 1);                 // swizzle, see above
+            if (ii < A_INSTR) {
+                int co = co0 + (row & ~31) + tile_row_to_channel(row & 31);
+                co = co < a.n ? co : a.n - 1;
+                ld_off[j] = static_cast<uint32_t>(co) * TAPS * kbytes + piece * 16;
+                ld_mask[j] = 0;
+            } else {
+                uint32_t pix = p0 + row;
+                pix = pix < a.pixels ? pix : a.pixels - 1;
+                ld_off[j] = pix * kbytes + piece * 16;
+                ld_mask[j] = TAPS > 1 ? s_mask[k & 1][row] : 1;
+            }
+        }
+        set_fetch_tap(0);
+    };
+    auto issue_loads = [&](int stage) {
+#pragma unroll
+        for (int j = 0; j < LPW; ++j) {
+            const int ii = (j * NW + wave) % NI;
+            const uint8_t *base = (ii < A_INSTR ? a.wq : a.xq) + fch * ROWB;
+            // stage image: A rows then B rows, each wave-wide load fills the next 1 KiB
+            load_to_lds16(base + ld_cur[j], lds + stage * STAGE_BYTES + ii * 1024);
+        }
+        ++fetched;
+        if (++fch == chunks_per_tap) {
+            fch = 0;
+            if (++ftap < TAPS) {
+                set_fetch_tap(ftap);
+            } else {
+                ftap = 0;
+                if (++fk < my_tiles) set_fetch_tile(fk);   // the stream runs on into the next tile
+            }
+        }
+    };
+
+    // ---- prologue of the stream ---------------------------------------------------------------
+    build_masks(0);
+    if (my_tiles > 1) build_masks(1);
+    __syncthreads();
+    set_fetch_tile(0);
+#pragma unroll
+    for (int st = 0; st < NSTAGE - 1; ++st)
+        if (fetched < stream_chunks) issue_loads(st);
+    load_scales(0);
+    store_scales(0);
+    __syncthreads();   // tables visible to every wave before the first raw barrier below
+
+    int stage = 0;
+    uint32_t g = 0;    // position in the chunk stream
+    for (uint32_t k = 0; k < my_tiles; ++k) {
+        int co0; uint32_t p0;
+        tile_origin(k, co0, p0);
+        const int tb = k & 1;   // table set of this tile
+
+        v16i acc[TM][TN];
+        float facc[TAPS > 1 ? TM : 1][TAPS > 1 ? TN : 1][16];
+        if constexpr (TAPS > 1) {
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) facc[tm][tn][r] = 0.f;
+        }
+
+        // MFMAs of one K step; first: the sums of a tap start from 0
+        auto multiply = [&](Ops &o, bool first) {
+            v4i a0[TM], a1[TM], b0[TN], b1[TN];
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) { pin(o.a[tm]); expand(o.a[tm], a0[tm], a1[tm]); }
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) { pin(o.b[tn]); expand(o.b[tn], b0[tn], b1[tn]); }
+            if (first) {
+                const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn)
+                        acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[tm], b0[tn], zero, 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn)
+                        acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[tm], b0[tn], acc[tm][tn], 0, 0, 0);
+            }
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[tm], b1[tn], acc[tm][tn], 0, 0, 0);
+        };
+
+        // this lane's tap masks, taken before chunk 0 lets the masks of tile k+2 into this set
+        int my_mask[TN];
+        if constexpr (OUT == kOutI32) {
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) my_mask[tn] = s_mask[tb][(wave_n * TN + tn) * 32 + lrow];
+        }
+
+        int tap = 0, ch = 0;
+        for (int chunk = 0; chunk < total_chunks; ++chunk, ++g) {
+            // this chunk has landed once at most the later (NSTAGE-2) chunks' loads are pending
+            if (g + NSTAGE - 2 < stream_chunks) wait_vmem<(NSTAGE - 2) * LPW>();
+            else wait_vmem<0>();
+            __builtin_amdgcn_s_barrier();   // every wave's share has landed; the previous stage is free
+            if (fetched < stream_chunks) issue_loads(stage == 0 ? NSTAGE - 1 : stage - 1);
+
+            // tables of the next tile, spread over this tile's first chunks: the masks of tile
+            // k+1 are already there (built one tile ahead); its scales are loaded in chunk 0
+            // and stored at the end of it; the masks of tile k+2 follow.
+            const bool tables_now = chunk == 0 && k + 1 < my_tiles;
+            if (tables_now) load_scales(k + 1);
+
+            const uint32_t sa = lds_a + stage * STAGE_BYTES, sb = lds_b + stage * STAGE_BYTES;
+            Ops op[2];
+            read_packed<TM, TN, ROWB>(op[0], sa, sb);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks + 1 < KS) {
+                    read_packed<TM, TN, ROWB>(op[(ks + 1) & 1], sa + (ks + 1) * 32, sb + (ks + 1) * 32);
+                    wait_lds<TM + TN>();   // everything but the reads just issued
+                } else {
+                    wait_lds<0>();
+                }
+                multiply(op[ks & 1], ks == 0 && ch == 0);
+            }
+
+            if (++ch == chunks_per_tap) {
+                ch = 0;
+                // ---- end of a tap: fold the integer sums into the result ----------------------
+                if constexpr (OUT == kOutI32) {
+                    int *yi = static_cast<int *>(a.y);
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn) {
+                        const int prow = (wave_n * TN + tn) * 32 + lrow;
+                        const uint32_t pix = p0 + prow;
+                        const bool inside = (my_mask[tn] >> tap) & 1;   // also false for pixels >= pixels
+#pragma unroll
+                        for (int tm = 0; tm < TM; ++tm) {
+                            const int cbase = co0 + (wave_m * TM + tm) * 32 + 16 * lhalf;
+                            if (pix < a.pixels) {
+                                int *dst = yi + (static_cast<int64_t>(pix) * TAPS + tap) * a.n + cbase;
+#pragma unroll
+                                for (int r = 0; r < 16; ++r)
+                                    if (cbase + r < a.n) dst[r] = inside ? (acc[tm][tn][r] >> 8) : 0;
+                            }
+                        }
+                    }
+                } else if constexpr (TAPS > 1) {
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn) {
+                        const float s = lds_read_f32_now(lds_sx + ((tb * TAPS + tap) * BP + tn * 32) * 4);
+#pragma unroll
+                        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r)
+                                facc[tm][tn][r] += s * static_cast<float>(acc[tm][tn][r]);
+                    }
+                }
+                ++tap;
+            }
+            if (tables_now) {
+                store_scales(k + 1);
+                if (k + 2 < my_tiles) build_masks(k + 2);   // into this tile's own set: no longer read
+            }
+            stage = stage + 1 == NSTAGE ? 0 : stage + 1;
+        }
+
+        // ---- dequantising epilogue -------------------------------------------------------------
+        if constexpr (OUT != kOutI32) {
+            Out *y = static_cast<Out *>(a.y);
+            const bool vec_ok = (a.n & 15) == 0;
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                const int clocal = (wave_m * TM + tm) * 32 + 16 * lhalf;
+                const int cbase = co0 + clocal;
+                float swv[16], bv[16];
+#pragma unroll
+                for (int r = 0; r < 16; r += 4) {
+                    const float4 s4 = *reinterpret_cast<const float4 *>(&s_sw[tb][clocal + r]);
+                    const float4 b4 = *reinterpret_cast<const float4 *>(&s_bias[tb][clocal + r]);
+                    swv[r] = s4.x; swv[r + 1] = s4.y; swv[r + 2] = s4.z; swv[r + 3] = s4.w;
+                    bv[r] = b4.x; bv[r + 1] = b4.y; bv[r + 2] = b4.z; bv[r + 3] = b4.w;
+                }
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) {
+                    const int prow = (wave_n * TN + tn) * 32 + lrow;
+                    const uint32_t pix = p0 + prow;
+                    if (pix >= a.pixels) continue;
+                    float out[16];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        float s;
+                        if constexpr (TAPS > 1) s = facc[tm][tn][r];
+                        else s = s_sx[tb][0][prow] * static_cast<float>(acc[tm][tn][r]);
+                        out[r] = s * swv[r] + bv[r];
+                    }
+                    Out *dst = y + static_cast<int64_t>(pix) * a.n + cbase;
+                    if (vec_ok && cbase + 16 <= a.n) {
+                        store16(dst, out);
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            if (cbase + r < a.n) dst[r] = static_cast<Out>(out[r]);
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int TM, int TN, int WAVES_M, int WAVES_N, int TAPS, int OUT, int KCH, int NSTAGE, int OCC>
+hq_status launch_tile(GemmArgs a, hipStream_t stream) {
+    constexpr int BCO = 32 * TM * WAVES_M, BP = 32 * TN * WAVES_N;
+    a.n_co_tiles = (a.n + BCO - 1) / BCO;
+    const int64_t p_tiles = (static_cast<int64_t>(a.pixels) + BP - 1) / BP;
+    const int64_t tiles = p_tiles * a.n_co_tiles;
+    if (tiles * (a.k / 64) * TAPS > 0x7fffffffLL) return HQ_ERR_SHAPE;   // chunk-stream counters are 32 bit
+    a.n_tiles = static_cast<uint32_t>(tiles);
+    const int64_t slots = static_cast<int64_t>(hq::compute_units()) * OCC;   // co-resident workgroups
+    const unsigned grid = static_cast<unsigned>(tiles < slots ? tiles : slots);
+    hipLaunchKernelGGL((int_gemm_kernel<TM, TN, WAVES_M, WAVES_N, TAPS, OUT, KCH, NSTAGE, OCC>),
+                       dim3(grid), dim3(64 * WAVES_M * WAVES_N), 0, stream, a);
+    return hq::launch_status();
+}
+
+// All instantiations of one tile configuration: TAPS = 1 | 9, the three output types, and
+// K chunks of 192 codes (96 contiguous bytes per row) or, if WITH_64 is set, the 64-code
+// fallback for channel counts that are not a multiple of 192.
+template <int TM, int TN, int WAVES_M, int WAVES_N, int OCC, bool WITH_64>
+hq_status launch_config(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream_t stream) {
+    const bool wide = a.k % 192 == 0;
+    if (!wide && !WITH_64) return HQ_ERR_UNSUPPORTED;
+#define HQ_GEMM_CASE(TAPS, OUT)                                                                        \
+    if (wide) return launch_tile<TM, TN, WAVES_M, WAVES_N, TAPS, OUT, 6, 2, OCC>(a, stream);           \
+    if constexpr (WITH_64) return launch_tile<TM, TN, WAVES_M, WAVES_N, TAPS, OUT, 2, 4, OCC>(a, stream); \
+    return HQ_ERR_UNSUPPORTED;
+    if (taps == 1) {
+        if (y_dtype == HQ_F16) { HQ_GEMM_CASE(1, kOutF16) }
+        if (y_dtype == HQ_F32) { HQ_GEMM_CASE(1, kOutF32) }
+        if (y_dtype == HQ_I32) { HQ_GEMM_CASE(1, kOutI32) }
+    } else if (taps == 9) {
+        if (y_dtype == HQ_F16) { HQ_GEMM_CASE(9, kOutF16) }
+        if (y_dtype == HQ_F32) { HQ_GEMM_CASE(9, kOutF32) }
+        if (y_dtype == HQ_I32) { HQ_GEMM_CASE(9, kOutI32) }
+    }
+#undef HQ_GEMM_CASE
+    return HQ_ERR_DTYPE;
+}
+
+}  // namespace
+
+// One translation unit per tile configuration (they compile in parallel).
+hq_status hq_gemm_launch_128x128(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream_t stream);
+hq_status hq_gemm_launch_64x128(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream_t stream);
+hq_status hq_gemm_launch_64x64(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream_t stream);
