@@ -195,7 +195,10 @@ def main():
         "roofline": {
             "kernel": "int_gemm_kernel (3x3 implicit-GEMM convolutions of the sweep)",
             "bound": "mfma", "achieved": round(achieved, 1), "peak": round(INT8_MFMA_PEAK_TOPS, 1),
-            "unit": "TOP/s", "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
+            "unit": "TOP/s", "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4),
+            "traffic": measured_traffic(),
+            "traffic_unit": "HBM bytes per launch, mean over the four 3x3 launches (rocprofv3 FETCH_SIZE/WRITE_SIZE)",
+            "ops_per_launch": round(conv3_ops / len(conv3)), "us_per_launch": round(conv3_us / len(conv3), 2),
         },
         "hadamard_quant": {
             "kernel": "hq_act_hadamard_quant on %s fp16" % (list(xb.shape),),
@@ -214,15 +217,29 @@ def main():
     print(json.dumps(result))
 
 
+def measured_traffic():
+    """HBM bytes per 3x3 convolution launch from the committed rocprofv3 counter summary of this
+    same command (counters cannot be read from inside the process); None if it is absent."""
+    path = os.path.join(ROOT, "profiles", "bench_config5_hbm_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("conv3x3_traffic_bytes_per_launch"):
+                    return int(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(layers):
-    """The oracle, as it stands, on the first 8 of the 16 images of each layer of the sweep."""
+    """The oracle, as it stands, on the whole sweep (all 16 images of each layer)."""
     import numpy as np
 
     import oracle
     import workloads
 
     oracle.build()
-    take = 8
+    take = 16
     ops = 0
     prepared = []
     for layer in layers:
@@ -249,7 +266,7 @@ def cpu_baseline(layers):
     cores = oracle.max_threads()
     return {"value": round(ops / dt / 1e12, 5), "unit": "TOP/s", "cores": cores, "kind": "oracle",
             "seconds": round(dt, 2),
-            "sample": "first %d of 16 images of every layer of the sweep (%.1f GOP), fp64/int64 "
+            "sample": "one whole step: %d of 16 images of every layer of the sweep (%.1f GOP), fp64/int64 "
                       "oracle with OpenMP over rows" % (take, ops / 1e9)}
 
 
