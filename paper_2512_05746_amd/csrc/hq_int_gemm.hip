@@ -25,10 +25,11 @@ hq_status launch_gemm(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream_t
 }
 
 // The kernels index pixels with 32 bits and address the packed operands with
-// 32-bit byte offsets.
-bool fits_32bit(int64_t pixels, int n, int taps, int k) {
+// 32-bit byte offsets; a 3x3 tap shifts an activation offset by up to w + 1 pixels
+// before it is clamped, which must not wrap past 2^32 either.
+bool fits_32bit(int64_t pixels, int w, int n, int taps, int k) {
     const int64_t lim = 0xFFFFFFFFLL;
-    return pixels < 0x7FFFFFFFLL && pixels * (k / 2) <= lim &&
+    return pixels < 0x7FFFFFFFLL && (pixels + w + 2) * (k / 2) <= lim &&
            static_cast<int64_t>(n) * taps * (k / 2) <= lim;
 }
 
@@ -52,8 +53,8 @@ extern "C" hq_status hq_int_linear(const uint8_t *xq, const float *x_scale, cons
                                    void *y, hq_dtype y_dtype, void *stream) {
     hq_status st = check_common(xq, x_scale, wq, w_scale, bias, m, n, k, y, y_dtype);
     if (st != HQ_OK) return st;
-    if (!fits_32bit(m, n, 1, k)) return HQ_ERR_UNSUPPORTED;
-    GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(m), n, k, 1, 1, 0, 0};
+    if (!fits_32bit(m, 1, n, 1, k)) return HQ_ERR_UNSUPPORTED;
+    GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(m), n, k, 1, 1, 0, 0, 0};
     return launch_gemm(a, 1, y_dtype, static_cast<hipStream_t>(stream));
 }
 
@@ -69,8 +70,8 @@ extern "C" hq_status hq_int_conv2d(const uint8_t *xq, const float *x_scale, cons
     hq_status st = check_common(xq, x_scale, wq, w_scale, bias, pixels, c_out, c_in, y, y_dtype);
     if (st != HQ_OK) return st;
     if (r != s || (r != 1 && r != 3) || stride != 1 || pad != (r - 1) / 2) return HQ_ERR_UNSUPPORTED;
-    if (!fits_32bit(pixels, c_out, r * s, c_in)) return HQ_ERR_UNSUPPORTED;
-    GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(pixels), c_out, c_in, h, w, 0, 0};
+    if (!fits_32bit(pixels, w, c_out, r * s, c_in)) return HQ_ERR_UNSUPPORTED;
+    GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(pixels), c_out, c_in, h, w, 0, 0, 0};
     hipStream_t st_ = static_cast<hipStream_t>(stream);
     return launch_gemm(a, r * s, y_dtype, st_);
 }

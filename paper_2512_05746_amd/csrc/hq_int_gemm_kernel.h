@@ -45,6 +45,7 @@ struct GemmArgs {
     int h, w;            // image size (convolution only)
     int n_co_tiles;
     uint32_t n_tiles;    // pixel tiles * channel tiles
+    uint32_t xcds;       // 1: deal the tiles out per XCD (grid is a multiple of 8); 0: plain grid stride
 };
 
 namespace {
@@ -103,10 +104,9 @@ __device__ __forceinline__ void lds_read16(v4i &dst, uint32_t addr) {
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFFSET) : "memory");
 }
 
-__device__ __forceinline__ float lds_read_f32_now(uint32_t addr) {
-    float r;
-    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(r) : "v"(addr) : "memory");
-    return r;
+template <int OFFSET>
+__device__ __forceinline__ void lds_read_f32(float &dst, uint32_t addr) {
+    asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFFSET) : "memory");
 }
 
 // Ties a register to the point after the preceding hand-placed wait.
@@ -138,14 +138,45 @@ struct Packed {
     v4i b[TN];
 };
 
-template <int TM, int TN, int ROWB, int I = 0>
+// KOFF: byte offset of the K step inside the chunk row (an immediate of the read)
+template <int TM, int TN, int ROWB, int KOFF, int I = 0>
 __device__ __forceinline__ void read_packed(Packed<TM, TN> &o, uint32_t addr_a, uint32_t addr_b) {
     if constexpr (I < TM) {
-        lds_read16<I * 32 * ROWB>(o.a[I], addr_a);
-        read_packed<TM, TN, ROWB, I + 1>(o, addr_a, addr_b);
+        lds_read16<I * 32 * ROWB + KOFF>(o.a[I], addr_a);
+        read_packed<TM, TN, ROWB, KOFF, I + 1>(o, addr_a, addr_b);
     } else if constexpr (I < TM + TN) {
-        lds_read16<(I - TM) * 32 * ROWB>(o.b[I - TM], addr_b);
-        read_packed<TM, TN, ROWB, I + 1>(o, addr_a, addr_b);
+        lds_read16<(I - TM) * 32 * ROWB + KOFF>(o.b[I - TM], addr_b);
+        read_packed<TM, TN, ROWB, KOFF, I + 1>(o, addr_a, addr_b);
+    }
+}
+
+// The K steps of one chunk: the packed operands of step K+1 are requested before the MFMAs of
+// step K are issued.  mul(operands, first) multiplies one step; first: the sums start from 0.
+template <int K, int KS, int TM, int TN, int ROWB, class Mul>
+__device__ __forceinline__ void chunk_steps(Packed<TM, TN> (&op)[2], uint32_t addr_a, uint32_t addr_b,
+                                            bool first_of_tap, Mul &mul) {
+    if constexpr (K < KS) {
+        if constexpr (K + 1 < KS) {
+            read_packed<TM, TN, ROWB, (K + 1) * 32>(op[(K + 1) & 1], addr_a, addr_b);
+            wait_lds<TM + TN>();   // everything but the reads just issued
+        } else {
+            wait_lds<0>();
+        }
+        mul(op[K & 1], K == 0 && first_of_tap);
+        chunk_steps<K + 1, KS, TM, TN, ROWB>(op, addr_a, addr_b, first_of_tap, mul);
+    }
+}
+
+// The TN per-pixel scales of one tap (32 pixels apart in the table), read together.
+template <int TN, int I = 0>
+__device__ __forceinline__ void read_tap_scales(float (&s)[TN], uint32_t addr) {
+    if constexpr (I < TN) {
+        lds_read_f32<I * 32 * 4>(s[I], addr);
+        read_tap_scales<TN, I + 1>(s, addr);
+    } else {
+        wait_lds<0>();
+#pragma unroll
+        for (int i = 0; i < TN; ++i) asm volatile("" : "+v"(s[i]));
     }
 }
 
@@ -180,11 +211,15 @@ __device__ __forceinline__ void store16(float *dst, const float (&v)[16]) {
 // TAPS = 1 (linear / 1x1) or 9 (3x3, stride 1, pad 1).
 //
 // Persistent workgroups: the grid is sized to the machine and every workgroup
-// walks its tiles (grid stride; output-channel tiles of one pixel tile are
-// adjacent).  All chunks of all its tiles form ONE stream through the LDS
-// stages, so the loads of the next tile's first chunks are in flight while the
-// current tile is finished and written out, and the scale tables of the next
-// tile are built during the current one (two table sets).
+// walks its tiles (output-channel tiles of one pixel tile are adjacent).  With
+// a.xcds set, workgroup b is taken to run on XCD b % 8 (the dispatcher deals
+// workgroups round-robin over the eight XCDs) and each XCD gets one contiguous
+// eighth of the tiles, so the activation rows a tile shares with its
+// neighbours are fetched into one L2 only.  All chunks of all tiles of a
+// workgroup form ONE stream through the LDS stages, so the loads of the next
+// tile's first chunks are in flight while the current tile is finished and
+// written out, and the scale tables of the next tile are built during the
+// current one (two table sets).
 //
 // K is consumed in chunks of KCH 16-byte pieces per row (KCH * 32 codes); NSTAGE
 // chunks of both operands live in LDS, filled by direct-to-LDS loads issued
@@ -197,9 +232,15 @@ __device__ __forceinline__ void store16(float *dst, const float (&v)[16]) {
 // groups.  Inside a chunk the packed operands of K step k+1 are read from LDS
 // while the MFMAs of step k run.
 //
-// Rows that do not exist (channels >= n, pixels >= pixels, taps outside the
-// image) are loaded from a clamped in-bounds address instead of being zeroed:
-// their sums are never stored, and a tap outside the image has scale 0.
+// Addresses.  A load is "uniform base + per-lane 32-bit offset".  The per-lane
+// offsets are set once per tile; the position inside the row (chunk) and the
+// weight tap move the uniform base only.  For a 3x3 tap the activation offset
+// is shifted by a uniform number of pixels and clamped to the last pixel
+// (unsigned: a shift below pixel 0 wraps and clamps too), two vector
+// instructions per load and tap.  So rows that do not exist (channels >= n,
+// pixels >= pixels) and taps outside the image read some other in-bounds row
+// instead of zeros: their sums are never stored, and a tap outside the image
+// has scale 0 (int32 output: written as 0).
 template <int TM, int TN, int WAVES_M, int WAVES_N, int TAPS, int OUT, int KCH, int NSTAGE, int OCC>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(GemmArgs a) {
     constexpr int NW = WAVES_M * WAVES_N;
@@ -211,16 +252,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     static_assert(KCH % 2 == 0, "a 64-code K step is two pieces");
     static_assert((BCO * KCH) % 64 == 0 && (BP * KCH) % 64 == 0, "whole wave-wide loads only");
     constexpr int A_INSTR = BCO * KCH / 64, B_INSTR = BP * KCH / 64;   // 1 KiB loads per chunk
-    // every wave issues the same number of loads (the hand-placed wait counts rely on it); if
-    // the loads do not split evenly, the surplus slots repeat an earlier load (same bytes, same
-    // destination)
-    constexpr int NI = A_INSTR + B_INSTR;
-    constexpr int LPW = (NI + NW - 1) / NW;
+    // Load i of an operand belongs to wave i % NW: every wave has A_SLOTS slots for weight rows
+    // and B_SLOTS for activation rows and skips a slot whose load does not exist.  With two
+    // stages every wait is for all of a wave's loads, so uneven shares are fine; a deeper
+    // pipeline counts outstanding loads and needs the same number in every wave.
+    constexpr int A_SLOTS = (A_INSTR + NW - 1) / NW, B_SLOTS = (B_INSTR + NW - 1) / NW;
+    constexpr int LPW = A_SLOTS + B_SLOTS;
+    static_assert(NSTAGE == 2 || (A_INSTR % NW == 0 && B_INSTR % NW == 0), "even shares for counted waits");
     static_assert((NSTAGE - 2) * LPW < 64, "vmcnt range");
     static_assert(TM + TN < 16, "lgkmcnt range");
     static_assert(BP <= NT && BCO <= NT, "one table entry per thread");
     constexpr int STAGE_BYTES = (BCO + BP) * ROWB;
     constexpr int SX_PER_T = (TAPS * BP + NT - 1) / NT;   // scale-table entries per thread
+    constexpr uint32_t XCDS = 8;
     using Out = typename OutT<OUT>::type;
     using Ops = Packed<TM, TN>;
 
@@ -245,11 +289,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     const uint32_t lds_b = lds_a + (BCO + (wave_n * TN - wave_m * TM) * 32) * ROWB;
     const uint32_t lds_sx = lds_address(&s_sx[0][0][0]) + (wave_n * TN * 32 + lrow) * 4;
 
-    if (blockIdx.x >= a.n_tiles) return;
-    const uint32_t my_tiles = (a.n_tiles - blockIdx.x + gridDim.x - 1) / gridDim.x;
+    // ---- this workgroup's tiles: t_first, t_first + t_step, ... below t_end -----------------------
+    uint32_t t_first = blockIdx.x, t_step = gridDim.x, t_end = a.n_tiles;
+    if (a.xcds) {   // gridDim.x is a multiple of XCDS then
+        const uint32_t x = blockIdx.x % XCDS;
+        t_step = gridDim.x / XCDS;
+        t_first = static_cast<uint32_t>(static_cast<uint64_t>(a.n_tiles) * x / XCDS) + blockIdx.x / XCDS;
+        t_end = static_cast<uint32_t>(static_cast<uint64_t>(a.n_tiles) * (x + 1) / XCDS);
+    }
+    if (t_first >= t_end) return;
+    const uint32_t my_tiles = (t_end - t_first + t_step - 1) / t_step;
     const uint32_t stream_chunks = my_tiles * total_chunks;   // < 2^31, checked on the host
     auto tile_origin = [&](uint32_t k, int &co0, uint32_t &p0) {
-        const uint32_t tile = blockIdx.x + k * gridDim.x;
+        const uint32_t tile = t_first + k * t_step;
         co0 = static_cast<int>(tile % a.n_co_tiles) * BCO;
         p0 = (tile / a.n_co_tiles) * BP;
     };
@@ -303,50 +355,67 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     };
 
     // ---- this wave's share of the direct-to-LDS loads -------------------------------------------
-    uint32_t ld_off[LPW];     // byte offset of this lane's piece at tap 0, chunk 0 of the tile being fetched
-    int ld_mask[LPW];         // activation rows: taps inside the image
-    uint32_t ld_cur[LPW];     // ld_off + the term of the tap being fetched
-    uint32_t fk = 0;          // tile (index in this workgroup's list) being fetched
+    uint32_t ld_a[A_SLOTS];      // weight rows: byte offset of this lane's piece at tap 0, chunk 0
+    uint32_t ld_b[B_SLOTS];      // activation rows: the same, at the tile's own pixel
+    uint32_t ld_bmax[B_SLOTS];   // ... at the last pixel of the tensor
+    uint32_t ld_bcur[B_SLOTS];   // ... at the pixel under the tap being fetched
+    uint32_t a_tap_off = 0;      // uniform: tap being fetched * kbytes
+    uint32_t fk = 0;             // tile (index in this workgroup's list) being fetched
     int ftap = 0, fch = 0;
-    uint32_t fetched = 0;     // chunks of the stream requested so far
-    auto set_fetch_tap = [&](int t) {
-        const int shift = TAPS > 1 ? ((t / 3 - 1) * a.w + (t % 3 - 1)) * kbytes : 0;
+    uint32_t fetched = 0;        // chunks of the stream requested so far
+    // lane's 16-byte slot in load i of an operand: row of the tile, byte offset inside the chunk row
+    auto slot_row = [&](int i) { return (i * 64 + lane) / KCH; };
+    auto slot_byte = [&](int i) {
+        const int q = i * 64 + lane, row = q / KCH;
+        return static_cast<uint32_t>(((q % KCH) ^ ((row >> 3) & 1)) * 16);   // swizzle, see above
+    };
 #pragma unroll
-        for (int j = 0; j < LPW; ++j) {
-            if ((j * NW + wave) % NI < A_INSTR) ld_cur[j] = ld_off[j] + t * kbytes;
-            else ld_cur[j] = ld_off[j] + (((ld_mask[j] >> t) & 1) ? shift : 0);
+    for (int j = 0; j < B_SLOTS; ++j) ld_bmax[j] = (a.pixels - 1) * kbytes + slot_byte(j * NW + wave);
+    auto set_fetch_tap = [&](int t) {
+        a_tap_off = static_cast<uint32_t>(t) * kbytes;
+#pragma unroll
+        for (int j = 0; j < B_SLOTS; ++j) {
+            if constexpr (TAPS > 1) {
+                const uint32_t shift = static_cast<uint32_t>(((t / 3 - 1) * a.w + (t % 3 - 1)) * kbytes);
+                const uint32_t o = ld_b[j] + shift;
+                ld_bcur[j] = o < ld_bmax[j] ? o : ld_bmax[j];
+            } else {
+                ld_bcur[j] = ld_b[j];
+            }
         }
     };
-    auto set_fetch_tile = [&](uint32_t k) {   // needs the masks of tile k to be visible
+    auto set_fetch_tile = [&](uint32_t k) {
         int co0; uint32_t p0;
         tile_origin(k, co0, p0);
 #pragma unroll
-        for (int j = 0; j < LPW; ++j) {
-            const int ii = (j * NW + wave) % NI;   // wave-uniform index of the 1 KiB load
-            const int q = (ii < A_INSTR ? ii : ii - A_INSTR) * 64 + lane;   // 16-byte slot in the tile image
-            const int row = q / KCH;
-            const int piece = (q % KCH) ^ ((row >> 3) & 1);                 // swizzle, see above
-            if (ii < A_INSTR) {
-                int co = co0 + (row & ~31) + tile_row_to_channel(row & 31);
-                co = co < a.n ? co : a.n - 1;
-                ld_off[j] = static_cast<uint32_t>(co) * TAPS * kbytes + piece * 16;
-                ld_mask[j] = 0;
-            } else {
-                uint32_t pix = p0 + row;
-                pix = pix < a.pixels ? pix : a.pixels - 1;
-                ld_off[j] = pix * kbytes + piece * 16;
-                ld_mask[j] = TAPS > 1 ? s_mask[k & 1][row] : 1;
-            }
+        for (int j = 0; j < A_SLOTS; ++j) {
+            const int i = j * NW + wave, row = slot_row(i);
+            int co = co0 + (row & ~31) + tile_row_to_channel(row & 31);
+            co = co < a.n ? co : a.n - 1;
+            ld_a[j] = static_cast<uint32_t>(co) * TAPS * kbytes + slot_byte(i);
+        }
+#pragma unroll
+        for (int j = 0; j < B_SLOTS; ++j) {
+            const int i = j * NW + wave;
+            uint32_t pix = p0 + slot_row(i);
+            pix = pix < a.pixels ? pix : a.pixels - 1;
+            ld_b[j] = pix * kbytes + slot_byte(i);
         }
         set_fetch_tap(0);
     };
     auto issue_loads = [&](int stage) {
+        const uint8_t *base_a = a.wq + (a_tap_off + static_cast<uint32_t>(fch * ROWB));
+        const uint8_t *base_b = a.xq + fch * ROWB;
+        uint8_t *image = lds + stage * STAGE_BYTES;   // weight rows, then activation rows; 1 KiB per load
 #pragma unroll
-        for (int j = 0; j < LPW; ++j) {
-            const int ii = (j * NW + wave) % NI;
-            const uint8_t *base = (ii < A_INSTR ? a.wq : a.xq) + fch * ROWB;
-            // stage image: A rows then B rows, each wave-wide load fills the next 1 KiB
-            load_to_lds16(base + ld_cur[j], lds + stage * STAGE_BYTES + ii * 1024);
+        for (int j = 0; j < A_SLOTS; ++j) {
+            const int i = j * NW + wave;
+            if (i < A_INSTR) load_to_lds16(base_a + ld_a[j], image + i * 1024);
+        }
+#pragma unroll
+        for (int j = 0; j < B_SLOTS; ++j) {
+            const int i = j * NW + wave;
+            if (i < B_INSTR) load_to_lds16(base_b + ld_bcur[j], image + BCO * ROWB + i * 1024);
         }
         ++fetched;
         if (++fch == chunks_per_tap) {
@@ -361,13 +430,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     };
 
     // ---- prologue of the stream ---------------------------------------------------------------
-    build_masks(0);
-    if (my_tiles > 1) build_masks(1);
-    __syncthreads();
     set_fetch_tile(0);
 #pragma unroll
     for (int st = 0; st < NSTAGE - 1; ++st)
         if (fetched < stream_chunks) issue_loads(st);
+    build_masks(0);
+    if (my_tiles > 1) build_masks(1);
+    __syncthreads();
     load_scales(0);
     store_scales(0);
     __syncthreads();   // tables visible to every wave before the first raw barrier below
@@ -441,17 +510,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
 
             const uint32_t sa = lds_a + stage * STAGE_BYTES, sb = lds_b + stage * STAGE_BYTES;
             Ops op[2];
-            read_packed<TM, TN, ROWB>(op[0], sa, sb);
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                if (ks + 1 < KS) {
-                    read_packed<TM, TN, ROWB>(op[(ks + 1) & 1], sa + (ks + 1) * 32, sb + (ks + 1) * 32);
-                    wait_lds<TM + TN>();   // everything but the reads just issued
-                } else {
-                    wait_lds<0>();
-                }
-                multiply(op[ks & 1], ks == 0 && ch == 0);
-            }
+            read_packed<TM, TN, ROWB, 0>(op[0], sa, sb);
+            chunk_steps<0, KS, TM, TN, ROWB>(op, sa, sb, ch == 0, multiply);
 
             if (++ch == chunks_per_tap) {
                 ch = 0;
@@ -475,15 +535,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
                         }
                     }
                 } else if constexpr (TAPS > 1) {
+                    float s[TN];
+                    read_tap_scales<TN>(s, lds_sx + (tb * TAPS + tap) * BP * 4);
 #pragma unroll
-                    for (int tn = 0; tn < TN; ++tn) {
-                        const float s = lds_read_f32_now(lds_sx + ((tb * TAPS + tap) * BP + tn * 32) * 4);
+                    for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
                         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
                             for (int r = 0; r < 16; ++r)
-                                facc[tm][tn][r] += s * static_cast<float>(acc[tm][tn][r]);
-                    }
+                                facc[tm][tn][r] += s[tn] * static_cast<float>(acc[tm][tn][r]);
                 }
                 ++tap;
             }
@@ -547,6 +607,7 @@ hq_status launch_tile(GemmArgs a, hipStream_t stream) {
     a.n_tiles = static_cast<uint32_t>(tiles);
     const int64_t slots = static_cast<int64_t>(hq::compute_units()) * OCC;   // co-resident workgroups
     const unsigned grid = static_cast<unsigned>(tiles < slots ? tiles : slots);
+    a.xcds = grid % 8 == 0 ? 1 : 0;
     hipLaunchKernelGGL((int_gemm_kernel<TM, TN, WAVES_M, WAVES_N, TAPS, OUT, KCH, NSTAGE, OCC>),
                        dim3(grid), dim3(64 * WAVES_M * WAVES_N), 0, stream, a);
     return hq::launch_status();
