@@ -73,5 +73,10 @@ extern "C" hq_status hq_int_conv2d(const uint8_t *xq, const float *x_scale, cons
     if (!fits_32bit(pixels, w, c_out, r * s, c_in)) return HQ_ERR_UNSUPPORTED;
     GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(pixels), c_out, c_in, h, w, 0, 0, 0};
     hipStream_t st_ = static_cast<hipStream_t>(stream);
+    // A 3x3 layer with about one 64x64 output tile per CU or fewer cannot fill the machine with
+    // whole tiles: it takes the kernel that also splits a tile's K range over waves.
+    const int64_t tiles64 = ((pixels + 63) / 64) * ((c_out + 63) / 64);
+    if (r == 3 && c_in % 192 == 0 && y_dtype != HQ_I32 && tiles64 * 4 <= 5 * static_cast<int64_t>(hq::compute_units()))
+        return hq_conv3x3_wave_launch(a, y_dtype, st_);
     return launch_gemm(a, r * s, y_dtype, st_);
 }

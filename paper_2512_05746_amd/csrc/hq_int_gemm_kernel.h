@@ -253,12 +253,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     static_assert((BCO * KCH) % 64 == 0 && (BP * KCH) % 64 == 0, "whole wave-wide loads only");
     constexpr int A_INSTR = BCO * KCH / 64, B_INSTR = BP * KCH / 64;   // 1 KiB loads per chunk
     // Load i of an operand belongs to wave i % NW: every wave has A_SLOTS slots for weight rows
-    // and B_SLOTS for activation rows and skips a slot whose load does not exist.  With two
-    // stages every wait is for all of a wave's loads, so uneven shares are fine; a deeper
-    // pipeline counts outstanding loads and needs the same number in every wave.
+    // and B_SLOTS for activation rows and skips a slot whose load does not exist (only the last
+    // slot of an operand can be missing; the counted waits below take that into account).
     constexpr int A_SLOTS = (A_INSTR + NW - 1) / NW, B_SLOTS = (B_INSTR + NW - 1) / NW;
     constexpr int LPW = A_SLOTS + B_SLOTS;
-    static_assert(NSTAGE == 2 || (A_INSTR % NW == 0 && B_INSTR % NW == 0), "even shares for counted waits");
     static_assert((NSTAGE - 2) * LPW < 64, "vmcnt range");
     static_assert(TM + TN < 16, "lgkmcnt range");
     static_assert(BP <= NT && BCO <= NT, "one table entry per thread");
@@ -497,8 +495,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
         int tap = 0, ch = 0;
         for (int chunk = 0; chunk < total_chunks; ++chunk, ++g) {
             // this chunk has landed once at most the later (NSTAGE-2) chunks' loads are pending
-            if (g + NSTAGE - 2 < stream_chunks) wait_vmem<(NSTAGE - 2) * LPW>();
-            else wait_vmem<0>();
+            if constexpr (NSTAGE == 2) {
+                wait_vmem<0>();
+            } else if (g + NSTAGE - 2 < stream_chunks) {
+                const int missing = ((A_SLOTS - 1) * NW + wave >= A_INSTR) + ((B_SLOTS - 1) * NW + wave >= B_INSTR);
+                if (missing == 0) wait_vmem<(NSTAGE - 2) * LPW>();
+                else if (missing == 1) wait_vmem<(NSTAGE - 2) * (LPW - 1)>();
+                else wait_vmem<(NSTAGE - 2) * (LPW - 2)>();
+            } else {
+                wait_vmem<0>();
+            }
             __builtin_amdgcn_s_barrier();   // every wave's share has landed; the previous stage is free
             if (fetched < stream_chunks) issue_loads(stage == 0 ? NSTAGE - 1 : stage - 1);
 
@@ -616,12 +622,12 @@ hq_status launch_tile(GemmArgs a, hipStream_t stream) {
 // All instantiations of one tile configuration: TAPS = 1 | 9, the three output types, and
 // K chunks of 192 codes (96 contiguous bytes per row) or, if WITH_64 is set, the 64-code
 // fallback for channel counts that are not a multiple of 192.
-template <int TM, int TN, int WAVES_M, int WAVES_N, int OCC, bool WITH_64>
+template <int TM, int TN, int WAVES_M, int WAVES_N, int OCC, bool WITH_64, int NSTAGE_WIDE = 2>
 hq_status launch_config(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream_t stream) {
     const bool wide = a.k % 192 == 0;
     if (!wide && !WITH_64) return HQ_ERR_UNSUPPORTED;
 #define HQ_GEMM_CASE(TAPS, OUT)                                                                        \
-    if (wide) return launch_tile<TM, TN, WAVES_M, WAVES_N, TAPS, OUT, 6, 2, OCC>(a, stream);           \
+    if (wide) return launch_tile<TM, TN, WAVES_M, WAVES_N, TAPS, OUT, 6, NSTAGE_WIDE, OCC>(a, stream);           \
     if constexpr (WITH_64) return launch_tile<TM, TN, WAVES_M, WAVES_N, TAPS, OUT, 2, 4, OCC>(a, stream); \
     return HQ_ERR_UNSUPPORTED;
     if (taps == 1) {
@@ -643,3 +649,5 @@ hq_status launch_config(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream
 hq_status hq_gemm_launch_128x128(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream_t stream);
 hq_status hq_gemm_launch_64x128(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream_t stream);
 hq_status hq_gemm_launch_64x64(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream_t stream);
+// 3x3 convolution, one wave per 64x64 tile and K share (hq_conv3x3_wave.hip)
+hq_status hq_conv3x3_wave_launch(const GemmArgs &a, hq_dtype y_dtype, hipStream_t stream);

@@ -154,4 +154,6 @@ def tiny_layers() -> List[Layer]:
         _conv("t_conv1", 0, 5, 2, 7, 64, 40, 1, **kw),
         _conv("t_conv3_a3", 0, 6, 1, 17, 64, 130, 3, a_bits=3, w_bits=4, dist="laplace",
               outlier_frac=0.02, outlier_factor=30.0, bias_std=0.01),
+        # 52 x 5 = 260 output tiles of 64 x 64: between one tile per CU and 1.25 (a K range in two shares)
+        _conv("t_conv3_split2", 0, 7, 13, 16, 192, 320, 3, bias_std=0.01, **kw),
     ]
