@@ -221,17 +221,26 @@ __global__ __launch_bounds__(kThreads) void rowquant_large(const T *__restrict__
     if (tid == 0) scale[blockIdx.x] = amax > 0.f ? (amax * a.norm) / a.qmax : 1.0f;
 }
 
-// ---- fp16 input, block 64: the transform on the matrix cores ---------------------------------
+// ---- fp16 input, block 64, rows of up to 1024 channels: the transform on the matrix cores ------
 //
 // For the streaming activation path the butterfly above is bound by vector-ALU work
 // (about 14 instructions per element), not by HBM.  Here the same product x * H64 is
 // evaluated as an MFMA: out^T = H^T x^T with H (entries +-1, exact in fp16) as the "A"
-// operand and 32 tokens as the columns of "B", accumulated in fp32; the products are exact,
-// so only the summation order differs from the butterfly.  A lane owns one token
-// (column lane%32); the rows of H are permuted so that the 32 results a lane holds per block
-// are 32 consecutive channels, i.e. 16 contiguous packed bytes.  The B operand of a
-// 32x32x16 MFMA is 8 consecutive fp16 of a token row, i.e. exactly one 16-byte global load,
-// so the activations go from HBM to the matrix core without touching LDS.
+// operand and 16 tokens as the columns of "B" of v_mfma_f32_16x16x32_f16, accumulated in
+// fp32; the products are exact, so only the summation order differs from the butterfly.
+//
+// Decomposition.  A workgroup has one wave per 64-channel block of the row and handles groups
+// of 16 tokens; wave b transforms block b of the group's tokens.  Lane l owns token l % 16
+// and K slice q = l / 16: its B operands are the two 16-byte pieces at channels 32 h + 8 q
+// (h = 0, 1) of the block, so activations go from HBM straight into the matrix core.  The rows
+// of H are permuted so that the 16 results of a lane are the 16 consecutive channels
+// 16 q .. 16 q + 15 of the block: 8 packed bytes, and the four lanes of a token write 32
+// contiguous bytes.  The abs-max of a token needs every block of its row: the waves exchange
+// their maxima through LDS (one barrier per group, two sets of slots).  Workgroups are
+// persistent and fetch the next group's pieces before they work on the current one.
+//
+// Only pairing matters for the K index: element e of K slice q of operand h is channel
+// 32 h + 8 q + e for both operands, whatever order the hardware sums them in.
 //
 // Quantisation: m = fma(v, qmax / amax, 1.5 * 2^23 + 8) rounds v * inv to the nearest
 // integer (ties to even, one rounding) and leaves code + 8 (1..15) in the low nibble of the
@@ -239,16 +248,11 @@ __global__ __launch_bounds__(kThreads) void rowquant_large(const T *__restrict__
 // constant contributed by the upper bits is subtracted and the offset removed by
 // xor 0x88888888, which yields the eight two's-complement nibbles.
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
-typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr float kMagic = 12582920.0f;                                 // 1.5 * 2^23 + 8
 constexpr uint32_t kMagicSum = 0x4B400000u * 0x11111111u;             // sum_i 0x4B400000 << 4i (mod 2^32)
-
-// Channel (inside a 64-block) produced by row i of H tile mt: lane half h = (i>>2)&1 ends up
-// with the consecutive channels 32h + 16mt + (0..15) in its 16 result registers.
-__device__ __forceinline__ int h_row_channel(int mt, int i) {
-    return 32 * ((i >> 2) & 1) + 16 * mt + 4 * (i >> 3) + (i & 3);
-}
+constexpr int kMaxBlocks = 16;                                        // waves per workgroup
 
 __device__ __forceinline__ uint32_t pack8_magic(const float *v, float inv) {
     uint32_t w = __float_as_uint(__builtin_fmaf(v[7], inv, kMagic));
@@ -257,9 +261,110 @@ __device__ __forceinline__ uint32_t pack8_magic(const float *v, float inv) {
     return (w - kMagicSum) ^ 0x88888888u;
 }
 
-// NB = k / 64 blocks per token, all held in registers (k <= 384).
+__global__ __launch_bounds__(64 * kMaxBlocks) void hadamard64_quant_f16(const __half *__restrict__ x, int64_t m,
+                                                                        int k, float qmax,
+                                                                        uint8_t *__restrict__ xq,
+                                                                        float *__restrict__ scale) {
+    __shared__ float s_amax[2][kMaxBlocks][16];
+    const int lane = threadIdx.x & 63;
+    const int blk = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // 64-channel block of this wave
+    const int nblk = k >> 6;
+    const int tok = lane & 15, q = lane >> 4;
+
+    // "A" operands: tile ct (4 tiles of 16 rows) x K half h.  Row i of tile ct is channel
+    // c = 16 (i / 4) + 4 ct + i % 4, so lane (token, q) ends up with channels 16 q + 4 ct + r.
+    // Sign of H[c][kk] = parity of popcount(c & kk), kk = 32 h + 8 q' + e with q' = this lane's
+    // K slice: the bits of e (0..2) and of 32 h + 8 q' (3..5) do not overlap, so the sign is
+    // (pattern over e from c & 7) xor (one bit from c & (32 h + 8 q')).
+    v8h hmat[4][2];
+    {
+        const int i = lane & 15;
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+            const int c = 16 * (i >> 2) + 4 * ct + (i & 3);
+            uint32_t pat[4];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                const uint32_t s0 = __popc(c & (2 * e2)) & 1, s1 = __popc(c & (2 * e2 + 1)) & 1;
+                pat[e2] = 0x3C003C00u ^ (s0 << 15) ^ (s1 << 31);   // +-1.0 in fp16
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t flip = (__popc(c & (32 * h + 8 * q)) & 1) ? 0x80008000u : 0u;
+                const uint4 w = uint4{pat[0] ^ flip, pat[1] ^ flip, pat[2] ^ flip, pat[3] ^ flip};
+                hmat[ct][h] = __builtin_bit_cast(v8h, w);
+            }
+        }
+    }
+
+    const int64_t groups = (m + 15) >> 4;
+    auto fetch = [&](int64_t grp, v8h (&b)[2]) {
+        int64_t token = grp * 16 + tok;
+        token = token < m ? token : m - 1;
+        const __half *src = x + token * k + 64 * blk + 8 * q;
+        b[0] = *reinterpret_cast<const v8h *>(src);
+        b[1] = *reinterpret_cast<const v8h *>(src + 32);
+    };
+
+    v8h b[2], bn[2];
+    int64_t grp = blockIdx.x;
+    if (grp < groups) fetch(grp, b);
+    int set = 0;
+    for (; grp < groups; grp += gridDim.x, set ^= 1) {
+        const int64_t next = grp + gridDim.x;
+        if (next < groups) fetch(next, bn);
+
+        float v[16];
+        float amax = 0.f;
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+            v4f acc = {0.f, 0.f, 0.f, 0.f};
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(hmat[ct][0], b[0], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(hmat[ct][1], b[1], acc, 0, 0, 0);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                v[4 * ct + r] = acc[r];
+                amax = fmaxf(amax, fabsf(acc[r]));
+            }
+        }
+        // the token's other three K slices of this block, then its other blocks
+        amax = fmaxf(amax, __shfl_xor(amax, 16));
+        amax = fmaxf(amax, __shfl_xor(amax, 32));
+        if (nblk > 1) {
+            if (q == 0) s_amax[set][blk][tok] = amax;
+            __syncthreads();
+            for (int w = 0; w < nblk; ++w) amax = fmaxf(amax, s_amax[set][w][tok]);
+        }
+
+        const int64_t token = grp * 16 + tok;
+        if (token < m) {
+            const float inv = amax > 0.f ? qmax / amax : 0.f;
+            if (blk == 0 && q == 0) scale[token] = amax > 0.f ? (amax * 0.125f) / qmax : 1.0f;
+            uint2 w;
+            w.x = pack8_magic(v, inv);
+            w.y = pack8_magic(v + 8, inv);
+            *reinterpret_cast<uint2 *>(xq + token * (k >> 1) + 32 * blk + 8 * q) = w;
+        }
+        b[0] = bn[0];
+        b[1] = bn[1];
+    }
+}
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+// Channel (inside a 64-block) produced by row i of H tile mt: lane half h = (i>>2)&1 ends up
+// with the consecutive channels 32h + 16mt + (0..15) in its 16 result registers.
+__device__ __forceinline__ int h_row_channel(int mt, int i) {
+    return 32 * ((i >> 2) & 1) + 16 * mt + 4 * (i >> 3) + (i & 3);
+}
+
+// Short rows (k <= 192): one wave transforms 32 whole tokens with v_mfma_f32_32x32x16_f16 and keeps
+// all NB = k / 64 blocks in registers; no exchange between waves is needed.  A lane owns token
+// lane % 32; the rows of H are permuted so that its 32 results per block are 32 consecutive
+// channels.  At this row length the whole-row form is the faster of the two (fewer, larger
+// units of work per wave; measured on [65536, 192]).
 template <int NB>
-__global__ __launch_bounds__(256) void hadamard64_quant_f16(const __half *__restrict__ x, int64_t m,
+__global__ __launch_bounds__(256) void hadamard64_rows_quant_f16(const __half *__restrict__ x, int64_t m,
                                                             float qmax, uint8_t *__restrict__ xq,
                                                             float *__restrict__ scale) {
     constexpr int K = 64 * NB;
@@ -331,14 +436,28 @@ __global__ __launch_bounds__(256) void hadamard64_quant_f16(const __half *__rest
 }
 
 template <int NB>
-hq_status launch_hadamard64(const __half *x, int64_t m, int bits, uint8_t *xq, float *scale, hipStream_t stream) {
+hq_status launch_hadamard64_rows(const __half *x, int64_t m, int bits, uint8_t *xq, float *scale, hipStream_t stream) {
     const float qmax = static_cast<float>((1 << (bits - 1)) - 1);
     const int64_t waves = (m + 31) / 32;
     int64_t grid = (waves + 3) / 4;
     const int64_t cap = static_cast<int64_t>(hq::compute_units()) * 8;
     if (grid > cap) grid = cap;
-    hipLaunchKernelGGL((hadamard64_quant_f16<NB>), dim3(static_cast<unsigned>(grid)), dim3(256), 0, stream, x, m,
+    hipLaunchKernelGGL((hadamard64_rows_quant_f16<NB>), dim3(static_cast<unsigned>(grid)), dim3(256), 0, stream, x, m,
                        qmax, xq, scale);
+    return hq::launch_status();
+}
+
+hq_status launch_hadamard64(const __half *x, int64_t m, int k, int bits, uint8_t *xq, float *scale,
+                            hipStream_t stream) {
+    const float qmax = static_cast<float>((1 << (bits - 1)) - 1);
+    const int nblk = k / 64;
+    const int64_t groups = (m + 15) / 16;
+    // resident workgroups: 32 waves per CU at the register use of this kernel
+    const int64_t cap = static_cast<int64_t>(hq::compute_units()) * (32 / nblk > 0 ? 32 / nblk : 1);
+    const int64_t rounds = (groups + cap - 1) / cap;          // groups per workgroup
+    const int64_t grid = (groups + rounds - 1) / rounds;      // the same number for (almost) all of them
+    hipLaunchKernelGGL(hadamard64_quant_f16, dim3(static_cast<unsigned>(grid)), dim3(64 * nblk), 0, stream, x, m,
+                       k, qmax, xq, scale);
     return hq::launch_status();
 }
 
@@ -416,15 +535,13 @@ extern "C" hq_status hq_act_hadamard_quant(const void *x, hq_dtype x_dtype, int6
     if (st != HQ_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint32_t *out = reinterpret_cast<uint32_t *>(xq);
-    if (x_dtype == HQ_F16 && had_block == 64 && k <= 384) {
+    if (x_dtype == HQ_F16 && had_block == 64 && k <= 64 * kMaxBlocks) {
         const __half *xh = static_cast<const __half *>(x);
         switch (k / 64) {
-            case 1: return launch_hadamard64<1>(xh, m, a_bits, xq, x_scale, s);
-            case 2: return launch_hadamard64<2>(xh, m, a_bits, xq, x_scale, s);
-            case 3: return launch_hadamard64<3>(xh, m, a_bits, xq, x_scale, s);
-            case 4: return launch_hadamard64<4>(xh, m, a_bits, xq, x_scale, s);
-            case 5: return launch_hadamard64<5>(xh, m, a_bits, xq, x_scale, s);
-            case 6: return launch_hadamard64<6>(xh, m, a_bits, xq, x_scale, s);
+            case 1: return launch_hadamard64_rows<1>(xh, m, a_bits, xq, x_scale, s);
+            case 2: return launch_hadamard64_rows<2>(xh, m, a_bits, xq, x_scale, s);
+            case 3: return launch_hadamard64_rows<3>(xh, m, a_bits, xq, x_scale, s);
+            default: return launch_hadamard64(xh, m, k, a_bits, xq, x_scale, s);
         }
     }
     if (x_dtype == HQ_F16)
