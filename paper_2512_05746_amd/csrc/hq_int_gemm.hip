@@ -5,23 +5,18 @@
 namespace {
 
 // Tile choice (measured on MI355X; all configurations share one kernel template):
-//   - channel counts that are a multiple of 64 but not of 128 waste a quarter of a 128-wide
-//     tile, so they take 64-channel tiles;
-//   - a layer with too few tiles to give every CU two workgroups takes 64 x 64 tiles at four
-//     workgroups per CU (more, smaller waves hide the latencies of a short stream better);
-//   - otherwise the larger tile wins on operand reuse.
+//   - with at least two 64 x 128 tiles per CU, 64-channel tiles at three workgroups per CU win
+//     even where 128-channel tiles waste nothing: three waves per SIMD hide the latencies of
+//     the chunk loop better than two, which outweighs the extra nibble expansion;
+//   - otherwise 128 x 128 tiles if there is at least one per CU;
+//   - a layer with fewer tiles takes 64 x 64 tiles at four workgroups per CU.
 hq_status launch_gemm(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream_t stream) {
     if (a.k % 192 != 0) return hq_gemm_launch_128x128(a, taps, y_dtype, stream);
     const int64_t cus = hq::compute_units();
     const int64_t pix128 = (static_cast<int64_t>(a.pixels) + 127) / 128;
-    if (a.n % 128 == 0 || a.n % 64 != 0) {
-        const int64_t tiles = pix128 * ((a.n + 127) / 128);
-        return tiles >= cus ? hq_gemm_launch_128x128(a, taps, y_dtype, stream)
-                            : hq_gemm_launch_64x64(a, taps, y_dtype, stream);
-    }
-    const int64_t tiles = pix128 * (a.n / 64);
-    return tiles >= 2 * cus ? hq_gemm_launch_64x128(a, taps, y_dtype, stream)
-                            : hq_gemm_launch_64x64(a, taps, y_dtype, stream);
+    if (a.n % 64 == 0 && pix128 * (a.n / 64) >= 2 * cus) return hq_gemm_launch_64x128(a, taps, y_dtype, stream);
+    if (pix128 * ((a.n + 127) / 128) >= cus) return hq_gemm_launch_128x128(a, taps, y_dtype, stream);
+    return hq_gemm_launch_64x64(a, taps, y_dtype, stream);
 }
 
 // The kernels index pixels with 32 bits and address the packed operands with
