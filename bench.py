@@ -115,14 +115,14 @@ def main():
 
     # ---- instrumented pass: HIP events around runs of identical launches ----------------------
     # A single 5 us launch bracketed by its own events mostly measures the gap to the next
-    # launch, so every kernel of every layer is launched `reps` times back to back between two
-    # events on the stream the kernels run on.
+    # launch, and a Python loop cannot issue launches faster than one per 5..8 us.  So every
+    # kernel of every layer is captured `reps` times back to back into a HIP graph of its own,
+    # and the events bracket one replay of that graph on the stream the kernels run on.
     ev = lambda: torch.cuda.Event(enable_timing=True)
     reps = max(args.steps, 20)
-    quant_us = np.zeros(len(state))
-    int_us = np.zeros(len(state))
-    for i, s in enumerate(state):
-        for fn, out in ((run_quant, quant_us), (run_int, int_us)):
+
+    def batched_us(fn, s):
+        if args.eager:
             fn(s)
             e0, e1 = ev(), ev()
             e0.record()
@@ -130,7 +130,25 @@ def main():
                 fn(s)
             e1.record()
             torch.cuda.synchronize()
-            out[i] = e0.elapsed_time(e1) * 1e3 / reps
+            return e0.elapsed_time(e1) * 1e3 / reps
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(reps):
+                fn(s)
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+
+    quant_us = np.zeros(len(state))
+    int_us = np.zeros(len(state))
+    for i, s in enumerate(state):
+        quant_us[i] = batched_us(run_quant, s)
+        int_us[i] = batched_us(run_int, s)
 
     per_layer = []
     for i, (layer, *_r) in enumerate(state):
@@ -162,14 +180,25 @@ def main():
     q_bytes = xb.numel() * 2 + xb.numel() // 2 + layer_b.m * 4
 
     def time_quant(bufs, reps):
-        for j in range(len(bufs)):
-            hq.hq_act_hadamard_quant(bufs[j], workloads.HAD_BLOCK, layer_b.a_bits, out=outs[j])
+        def launches():
+            for r in range(reps):
+                j = r % len(bufs)
+                hq.hq_act_hadamard_quant(bufs[j], workloads.HAD_BLOCK, layer_b.a_bits, out=outs[j])
+        launches()
         torch.cuda.synchronize()
+        g = None
+        if not args.eager:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                launches()
+            g.replay()
+            torch.cuda.synchronize()
         e0, e1 = ev(), ev()
         e0.record()
-        for r in range(reps):
-            j = r % len(bufs)
-            hq.hq_act_hadamard_quant(bufs[j], workloads.HAD_BLOCK, layer_b.a_bits, out=outs[j])
+        if g is not None:
+            g.replay()
+        else:
+            launches()
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / reps

@@ -350,103 +350,6 @@ __global__ __launch_bounds__(64 * kMaxBlocks) void hadamard64_quant_f16(const __
     }
 }
 
-typedef float v16f __attribute__((ext_vector_type(16)));
-
-// Channel (inside a 64-block) produced by row i of H tile mt: lane half h = (i>>2)&1 ends up
-// with the consecutive channels 32h + 16mt + (0..15) in its 16 result registers.
-__device__ __forceinline__ int h_row_channel(int mt, int i) {
-    return 32 * ((i >> 2) & 1) + 16 * mt + 4 * (i >> 3) + (i & 3);
-}
-
-// Short rows (k <= 192): one wave transforms 32 whole tokens with v_mfma_f32_32x32x16_f16 and keeps
-// all NB = k / 64 blocks in registers; no exchange between waves is needed.  A lane owns token
-// lane % 32; the rows of H are permuted so that its 32 results per block are 32 consecutive
-// channels.  At this row length the whole-row form is the faster of the two (fewer, larger
-// units of work per wave; measured on [65536, 192]).
-template <int NB>
-__global__ __launch_bounds__(256) void hadamard64_rows_quant_f16(const __half *__restrict__ x, int64_t m,
-                                                            float qmax, uint8_t *__restrict__ xq,
-                                                            float *__restrict__ scale) {
-    constexpr int K = 64 * NB;
-    __shared__ uint4 s_h[8][64];   // MFMA "A" operands of H: [tile mt * 4 + k slice][lane]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int idx = tid; idx < 512; idx += 256) {
-        const int combo = idx >> 6, ln = idx & 63;
-        const int c = h_row_channel(combo >> 2, ln & 31);
-        const int k0 = 16 * (combo & 3) + 8 * (ln >> 5);
-        uint32_t w[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const uint32_t s0 = __popc(c & (k0 + 2 * e)) & 1, s1 = __popc(c & (k0 + 2 * e + 1)) & 1;
-            w[e] = 0x3C003C00u ^ (s0 << 15) ^ (s1 << 31);   // +-1.0 in fp16, Sylvester sign (-1)^popcount(c & k)
-        }
-        s_h[combo][ln] = uint4{w[0], w[1], w[2], w[3]};
-    }
-    __syncthreads();
-    v8h hmat[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) hmat[i] = __builtin_bit_cast(v8h, s_h[i][lane]);
-
-    const int col = lane & 31, half = lane >> 5;
-    const int64_t wave_stride = static_cast<int64_t>(gridDim.x) * 4 * 32;
-    for (int64_t t0 = (static_cast<int64_t>(blockIdx.x) * 4 + wave) * 32; t0 < m; t0 += wave_stride) {
-        const int64_t token = t0 + col;
-        const bool valid = token < m;
-        const __half *row = x + (valid ? token : m - 1) * K + 8 * half;
-        v8h b[NB][4];
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                b[nb][ks] = *reinterpret_cast<const v8h *>(row + 64 * nb + 16 * ks);
-
-        v16f o[NB][2];
-        float amax = 0.f;
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                v16f acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(hmat[mt * 4 + ks], b[nb][ks], acc, 0, 0, 0);
-                o[nb][mt] = acc;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) amax = fmaxf(amax, fabsf(acc[r]));
-            }
-        amax = fmaxf(amax, __shfl_xor(amax, 32));   // the token's other 32 channels of every block
-        const float inv = amax > 0.f ? qmax / amax : 0.f;
-        if (valid) {
-            if (half == 0) scale[token] = amax > 0.f ? (amax * 0.125f) / qmax : 1.0f;
-            uint8_t *dst = xq + token * (K / 2) + 16 * half;
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                float v[32];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) { v[r] = o[nb][0][r]; v[16 + r] = o[nb][1][r]; }
-                uint4 w;
-                w.x = pack8_magic(v, inv);
-                w.y = pack8_magic(v + 8, inv);
-                w.z = pack8_magic(v + 16, inv);
-                w.w = pack8_magic(v + 24, inv);
-                *reinterpret_cast<uint4 *>(dst + 32 * nb) = w;
-            }
-        }
-    }
-}
-
-template <int NB>
-hq_status launch_hadamard64_rows(const __half *x, int64_t m, int bits, uint8_t *xq, float *scale, hipStream_t stream) {
-    const float qmax = static_cast<float>((1 << (bits - 1)) - 1);
-    const int64_t waves = (m + 31) / 32;
-    int64_t grid = (waves + 3) / 4;
-    const int64_t cap = static_cast<int64_t>(hq::compute_units()) * 8;
-    if (grid > cap) grid = cap;
-    hipLaunchKernelGGL((hadamard64_rows_quant_f16<NB>), dim3(static_cast<unsigned>(grid)), dim3(256), 0, stream, x, m,
-                       qmax, xq, scale);
-    return hq::launch_status();
-}
-
 hq_status launch_hadamard64(const __half *x, int64_t m, int k, int bits, uint8_t *xq, float *scale,
                             hipStream_t stream) {
     const float qmax = static_cast<float>((1 << (bits - 1)) - 1);
@@ -535,15 +438,8 @@ extern "C" hq_status hq_act_hadamard_quant(const void *x, hq_dtype x_dtype, int6
     if (st != HQ_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint32_t *out = reinterpret_cast<uint32_t *>(xq);
-    if (x_dtype == HQ_F16 && had_block == 64 && k <= 64 * kMaxBlocks) {
-        const __half *xh = static_cast<const __half *>(x);
-        switch (k / 64) {
-            case 1: return launch_hadamard64_rows<1>(xh, m, a_bits, xq, x_scale, s);
-            case 2: return launch_hadamard64_rows<2>(xh, m, a_bits, xq, x_scale, s);
-            case 3: return launch_hadamard64_rows<3>(xh, m, a_bits, xq, x_scale, s);
-            default: return launch_hadamard64(xh, m, k, a_bits, xq, x_scale, s);
-        }
-    }
+    if (x_dtype == HQ_F16 && had_block == 64 && k <= 64 * kMaxBlocks)
+        return launch_hadamard64(static_cast<const __half *>(x), m, k, a_bits, xq, x_scale, s);
     if (x_dtype == HQ_F16)
         return dispatch_block(static_cast<const __half *>(x), m, k, had_block, a_bits, out, x_scale, s);
     return dispatch_block(static_cast<const float *>(x), m, k, had_block, a_bits, out, x_scale, s);
