@@ -49,7 +49,7 @@ extern "C" hq_status hq_int_linear(const uint8_t *xq, const float *x_scale, cons
     hq_status st = check_common(xq, x_scale, wq, w_scale, bias, m, n, k, y, y_dtype);
     if (st != HQ_OK) return st;
     if (!fits_32bit(m, 1, n, 1, k)) return HQ_ERR_UNSUPPORTED;
-    GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(m), n, k, 1, 1, 0, 0, 0};
+    GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(m), n, k, 1, 1, 0, 0, 0, 1};
     return launch_gemm(a, 1, y_dtype, static_cast<hipStream_t>(stream));
 }
 
@@ -66,7 +66,7 @@ extern "C" hq_status hq_int_conv2d(const uint8_t *xq, const float *x_scale, cons
     if (st != HQ_OK) return st;
     if (r != s || (r != 1 && r != 3) || stride != 1 || pad != (r - 1) / 2) return HQ_ERR_UNSUPPORTED;
     if (!fits_32bit(pixels, w, c_out, r * s, c_in)) return HQ_ERR_UNSUPPORTED;
-    GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(pixels), c_out, c_in, h, w, 0, 0, 0};
+    GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(pixels), c_out, c_in, h, w, 0, 0, 0, 1};
     hipStream_t st_ = static_cast<hipStream_t>(stream);
     // A 3x3 layer with about one 64x64 output tile per CU or fewer cannot fill the machine with
     // whole tiles: it takes the kernel that also splits a tile's K range over waves.

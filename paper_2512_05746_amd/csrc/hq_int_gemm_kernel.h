@@ -46,6 +46,7 @@ struct GemmArgs {
     int n_co_tiles;
     uint32_t n_tiles;    // pixel tiles * channel tiles
     uint32_t xcds;       // 1: deal the tiles out per XCD (grid is a multiple of 8); 0: plain grid stride
+    uint32_t cus;        // compute units of the device (workgroups b and b + cus tend to share a CU)
 };
 
 namespace {
@@ -211,11 +212,11 @@ __device__ __forceinline__ void store16(float *dst, const float (&v)[16]) {
 // TAPS = 1 (linear / 1x1) or 9 (3x3, stride 1, pad 1).
 //
 // Persistent workgroups: the grid is sized to the machine and every workgroup
-// walks its tiles (output-channel tiles of one pixel tile are adjacent).  With
-// a.xcds set, workgroup b is taken to run on XCD b % 8 (the dispatcher deals
-// workgroups round-robin over the eight XCDs) and each XCD gets one contiguous
-// eighth of the tiles, so the activation rows a tile shares with its
-// neighbours are fetched into one L2 only.  All chunks of all tiles of a
+// walks a contiguous run of tiles (output-channel tiles of one pixel tile are
+// adjacent).  With a.xcds set, workgroup b is taken to run on XCD b % 8 (the
+// dispatcher deals workgroups round-robin over the eight XCDs) and each XCD
+// gets one contiguous eighth of the tiles, so the activation rows a tile shares
+// with its neighbours are fetched into one L2 only.  All chunks of all tiles of a
 // workgroup form ONE stream through the LDS stages, so the loads of the next
 // tile's first chunks are in flight while the current tile is finished and
 // written out, and the scale tables of the next tile are built during the
@@ -283,23 +284,28 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     const int kbytes = a.k >> 1;                 // packed bytes per (row, tap)
     const int chunks_per_tap = kbytes / ROWB;    // host guarantees divisibility
     const int total_chunks = TAPS * chunks_per_tap;
-    const uint32_t lds_a = lds_address(lds) + (wave_m * TM * 32 + lrow) * ROWB + (lhalf ^ ((lrow >> 3) & 1)) * 16;
-    const uint32_t lds_b = lds_a + (BCO + (wave_n * TN - wave_m * TM) * 32) * ROWB;
+    const uint32_t lds_row = lds_address(lds) + lrow * ROWB + (lhalf ^ ((lrow >> 3) & 1)) * 16;
+    const uint32_t lds_b = lds_row + (BCO + wave_n * TN * 32) * ROWB;
     const uint32_t lds_sx = lds_address(&s_sx[0][0][0]) + (wave_n * TN * 32 + lrow) * 4;
 
-    // ---- this workgroup's tiles: t_first, t_first + t_step, ... below t_end -----------------------
-    uint32_t t_first = blockIdx.x, t_step = gridDim.x, t_end = a.n_tiles;
+    // ---- this workgroup's tiles: a contiguous run t_first .. t_first + my_tiles - 1 -------------
+    // (consecutive tiles are the channel tiles of one pixel tile, so a run reuses the pixel
+    // rows from L2 and mixes full and cut-off channel tiles evenly over the workgroups)
+    uint32_t lo = 0, hi = a.n_tiles, j = blockIdx.x, sharers = gridDim.x;
     if (a.xcds) {   // gridDim.x is a multiple of XCDS then
         const uint32_t x = blockIdx.x % XCDS;
-        t_step = gridDim.x / XCDS;
-        t_first = static_cast<uint32_t>(static_cast<uint64_t>(a.n_tiles) * x / XCDS) + blockIdx.x / XCDS;
-        t_end = static_cast<uint32_t>(static_cast<uint64_t>(a.n_tiles) * (x + 1) / XCDS);
+        lo = static_cast<uint32_t>(static_cast<uint64_t>(a.n_tiles) * x / XCDS);
+        hi = static_cast<uint32_t>(static_cast<uint64_t>(a.n_tiles) * (x + 1) / XCDS);
+        j = blockIdx.x / XCDS;
+        sharers = gridDim.x / XCDS;
     }
-    if (t_first >= t_end) return;
-    const uint32_t my_tiles = (t_end - t_first + t_step - 1) / t_step;
+    const uint32_t per = (hi - lo) / sharers, rem = (hi - lo) % sharers;
+    const uint32_t t_first = lo + j * per + (j < rem ? j : rem);
+    const uint32_t my_tiles = per + (j < rem ? 1 : 0);
+    if (my_tiles == 0) return;
     const uint32_t stream_chunks = my_tiles * total_chunks;   // < 2^31, checked on the host
     auto tile_origin = [&](uint32_t k, int &co0, uint32_t &p0) {
-        const uint32_t tile = t_first + k * t_step;
+        const uint32_t tile = t_first + k;
         co0 = static_cast<int>(tile % a.n_co_tiles) * BCO;
         p0 = (tile / a.n_co_tiles) * BP;
     };
@@ -445,6 +451,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
         int co0; uint32_t p0;
         tile_origin(k, co0, p0);
         const int tb = k & 1;   // table set of this tile
+        // A wave whose channels or pixels all lie outside the tensor skips the arithmetic of the
+        // tile (it still loads, waits and meets the barriers).  In a tile that is cut off in the
+        // channel direction, every second workgroup (by residency round) rotates which waves own
+        // the existing channels, so that the SIMDs a CU's workgroups leave idle differ.
+        const int rot = (co0 + BCO > a.n && ((blockIdx.x / a.cus) & 1)) ? 1 : 0;
+        const int wm = (wave_m + rot) % WAVES_M;   // channel block of this wave in this tile
+        const bool active = co0 + wm * TM * 32 < a.n && p0 + wave_n * TN * 32 < a.pixels;
+        const uint32_t lds_a = lds_row + wm * TM * 32 * ROWB;
 
         v16i acc[TM][TN];
         float facc[TAPS > 1 ? TM : 1][TAPS > 1 ? TN : 1][16];
@@ -514,13 +528,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
             const bool tables_now = chunk == 0 && k + 1 < my_tiles;
             if (tables_now) load_scales(k + 1);
 
-            const uint32_t sa = lds_a + stage * STAGE_BYTES, sb = lds_b + stage * STAGE_BYTES;
-            Ops op[2];
-            read_packed<TM, TN, ROWB, 0>(op[0], sa, sb);
-            chunk_steps<0, KS, TM, TN, ROWB>(op, sa, sb, ch == 0, multiply);
+            if (active) {
+                const uint32_t sa = lds_a + stage * STAGE_BYTES, sb = lds_b + stage * STAGE_BYTES;
+                Ops op[2];
+                read_packed<TM, TN, ROWB, 0>(op[0], sa, sb);
+                chunk_steps<0, KS, TM, TN, ROWB>(op, sa, sb, ch == 0, multiply);
+            }
 
             if (++ch == chunks_per_tap) {
                 ch = 0;
+                if (active) {
                 // ---- end of a tap: fold the integer sums into the result ----------------------
                 if constexpr (OUT == kOutI32) {
                     int *yi = static_cast<int *>(a.y);
@@ -531,7 +548,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
                         const bool inside = (my_mask[tn] >> tap) & 1;   // also false for pixels >= pixels
 #pragma unroll
                         for (int tm = 0; tm < TM; ++tm) {
-                            const int cbase = co0 + (wave_m * TM + tm) * 32 + 16 * lhalf;
+                            const int cbase = co0 + (wm * TM + tm) * 32 + 16 * lhalf;
                             if (pix < a.pixels) {
                                 int *dst = yi + (static_cast<int64_t>(pix) * TAPS + tap) * a.n + cbase;
 #pragma unroll
@@ -551,6 +568,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
                             for (int r = 0; r < 16; ++r)
                                 facc[tm][tn][r] += s[tn] * static_cast<float>(acc[tm][tn][r]);
                 }
+                }
                 ++tap;
             }
             if (tables_now) {
@@ -562,11 +580,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
 
         // ---- dequantising epilogue -------------------------------------------------------------
         if constexpr (OUT != kOutI32) {
+            if (!active) continue;   // next tile
             Out *y = static_cast<Out *>(a.y);
             const bool vec_ok = (a.n & 15) == 0;
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm) {
-                const int clocal = (wave_m * TM + tm) * 32 + 16 * lhalf;
+                const int clocal = (wm * TM + tm) * 32 + 16 * lhalf;
                 const int cbase = co0 + clocal;
                 float swv[16], bv[16];
 #pragma unroll
@@ -614,6 +633,7 @@ hq_status launch_tile(GemmArgs a, hipStream_t stream) {
     const int64_t slots = static_cast<int64_t>(hq::compute_units()) * OCC;   // co-resident workgroups
     const unsigned grid = static_cast<unsigned>(tiles < slots ? tiles : slots);
     a.xcds = grid % 8 == 0 ? 1 : 0;
+    a.cus = static_cast<uint32_t>(hq::compute_units());
     hipLaunchKernelGGL((int_gemm_kernel<TM, TN, WAVES_M, WAVES_N, TAPS, OUT, KCH, NSTAGE, OCC>),
                        dim3(grid), dim3(64 * WAVES_M * WAVES_N), 0, stream, a);
     return hq::launch_status();
