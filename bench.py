@@ -53,6 +53,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     hq.load_library()
     torch.cuda.set_device(0)
+    props = torch.cuda.get_device_properties(0)
+    clock_khz = getattr(props, "clock_rate", 0) or 2400000
     layers = workloads.config_layers(CONFIG)
 
     # ---- resident inputs, offline weight preparation, preallocated outputs -----------------
@@ -219,6 +221,10 @@ def main():
             "launch": "hipgraph replay" if graph is not None else "eager",
         },
         "frac_int8_mfma_peak_wall": round(value / INT8_MFMA_PEAK_TOPS, 4),
+        "int8_mfma_peak_tops": {"nominal_2.4GHz": round(INT8_MFMA_PEAK_TOPS, 1),
+                                "at_queried_clock": round(props.multi_processor_count * 8192 * clock_khz * 1e3 / 1e12, 1),
+                                "queried_clock_mhz": round(clock_khz / 1e3), "compute_units": props.multi_processor_count,
+                                "fractions_use": "nominal"},
         "int_stage_tops_kernel_time": round(int_all_tops, 1),
         "frac_int8_mfma_peak_kernel_time": round(int_all_tops / INT8_MFMA_PEAK_TOPS, 4),
         "roofline": {
@@ -283,18 +289,24 @@ def cpu_baseline(layers):
         wq, sw, _ = oracle.quantize_weights(w, workloads.HAD_BLOCK, layer.w_bits)   # offline
         prepared.append((layer, x, wq, sw))
         ops += 2 * m * layer.n_out * layer.taps * layer.k_in
-    t0 = time.perf_counter()
+    t_act = t_int = 0.0
     for layer, x, wq, sw in prepared:
+        t0 = time.perf_counter()
         xq, sx, _ = oracle.act_hadamard_quant(x, workloads.HAD_BLOCK, layer.a_bits)
+        t1 = time.perf_counter()
         if layer.kind == "conv":
             oracle.int_conv2d(xq, sx, wq.reshape(layer.n_out, layer.ksize, layer.ksize, layer.k_in), sw,
                               None, stride=1, pad=layer.pad, want_acc=False)
         else:
             oracle.int_linear(xq, sx, wq[:, 0, :], sw, None)
-    dt = time.perf_counter() - t0
+        t2 = time.perf_counter()
+        t_act += t1 - t0
+        t_int += t2 - t1
+    dt = t_act + t_int
     cores = oracle.max_threads()
     return {"value": round(ops / dt / 1e12, 5), "unit": "TOP/s", "cores": cores, "kind": "oracle",
-            "seconds": round(dt, 2),
+            "seconds": round(dt, 2), "seconds_transform_quantise": round(t_act, 2),
+            "seconds_integer_dequant": round(t_int, 2),
             "sample": "one whole step: %d of 16 images of every layer of the sweep (%.1f GOP), fp64/int64 "
                       "oracle with OpenMP over rows" % (take, ops / 1e9)}
 

@@ -31,6 +31,13 @@
  *     y = s_w[co] * sum_t s_x[pixel_t] * acc_t  (+ bias).
  *   - Dequantisation is the product of scales of the Method section
  *     (Y ~ S_XH S_W (integer product)), in fp64, plus an optional bias.
+ *   - Static mode (the *_static functions): the activation scale is one
+ *     caller-supplied number for the whole tensor, as in the paper, where S
+ *     is a learned parameter kept per timestep (Background, "Model
+ *     Quantization"; Method, timestep-indexed quantisation parameters).  The
+ *     clamp is then active (codes reach -2^(b-1)), and a convolution is the
+ *     paper's form: ONE integer sum over all taps and input channels followed
+ *     by one product of scales, y = S_x s_w[co] * sum + bias.
  *
  * All arrays are row-major and owned by the caller.
  */
@@ -195,6 +202,67 @@ int hqo_int_conv2d(const int8_t *xq, const double *sx, const int8_t *wq, const d
             }
             if (y) {
                 double v = sw[co] * sum;
+                if (bias) v += bias[co];
+                y[(size_t)pix * cout + co] = v;
+            }
+        }
+    }
+    return 0;
+}
+
+/* Symmetric quantiser with one caller-supplied scale for the whole tensor
+ * (Background, "Model Quantization": X_int = clamp(round(X_fp / S), min, max)).
+ * xt: [count] -> q: [count] codes, t: [count] pre-rounding values xt / scale
+ * (t may be NULL).  scale must be positive and finite. */
+int hqo_quantize_static(const double *xt, int64_t count, int bits, double scale, int8_t *q, double *t)
+{
+    if (bits < 2 || bits > 8 || !(scale > 0.0) || isinf(scale)) return -1;
+    const double qmax = (double)((1 << (bits - 1)) - 1);
+    const double qmin = -(double)(1 << (bits - 1));
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < count; ++i) {
+        double v = xt[i] / scale;
+        if (t) t[i] = v;
+        double c = nearbyint(v); /* default rounding mode: ties to even */
+        if (c < qmin) c = qmin;
+        if (c > qmax) c = qmax;
+        q[i] = (int8_t)c;
+    }
+    return 0;
+}
+
+/* NHWC convolution with ONE activation scale for the tensor (Method,
+ * "Convolution": integer convolution of the codes, then the product of scales).
+ *   xq: [nb, h, w, cin], wq: [cout, r, s, cin], sw: [cout], bias: [cout] or NULL.
+ *   acc: [nb, ho, wo, cout] int64 = sum over taps and input channels, or NULL.
+ *   y:   [nb, ho, wo, cout] fp64 = sx * sw[co] * acc + bias, or NULL.
+ * A tap outside the image contributes code 0. */
+int hqo_int_conv2d_static(const int8_t *xq, double sx, const int8_t *wq, const double *sw,
+                          const double *bias, int nb, int h, int w, int cin, int cout,
+                          int r, int s, int stride, int pad, int64_t *acc, double *y)
+{
+    if (stride < 1 || pad < 0 || h + 2 * pad < r || w + 2 * pad < s) return -1;
+    const int ho = (h + 2 * pad - r) / stride + 1;
+    const int wo = (w + 2 * pad - s) / stride + 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t pix = 0; pix < (int64_t)nb * ho * wo; ++pix) {
+        const int b = (int)(pix / ((int64_t)ho * wo));
+        const int p = (int)((pix / wo) % ho);
+        const int q = (int)(pix % wo);
+        for (int co = 0; co < cout; ++co) {
+            int64_t a = 0;
+            for (int kr = 0; kr < r; ++kr)
+                for (int ks = 0; ks < s; ++ks) {
+                    const int ih = p * stride + kr - pad;
+                    const int iw = q * stride + ks - pad;
+                    if (ih < 0 || ih >= h || iw < 0 || iw >= w) continue;
+                    const int8_t *xr = xq + (((size_t)b * h + ih) * w + iw) * cin;
+                    const int8_t *wr = wq + (((size_t)co * r + kr) * s + ks) * cin;
+                    for (int c = 0; c < cin; ++c) a += (int64_t)xr[c] * (int64_t)wr[c];
+                }
+            if (acc) acc[(size_t)pix * cout + co] = a;
+            if (y) {
+                double v = sx * sw[co] * (double)a;
                 if (bias) v += bias[co];
                 y[(size_t)pix * cout + co] = v;
             }

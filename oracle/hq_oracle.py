@@ -59,6 +59,11 @@ def _load():
         lib.hqo_dequant_linear.restype = None
         lib.hqo_int_conv2d.argtypes = [c_i8p, c_dp, c_i8p, c_dp, c_dp] + [i32] * 9 + [c_i64p, c_dp]
         lib.hqo_int_conv2d.restype = i32
+        lib.hqo_quantize_static.argtypes = [c_dp, i64, i32, ctypes.c_double, c_i8p, c_dp]
+        lib.hqo_quantize_static.restype = i32
+        lib.hqo_int_conv2d_static.argtypes = ([c_i8p, ctypes.c_double, c_i8p, c_dp, c_dp] + [i32] * 9
+                                              + [c_i64p, c_dp])
+        lib.hqo_int_conv2d_static.restype = i32
         lib.hqo_max_threads.argtypes = []
         lib.hqo_max_threads.restype = i32
         _lib = lib
@@ -183,6 +188,60 @@ def int_conv2d(xq, sx, wq, sw, bias=None, stride: int = 1, pad: int = 0,
     y = np.empty((nb, ho, wo, cout), dtype=np.float64) if want_y else None
     rc = _load().hqo_int_conv2d(_i8p(xq), _dp(sx64), _i8p(wq), _dp(sw64), _dp(b64),
                                 nb, h, w, cin, cout, r, s, stride, pad, _i64p(acc), _dp(y))
+    if rc != 0:
+        raise ValueError("bad convolution shape")
+    if acc is not None:
+        assert np.abs(acc).max(initial=0) < 2**31
+    return acc, y
+
+
+# ---- static mode: one caller-supplied activation scale per tensor -----------------------------
+
+def quantize_static(xt, bits: int, scale: float):
+    """Symmetric quantiser with a given scale for the whole tensor; the clamp is active.
+    Returns (codes int8, t fp64)."""
+    x64 = _f64(xt)
+    q = np.empty(x64.shape, dtype=np.int8)
+    t = np.empty_like(x64)
+    rc = _load().hqo_quantize_static(_dp(x64), x64.size, bits, float(scale), _i8p(q), _dp(t))
+    if rc != 0:
+        raise ValueError("bad bit width %d or scale %r" % (bits, scale))
+    return q, t
+
+
+def act_hadamard_quant_static(x, block: int, bits: int, scale: float):
+    """Activation side with a static scale: x [..., K] -> (codes [..., K] int8, t fp64)."""
+    return quantize_static(block_hadamard(x, block), bits, scale)
+
+
+def int_linear_static(xq, sx: float, wq, sw, bias=None):
+    """Integer product, then y = sx * sw[n] * acc + bias.  Returns (acc int64, y fp64)."""
+    acc = int_gemm(xq, wq)
+    assert np.abs(acc).max(initial=0) < 2**31
+    y = float(sx) * _f64(sw).reshape(1, -1) * acc.astype(np.float64)
+    if bias is not None:
+        y = y + _f64(bias).reshape(1, -1)
+    return acc, y
+
+
+def int_conv2d_static(xq, sx: float, wq, sw, bias=None, stride: int = 1, pad: int = 0,
+                      want_acc: bool = True, want_y: bool = True):
+    """NHWC integer convolution with one sum over all taps and input channels.
+
+    Returns (acc int64 [N, Ho, Wo, Cout] or None, y fp64 [N, Ho, Wo, Cout] or None)."""
+    xq = np.ascontiguousarray(xq, dtype=np.int8)
+    wq = np.ascontiguousarray(wq, dtype=np.int8)
+    nb, h, w, cin = xq.shape
+    cout, r, s, cin2 = wq.shape
+    assert cin == cin2
+    ho = (h + 2 * pad - r) // stride + 1
+    wo = (w + 2 * pad - s) // stride + 1
+    sw64 = _f64(sw).reshape(cout)
+    b64 = _f64(bias).reshape(cout) if bias is not None else None
+    acc = np.empty((nb, ho, wo, cout), dtype=np.int64) if want_acc else None
+    y = np.empty((nb, ho, wo, cout), dtype=np.float64) if want_y else None
+    rc = _load().hqo_int_conv2d_static(_i8p(xq), float(sx), _i8p(wq), _dp(sw64), _dp(b64),
+                                       nb, h, w, cin, cout, r, s, stride, pad, _i64p(acc), _dp(y))
     if rc != 0:
         raise ValueError("bad convolution shape")
     if acc is not None:

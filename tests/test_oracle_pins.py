@@ -300,3 +300,80 @@ def test_workload_recipe_counts_and_determinism():
     x = workloads.make_x(t).astype(np.float64)
     rms = np.sqrt((x.reshape(-1, t.k_in) ** 2).mean(axis=0))
     assert (rms > 10).sum() == t.n_outlier_channels()
+
+
+# ---- static mode: one caller-supplied activation scale (the paper's learned, per-timestep S) ----
+
+def test_static_quantiser_clamps_and_rounds_to_even():
+    # Background, "Model Quantization": x_int = clamp(round(x / S), min, max)
+    s = 0.25
+    xt = np.array([0.0, 0.125, 0.375, -0.125, -0.375, 0.625, 1.74, 1.76, 5.0, -1.99, -2.2, -50.0, 1e9]) 
+    q, t = oracle.quantize_static(xt, 4, s)
+    #   t =     0    0.5    1.5    -0.5   -1.5    2.5   6.96  7.04   20    -7.96  -8.8   -200   4e9
+    assert q.tolist() == [0, 0, 2, 0, -2, 2, 7, 7, 7, -8, -8, -8, 7]
+    assert np.allclose(t, xt / s)
+    q3, _ = oracle.quantize_static(xt, 3, s)
+    assert q3.min() == -4 and q3.max() == 3
+    with pytest.raises(ValueError):
+        oracle.quantize_static(xt, 4, 0.0)
+
+
+def test_static_equals_dynamic_when_given_the_dynamic_scale():
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((1, 128)).astype(np.float32)
+    q_dyn, s_dyn, t_dyn = oracle.act_hadamard_quant(x, 64, 4)
+    q_st, t_st = oracle.act_hadamard_quant_static(x, 64, 4, float(s_dyn[0]))
+    assert np.array_equal(q_dyn, q_st) and np.array_equal(t_dyn, t_st)
+
+
+def test_static_one_hot_saturates_at_both_ends():
+    # e_i H = row i of H, entries +-1/8 for block 64: with S = 1/64 every |t| is 8, so the codes
+    # are +7 (clamped) where H is positive and -8 (reachable only with a static scale) elsewhere
+    x = np.zeros((1, 64)); x[0, 5] = 1.0
+    q, t = oracle.act_hadamard_quant_static(x, 64, 4, 1.0 / 64)
+    h = oracle.hadamard_raw(64)[5]
+    assert np.allclose(np.abs(t), 8.0)
+    assert np.array_equal(q[0], np.where(h > 0, 7, -8))
+
+
+def test_static_linear_is_matmul_of_dequantised_tensors():
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal((9, 128)); w = rng.standard_normal((5, 1, 128)) * 0.02
+    bias = rng.standard_normal(5) * 0.01
+    sx = 0.05
+    xq, _ = oracle.act_hadamard_quant_static(x, 64, 4, sx)
+    wq, sw, _ = oracle.quantize_weights(w, 64, 4)
+    acc, y = oracle.int_linear_static(xq, sx, wq[:, 0, :], sw, bias)
+    assert np.array_equal(acc, xq.astype(np.int64) @ wq[:, 0, :].astype(np.int64).T)
+    ref = (sx * xq.astype(np.float64)) @ (sw[:, None] * wq[:, 0, :]).T + bias
+    assert np.allclose(y, ref, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("ksize,stride,pad", [(3, 1, 1), (3, 2, 1), (3, 1, 0), (1, 1, 0)])
+def test_static_conv_vs_brute_force_and_library(ksize, stride, pad):
+    rng = np.random.default_rng(13 + ksize + stride + pad)
+    nb, h, w, cin, cout = 2, 5, 6, 8, 3
+    xq = rng.integers(-8, 8, (nb, h, w, cin)).astype(np.int8)
+    wq = rng.integers(-8, 8, (cout, ksize, ksize, cin)).astype(np.int8)
+    sw = rng.uniform(0.5, 1.5, cout); bias = rng.standard_normal(cout); sx = 0.37
+    acc, y = oracle.int_conv2d_static(xq, sx, wq, sw, bias, stride=stride, pad=pad)
+    ho, wo = acc.shape[1], acc.shape[2]
+    brute = np.zeros((nb, ho, wo, cout), dtype=np.int64)
+    for b in range(nb):
+        for p in range(ho):
+            for q in range(wo):
+                for co in range(cout):
+                    for kr in range(ksize):
+                        for ks in range(ksize):
+                            ih, iw = p * stride + kr - pad, q * stride + ks - pad
+                            if 0 <= ih < h and 0 <= iw < w:
+                                for c in range(cin):
+                                    brute[b, p, q, co] += int(xq[b, ih, iw, c]) * int(wq[co, kr, ks, c])
+    assert np.array_equal(acc, brute)
+    # one sum over taps and channels = the per-tap sums of the dynamic-scale oracle added up
+    acc_t, _ = oracle.int_conv2d(xq, np.full((nb, h, w), sx), wq, sw, bias, stride=stride, pad=pad)
+    assert np.array_equal(acc, acc_t.sum(axis=3))
+    xh = torch.from_numpy(sx * xq.astype(np.float64)).permute(0, 3, 1, 2)
+    wh = torch.from_numpy(sw[:, None, None, None] * wq).permute(0, 3, 1, 2)
+    ref = torch.nn.functional.conv2d(xh, wh, torch.from_numpy(bias), stride=stride, padding=pad)
+    assert np.allclose(y, ref.permute(0, 2, 3, 1).numpy(), rtol=1e-12, atol=1e-12)
