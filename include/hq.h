@@ -131,6 +131,51 @@ hq_status hq_int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *
                         int c_in, int c_out, int r, int s, int stride, int pad,
                         void *y, hq_dtype y_dtype, void *stream);
 
+/*
+ * ---- Static activation scale -------------------------------------------------
+ *
+ * The paper's own quantiser uses a learned scale S that is a property of the
+ * tensor, one per denoising timestep (Background, "Model Quantization"; Method,
+ * timestep-indexed quantisation parameters), not a value derived from the data.
+ * The three calls below are the layer with such a scale: x_scale is a DEVICE
+ * pointer to ONE positive fp32 (4-byte aligned) that the caller selects per
+ * timestep; it is read when the kernel runs, so a captured launch can be replayed
+ * with another value in that memory.  Everything else is as in the dynamic calls.
+ */
+
+/*
+ * Block Hadamard over the channel axis, then xq = clamp(rne((x H) / x_scale[0]),
+ * -2^(a_bits-1), 2^(a_bits-1) - 1).  With a given scale the clamp is active and
+ * the most negative code is reachable.  Writes xq [m, k/2] only.
+ */
+hq_status hq_act_hadamard_quant_static(const void *x, hq_dtype x_dtype, int64_t m, int k,
+                                       int had_block, int a_bits, const float *x_scale,
+                                       uint8_t *xq, void *stream);
+
+/*
+ * y[i, j] = acc[i, j] * x_scale[0] * w_scale[j] + bias[j], acc as in hq_int_linear.
+ */
+hq_status hq_int_linear_static(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
+                               const float *w_scale, const void *bias, int64_t m, int n, int k,
+                               void *y, hq_dtype y_dtype, void *stream);
+
+/*
+ * With one scale for the whole activation tensor a convolution is the paper's
+ * form (Method, "Convolution"): ONE integer sum over all taps and input channels,
+ * then one product of scales:
+ *
+ *   acc[b, p, q, co] = sum_{r, s, ci} xq[b, p + r - pad, q + s - pad, ci] * wq[co, r, s, ci]
+ *   y[b, p, q, co]   = acc * x_scale[0] * w_scale[co] + bias[co]
+ *
+ * A tap outside the image contributes 0.  Shapes and the built geometries are
+ * those of hq_int_conv2d; c_in * R * S < 131072.  y_dtype == HQ_I32 writes acc,
+ * [nb, h, w, c_out].
+ */
+hq_status hq_int_conv2d_static(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
+                               const float *w_scale, const void *bias, int nb, int h, int w,
+                               int c_in, int c_out, int r, int s, int stride, int pad,
+                               void *y, hq_dtype y_dtype, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -2,8 +2,11 @@
 from .binding import (  # noqa: F401
     HqError,
     hq_act_hadamard_quant,
+    hq_act_hadamard_quant_static,
     hq_int_conv2d,
+    hq_int_conv2d_static,
     hq_int_linear,
+    hq_int_linear_static,
     hq_quantize_weights,
     load_library,
     status_string,

@@ -19,7 +19,8 @@ HQ_F16, HQ_F32, HQ_I32 = 0, 1, 2
 _DTYPES = {torch.float16: HQ_F16, torch.float32: HQ_F32, torch.int32: HQ_I32}
 
 SYMBOLS = ("hq_status_string", "hq_quantize_weights", "hq_act_hadamard_quant",
-           "hq_int_linear", "hq_int_conv2d")
+           "hq_int_linear", "hq_int_conv2d", "hq_act_hadamard_quant_static",
+           "hq_int_linear_static", "hq_int_conv2d_static")
 
 
 class HqError(RuntimeError):
@@ -47,6 +48,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.hq_act_hadamard_quant.argtypes = [vp, i32, i64, i32, i32, i32, vp, vp, vp]
     lib.hq_int_linear.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, vp, i32, vp]
     lib.hq_int_conv2d.argtypes = [vp] * 5 + [i32] * 9 + [vp, i32, vp]
+    lib.hq_act_hadamard_quant_static.argtypes = [vp, i32, i64, i32, i32, i32, vp, vp, vp]
+    lib.hq_int_linear_static.argtypes = lib.hq_int_linear.argtypes
+    lib.hq_int_conv2d_static.argtypes = lib.hq_int_conv2d.argtypes
     for name in SYMBOLS[1:]:
         getattr(lib, name).restype = i32
     _lib = lib
@@ -146,6 +150,65 @@ def hq_int_conv2d(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torch.T
     else:
         y = torch.empty((nb, h, w, cout), dtype=y_dtype, device=xq.device)
     _check("hq_int_conv2d", load_library().hq_int_conv2d(
+        _ptr(xq), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), nb, h, w, cb * 2, cout,
+        ksize, ksize, stride, pad, _ptr(y), _DTYPES[y_dtype], _stream()))
+    return y
+
+
+def _scalar(x_scale: torch.Tensor) -> torch.Tensor:
+    if x_scale is None or not x_scale.is_cuda or x_scale.dtype != torch.float32 or x_scale.numel() != 1:
+        raise ValueError("x_scale must be a device tensor holding one float32")
+    return x_scale
+
+
+def hq_act_hadamard_quant_static(x: torch.Tensor, x_scale: torch.Tensor, had_block: int = 64,
+                                 a_bits: int = 4, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """x [..., k] fp16/fp32, x_scale one fp32 on the device -> xq uint8 [..., k/2]."""
+    _dev(x, "x")
+    k = x.shape[-1]
+    m = x.numel() // k
+    xq = out if out is not None else torch.empty(x.shape[:-1] + (k // 2,), dtype=torch.uint8, device=x.device)
+    _check("hq_act_hadamard_quant_static", load_library().hq_act_hadamard_quant_static(
+        _ptr(x), _DTYPES[x.dtype], m, k, had_block, a_bits, _ptr(_scalar(x_scale)), _ptr(xq), _stream()))
+    return xq
+
+
+def hq_int_linear_static(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torch.Tensor,
+                         w_scale: Optional[torch.Tensor], bias: Optional[torch.Tensor] = None,
+                         y_dtype: torch.dtype = torch.float16, out: Optional[torch.Tensor] = None
+                         ) -> torch.Tensor:
+    """As hq_int_linear with one activation scale (a device tensor holding one float32)."""
+    _dev(xq, "xq"), _dev(wq, "wq")
+    m, kb = xq.shape
+    n = wq.shape[0]
+    if wq.numel() != n * kb:
+        raise ValueError("wq does not match xq in k")
+    if bias is not None and bias.dtype != y_dtype:
+        raise ValueError("bias must have the output dtype")
+    y = out if out is not None else torch.empty((m, n), dtype=y_dtype, device=xq.device)
+    _check("hq_int_linear_static", load_library().hq_int_linear_static(
+        _ptr(xq), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), m, n, kb * 2,
+        _ptr(y), _DTYPES[y_dtype], _stream()))
+    return y
+
+
+def hq_int_conv2d_static(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torch.Tensor,
+                         w_scale: Optional[torch.Tensor], bias: Optional[torch.Tensor] = None,
+                         ksize: int = 3, stride: int = 1, pad: Optional[int] = None,
+                         y_dtype: torch.dtype = torch.float16, out: Optional[torch.Tensor] = None
+                         ) -> torch.Tensor:
+    """As hq_int_conv2d with one activation scale; y_dtype int32 returns the sums over all
+    taps and input channels, [nb, h, w, cout]."""
+    _dev(xq, "xq"), _dev(wq, "wq")
+    nb, h, w, cb = xq.shape
+    cout = wq.shape[0]
+    if wq.numel() != cout * ksize * ksize * cb:
+        raise ValueError("wq does not match xq / ksize")
+    if bias is not None and bias.dtype != y_dtype:
+        raise ValueError("bias must have the output dtype")
+    pad = (ksize - 1) // 2 if pad is None else pad
+    y = out if out is not None else torch.empty((nb, h, w, cout), dtype=y_dtype, device=xq.device)
+    _check("hq_int_conv2d_static", load_library().hq_int_conv2d_static(
         _ptr(xq), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), nb, h, w, cb * 2, cout,
         ksize, ksize, stride, pad, _ptr(y), _DTYPES[y_dtype], _stream()))
     return y

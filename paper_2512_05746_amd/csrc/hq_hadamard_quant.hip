@@ -123,6 +123,7 @@ struct RowQuantArgs {
     int max_group;      // power of two <= 16 dividing `chunks`
     float qmin, qmax;
     float norm;         // 2^{-LOGB/2}
+    const float *given;   // static mode: one scale for the whole tensor (device); NULL = per-row abs-max
 };
 
 // Rows short enough that a workgroup keeps several whole rows in registers.
@@ -169,9 +170,9 @@ __global__ __launch_bounds__(kThreads) void rowquant_small(const T *__restrict__
         const int slot = tid + kThreads * u;
         if (slot < nslots) {
             const float amax = __uint_as_float(s_max[rl[u]]);
-            const float inv = amax > 0.f ? a.qmax / amax : 0.f;
+            const float inv = a.given ? a.norm / a.given[0] : (amax > 0.f ? a.qmax / amax : 0.f);
             xq[chunk0 + slot] = quant_pack8(v[u], inv, a.qmin, a.qmax);
-            if (slot == rl[u] * a.chunks)
+            if (!a.given && slot == rl[u] * a.chunks)
                 scale[row0 + rl[u]] = amax > 0.f ? (amax * a.norm) / a.qmax : 1.0f;
         }
     }
@@ -205,7 +206,7 @@ __global__ __launch_bounds__(kThreads) void rowquant_large(const T *__restrict__
     atomicMax(&s_max, __float_as_uint(amax));
     __syncthreads();
     amax = __uint_as_float(s_max);
-    const float inv = amax > 0.f ? a.qmax / amax : 0.f;
+    const float inv = a.given ? a.norm / a.given[0] : (amax > 0.f ? a.qmax / amax : 0.f);
 
     for (int c = tid; c < rounded; c += kThreads) {
         float v[8];
@@ -218,7 +219,7 @@ __global__ __launch_bounds__(kThreads) void rowquant_large(const T *__restrict__
         hadamard_raw<LOGB>(v, lane);
         if (c < a.chunks) xq[chunk0 + c] = quant_pack8(v, inv, a.qmin, a.qmax);
     }
-    if (tid == 0) scale[blockIdx.x] = amax > 0.f ? (amax * a.norm) / a.qmax : 1.0f;
+    if (tid == 0 && !a.given) scale[blockIdx.x] = amax > 0.f ? (amax * a.norm) / a.qmax : 1.0f;
 }
 
 // ---- fp16 input, block 64, rows of up to 1024 channels: the transform on the matrix cores ------
@@ -261,10 +262,23 @@ __device__ __forceinline__ uint32_t pack8_magic(const float *v, float inv) {
     return (w - kMagicSum) ^ 0x88888888u;
 }
 
+// The same with the clamp of a given scale: v is limited to [lo, hi] = [qmin / inv, qmax / inv]
+// first (rounding is monotonic and the limits are integers, so clamp and round commute).
+__device__ __forceinline__ uint32_t pack8_magic_clamped(const float *v, float inv, float lo, float hi) {
+    float c[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) c[i] = fminf(fmaxf(v[i], lo), hi);
+    return pack8_magic(c, inv);
+}
+
+// STATIC: the scale is given (one for the tensor): no abs-max, no exchange, clamp active, no
+// scale output; `given` points to it.
+template <bool STATIC>
 __global__ __launch_bounds__(64 * kMaxBlocks) void hadamard64_quant_f16(const __half *__restrict__ x, int64_t m,
                                                                         int k, float qmax,
                                                                         uint8_t *__restrict__ xq,
-                                                                        float *__restrict__ scale) {
+                                                                        float *__restrict__ scale,
+                                                                        const float *__restrict__ given) {
     __shared__ float s_amax[2][kMaxBlocks][16];
     const int lane = threadIdx.x & 63;
     const int blk = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // 64-channel block of this wave
@@ -327,23 +341,33 @@ __global__ __launch_bounds__(64 * kMaxBlocks) void hadamard64_quant_f16(const __
                 amax = fmaxf(amax, fabsf(acc[r]));
             }
         }
-        // the token's other three K slices of this block, then its other blocks
-        amax = fmaxf(amax, __shfl_xor(amax, 16));
-        amax = fmaxf(amax, __shfl_xor(amax, 32));
-        if (nblk > 1) {
-            if (q == 0) s_amax[set][blk][tok] = amax;
-            __syncthreads();
-            for (int w = 0; w < nblk; ++w) amax = fmaxf(amax, s_amax[set][w][tok]);
-        }
-
         const int64_t token = grp * 16 + tok;
-        if (token < m) {
-            const float inv = amax > 0.f ? qmax / amax : 0.f;
-            if (blk == 0 && q == 0) scale[token] = amax > 0.f ? (amax * 0.125f) / qmax : 1.0f;
-            uint2 w;
-            w.x = pack8_magic(v, inv);
-            w.y = pack8_magic(v + 8, inv);
-            *reinterpret_cast<uint2 *>(xq + token * (k >> 1) + 32 * blk + 8 * q) = w;
+        if constexpr (STATIC) {
+            if (token < m) {
+                const float inv = 0.125f / given[0];   // the sums are 8 x the orthonormal transform
+                const float lo = (-qmax - 1.0f) / inv, hi = qmax / inv;
+                uint2 w;
+                w.x = pack8_magic_clamped(v, inv, lo, hi);
+                w.y = pack8_magic_clamped(v + 8, inv, lo, hi);
+                *reinterpret_cast<uint2 *>(xq + token * (k >> 1) + 32 * blk + 8 * q) = w;
+            }
+        } else {
+            // the token's other three K slices of this block, then its other blocks
+            amax = fmaxf(amax, __shfl_xor(amax, 16));
+            amax = fmaxf(amax, __shfl_xor(amax, 32));
+            if (nblk > 1) {
+                if (q == 0) s_amax[set][blk][tok] = amax;
+                __syncthreads();
+                for (int w = 0; w < nblk; ++w) amax = fmaxf(amax, s_amax[set][w][tok]);
+            }
+            if (token < m) {
+                const float inv = amax > 0.f ? qmax / amax : 0.f;
+                if (blk == 0 && q == 0) scale[token] = amax > 0.f ? (amax * 0.125f) / qmax : 1.0f;
+                uint2 w;
+                w.x = pack8_magic(v, inv);
+                w.y = pack8_magic(v + 8, inv);
+                *reinterpret_cast<uint2 *>(xq + token * (k >> 1) + 32 * blk + 8 * q) = w;
+            }
         }
         b[0] = bn[0];
         b[1] = bn[1];
@@ -351,7 +375,7 @@ __global__ __launch_bounds__(64 * kMaxBlocks) void hadamard64_quant_f16(const __
 }
 
 hq_status launch_hadamard64(const __half *x, int64_t m, int k, int bits, uint8_t *xq, float *scale,
-                            hipStream_t stream) {
+                            const float *given, hipStream_t stream) {
     const float qmax = static_cast<float>((1 << (bits - 1)) - 1);
     const int nblk = k / 64;
     const int64_t groups = (m + 15) / 16;
@@ -359,15 +383,20 @@ hq_status launch_hadamard64(const __half *x, int64_t m, int k, int bits, uint8_t
     const int64_t cap = static_cast<int64_t>(hq::compute_units()) * (32 / nblk > 0 ? 32 / nblk : 1);
     const int64_t rounds = (groups + cap - 1) / cap;          // groups per workgroup
     const int64_t grid = (groups + rounds - 1) / rounds;      // the same number for (almost) all of them
-    hipLaunchKernelGGL(hadamard64_quant_f16, dim3(static_cast<unsigned>(grid)), dim3(64 * nblk), 0, stream, x, m,
-                       k, qmax, xq, scale);
+    if (given)
+        hipLaunchKernelGGL(hadamard64_quant_f16<true>, dim3(static_cast<unsigned>(grid)), dim3(64 * nblk), 0,
+                           stream, x, m, k, qmax, xq, scale, given);
+    else
+        hipLaunchKernelGGL(hadamard64_quant_f16<false>, dim3(static_cast<unsigned>(grid)), dim3(64 * nblk), 0,
+                           stream, x, m, k, qmax, xq, scale, given);
     return hq::launch_status();
 }
 
 template <typename T, int LOGB>
 hq_status launch_rowquant(const T *x, int64_t m, int row_len, int bits, uint32_t *xq, float *scale,
-                          hipStream_t stream) {
+                          const float *given, hipStream_t stream) {
     RowQuantArgs a;
+    a.given = given;
     a.m = m;
     a.chunks = row_len / 8;
     a.inv_chunks = a.chunks >= 2 ? static_cast<uint32_t>(((1ull << 32) + a.chunks - 1) / a.chunks) : 0u;
@@ -401,16 +430,16 @@ hq_status launch_rowquant(const T *x, int64_t m, int row_len, int bits, uint32_t
 
 template <typename T>
 hq_status dispatch_block(const T *x, int64_t m, int row_len, int had_block, int bits, uint32_t *xq,
-                         float *scale, hipStream_t stream) {
+                         float *scale, const float *given, hipStream_t stream) {
     switch (hq::ilog2(had_block)) {
-        case 0: return launch_rowquant<T, 0>(x, m, row_len, bits, xq, scale, stream);
-        case 1: return launch_rowquant<T, 1>(x, m, row_len, bits, xq, scale, stream);
-        case 2: return launch_rowquant<T, 2>(x, m, row_len, bits, xq, scale, stream);
-        case 3: return launch_rowquant<T, 3>(x, m, row_len, bits, xq, scale, stream);
-        case 4: return launch_rowquant<T, 4>(x, m, row_len, bits, xq, scale, stream);
-        case 5: return launch_rowquant<T, 5>(x, m, row_len, bits, xq, scale, stream);
-        case 6: return launch_rowquant<T, 6>(x, m, row_len, bits, xq, scale, stream);
-        case 7: return launch_rowquant<T, 7>(x, m, row_len, bits, xq, scale, stream);
+        case 0: return launch_rowquant<T, 0>(x, m, row_len, bits, xq, scale, given, stream);
+        case 1: return launch_rowquant<T, 1>(x, m, row_len, bits, xq, scale, given, stream);
+        case 2: return launch_rowquant<T, 2>(x, m, row_len, bits, xq, scale, given, stream);
+        case 3: return launch_rowquant<T, 3>(x, m, row_len, bits, xq, scale, given, stream);
+        case 4: return launch_rowquant<T, 4>(x, m, row_len, bits, xq, scale, given, stream);
+        case 5: return launch_rowquant<T, 5>(x, m, row_len, bits, xq, scale, given, stream);
+        case 6: return launch_rowquant<T, 6>(x, m, row_len, bits, xq, scale, given, stream);
+        case 7: return launch_rowquant<T, 7>(x, m, row_len, bits, xq, scale, given, stream);
         default: return HQ_ERR_SHAPE;
     }
 }
@@ -431,18 +460,36 @@ hq_status check_rowquant(const void *x, hq_dtype dt, int64_t m, int k, int64_t r
 
 }  // namespace
 
+namespace {
+
+// Activation path; given == NULL: per-token abs-max scales written to x_scale, else one static scale.
+hq_status act_hadamard_quant(const void *x, hq_dtype x_dtype, int64_t m, int k, int had_block, int a_bits,
+                             uint8_t *xq, float *x_scale, const float *given, void *stream) {
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint32_t *out = reinterpret_cast<uint32_t *>(xq);
+    if (x_dtype == HQ_F16 && had_block == 64 && k <= 64 * kMaxBlocks)
+        return launch_hadamard64(static_cast<const __half *>(x), m, k, a_bits, xq, x_scale, given, s);
+    if (x_dtype == HQ_F16)
+        return dispatch_block(static_cast<const __half *>(x), m, k, had_block, a_bits, out, x_scale, given, s);
+    return dispatch_block(static_cast<const float *>(x), m, k, had_block, a_bits, out, x_scale, given, s);
+}
+
+}  // namespace
+
 extern "C" hq_status hq_act_hadamard_quant(const void *x, hq_dtype x_dtype, int64_t m, int k,
                                            int had_block, int a_bits, uint8_t *xq, float *x_scale,
                                            void *stream) {
     hq_status st = check_rowquant(x, x_dtype, m, k, k, had_block, a_bits, xq, x_scale);
     if (st != HQ_OK) return st;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    uint32_t *out = reinterpret_cast<uint32_t *>(xq);
-    if (x_dtype == HQ_F16 && had_block == 64 && k <= 64 * kMaxBlocks)
-        return launch_hadamard64(static_cast<const __half *>(x), m, k, a_bits, xq, x_scale, s);
-    if (x_dtype == HQ_F16)
-        return dispatch_block(static_cast<const __half *>(x), m, k, had_block, a_bits, out, x_scale, s);
-    return dispatch_block(static_cast<const float *>(x), m, k, had_block, a_bits, out, x_scale, s);
+    return act_hadamard_quant(x, x_dtype, m, k, had_block, a_bits, xq, x_scale, nullptr, stream);
+}
+
+extern "C" hq_status hq_act_hadamard_quant_static(const void *x, hq_dtype x_dtype, int64_t m, int k,
+                                                  int had_block, int a_bits, const float *x_scale,
+                                                  uint8_t *xq, void *stream) {
+    hq_status st = check_rowquant(x, x_dtype, m, k, k, had_block, a_bits, xq, x_scale);
+    if (st != HQ_OK) return st;
+    return act_hadamard_quant(x, x_dtype, m, k, had_block, a_bits, xq, nullptr, x_scale, stream);
 }
 
 extern "C" hq_status hq_quantize_weights(const void *w, hq_dtype w_dtype, int n_out, int taps, int k_in,
@@ -456,8 +503,8 @@ extern "C" hq_status hq_quantize_weights(const void *w, hq_dtype w_dtype, int n_
     uint32_t *out = reinterpret_cast<uint32_t *>(wq);
     const int len = static_cast<int>(row_len);
     if (w_dtype == HQ_F16)
-        return dispatch_block(static_cast<const __half *>(w), n_out, len, had_block, w_bits, out, w_scale, s);
-    return dispatch_block(static_cast<const float *>(w), n_out, len, had_block, w_bits, out, w_scale, s);
+        return dispatch_block(static_cast<const __half *>(w), n_out, len, had_block, w_bits, out, w_scale, nullptr, s);
+    return dispatch_block(static_cast<const float *>(w), n_out, len, had_block, w_bits, out, w_scale, nullptr, s);
 }
 
 extern "C" const char *hq_status_string(hq_status s) {

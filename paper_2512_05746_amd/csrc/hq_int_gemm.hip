@@ -43,20 +43,21 @@ hq_status check_common(const uint8_t *xq, const float *x_scale, const uint8_t *w
 
 }  // namespace
 
-extern "C" hq_status hq_int_linear(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
-                                   const float *w_scale, const void *bias, int64_t m, int n, int k,
-                                   void *y, hq_dtype y_dtype, void *stream) {
+namespace {
+
+hq_status int_linear(const uint8_t *xq, const float *x_scale, const uint8_t *wq, const float *w_scale,
+                     const void *bias, int64_t m, int n, int k, void *y, hq_dtype y_dtype, int sx_static,
+                     void *stream) {
     hq_status st = check_common(xq, x_scale, wq, w_scale, bias, m, n, k, y, y_dtype);
     if (st != HQ_OK) return st;
     if (!fits_32bit(m, 1, n, 1, k)) return HQ_ERR_UNSUPPORTED;
-    GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(m), n, k, 1, 1, 0, 0, 0, 1};
+    GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(m), n, k, 1, 1, 0, 0, 0, 1, sx_static};
     return launch_gemm(a, 1, y_dtype, static_cast<hipStream_t>(stream));
 }
 
-extern "C" hq_status hq_int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
-                                   const float *w_scale, const void *bias, int nb, int h, int w, int c_in,
-                                   int c_out, int r, int s, int stride, int pad, void *y, hq_dtype y_dtype,
-                                   void *stream) {
+hq_status int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq, const float *w_scale,
+                     const void *bias, int nb, int h, int w, int c_in, int c_out, int r, int s, int stride,
+                     int pad, void *y, hq_dtype y_dtype, int sx_static, void *stream) {
     if (nb <= 0 || h <= 0 || w <= 0 || r <= 0 || s <= 0 || stride <= 0 || pad < 0) {
         if (!xq || !wq || !y) return HQ_ERR_NULL;
         return HQ_ERR_SHAPE;
@@ -66,12 +67,46 @@ extern "C" hq_status hq_int_conv2d(const uint8_t *xq, const float *x_scale, cons
     if (st != HQ_OK) return st;
     if (r != s || (r != 1 && r != 3) || stride != 1 || pad != (r - 1) / 2) return HQ_ERR_UNSUPPORTED;
     if (!fits_32bit(pixels, w, c_out, r * s, c_in)) return HQ_ERR_UNSUPPORTED;
-    GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(pixels), c_out, c_in, h, w, 0, 0, 0, 1};
+    // one sum over all taps: 256 * (64 per product) * (codes per sum) must stay below 2^31
+    if (sx_static && static_cast<int64_t>(c_in) * r * s >= 131072) return HQ_ERR_SHAPE;
+    GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(pixels), c_out, c_in, h, w, 0, 0, 0, 1,
+               sx_static};
     hipStream_t st_ = static_cast<hipStream_t>(stream);
     // A 3x3 layer with about one 64x64 output tile per CU or fewer cannot fill the machine with
     // whole tiles: it takes the kernel that also splits a tile's K range over waves.
     const int64_t tiles64 = ((pixels + 63) / 64) * ((c_out + 63) / 64);
-    if (r == 3 && c_in % 192 == 0 && y_dtype != HQ_I32 && tiles64 * 4 <= 5 * static_cast<int64_t>(hq::compute_units()))
+    if (r == 3 && !sx_static && c_in % 192 == 0 && y_dtype != HQ_I32 &&
+        tiles64 * 4 <= 5 * static_cast<int64_t>(hq::compute_units()))
         return hq_conv3x3_wave_launch(a, y_dtype, st_);
     return launch_gemm(a, r * s, y_dtype, st_);
+}
+
+}  // namespace
+
+extern "C" hq_status hq_int_linear(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
+                                   const float *w_scale, const void *bias, int64_t m, int n, int k,
+                                   void *y, hq_dtype y_dtype, void *stream) {
+    return int_linear(xq, x_scale, wq, w_scale, bias, m, n, k, y, y_dtype, 0, stream);
+}
+
+extern "C" hq_status hq_int_linear_static(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
+                                          const float *w_scale, const void *bias, int64_t m, int n, int k,
+                                          void *y, hq_dtype y_dtype, void *stream) {
+    return int_linear(xq, x_scale, wq, w_scale, bias, m, n, k, y, y_dtype, 1, stream);
+}
+
+extern "C" hq_status hq_int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
+                                   const float *w_scale, const void *bias, int nb, int h, int w, int c_in,
+                                   int c_out, int r, int s, int stride, int pad, void *y, hq_dtype y_dtype,
+                                   void *stream) {
+    return int_conv2d(xq, x_scale, wq, w_scale, bias, nb, h, w, c_in, c_out, r, s, stride, pad, y, y_dtype, 0,
+                      stream);
+}
+
+extern "C" hq_status hq_int_conv2d_static(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
+                                          const float *w_scale, const void *bias, int nb, int h, int w,
+                                          int c_in, int c_out, int r, int s, int stride, int pad, void *y,
+                                          hq_dtype y_dtype, void *stream) {
+    return int_conv2d(xq, x_scale, wq, w_scale, bias, nb, h, w, c_in, c_out, r, s, stride, pad, y, y_dtype, 1,
+                      stream);
 }

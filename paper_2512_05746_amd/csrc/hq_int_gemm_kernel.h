@@ -47,6 +47,8 @@ struct GemmArgs {
     uint32_t n_tiles;    // pixel tiles * channel tiles
     uint32_t xcds;       // 1: deal the tiles out per XCD (grid is a multiple of 8); 0: plain grid stride
     uint32_t cus;        // compute units of the device (workgroups b and b + cus tend to share a CU)
+    int sx_static;       // sx is ONE scale for the whole activation tensor (a 3x3 convolution then keeps
+                         // one integer sum over all taps)
 };
 
 namespace {
@@ -55,6 +57,10 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kOutF16 = 0, kOutF32 = 1, kOutI32 = 2;
+// What a kernel instance computes: a linear layer / 1x1 convolution; a 3x3 convolution whose
+// integer sums are kept per tap (every input pixel has its own scale); a 3x3 convolution with
+// one integer sum over all taps (one scale for the tensor).
+constexpr int kLinear = 0, kConvPerTap = 1, kConvSum = 2;
 
 
 // Output channel handled by row i of a 32-row MFMA tile.  Chosen so that the
@@ -112,6 +118,10 @@ __device__ __forceinline__ void lds_read_f32(float &dst, uint32_t addr) {
 
 // Ties a register to the point after the preceding hand-placed wait.
 __device__ __forceinline__ void pin(v4i &v) { asm volatile("" : "+v"(v)); }
+
+// Source of the activation rows of taps that fall outside the image when all taps share one
+// integer sum (they must then contribute zeros, not merely be ignored).
+__device__ __attribute__((aligned(128))) const uint8_t g_zero_row[128] = {0};
 
 // Bit t set: tap t = (r, s) of a 3x3 / pad 1 window around pixel `pix` lies inside its image.
 template <int TAPS>
@@ -242,8 +252,12 @@ __device__ __forceinline__ void store16(float *dst, const float (&v)[16]) {
 // pixels >= pixels) and taps outside the image read some other in-bounds row
 // instead of zeros: their sums are never stored, and a tap outside the image
 // has scale 0 (int32 output: written as 0).
-template <int TM, int TN, int WAVES_M, int WAVES_N, int TAPS, int OUT, int KCH, int NSTAGE, int OCC>
+template <int TM, int TN, int WAVES_M, int WAVES_N, int KIND, int OUT, int KCH, int NSTAGE, int OCC>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(GemmArgs a) {
+    constexpr int TAPS = KIND == kLinear ? 1 : 9;
+    constexpr bool PER_TAP = KIND == kConvPerTap;   // per-tap sums, combined in fp32 with per-pixel scales
+    constexpr bool SUM = KIND == kConvSum;          // one sum over all taps; padding taps load zeros
+    constexpr int STAPS = PER_TAP ? TAPS : 1;       // rows of the activation-scale table
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int NT = 64 * NW;
     constexpr int BCO = 32 * TM * WAVES_M;   // output channels per workgroup
@@ -262,7 +276,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     static_assert(TM + TN < 16, "lgkmcnt range");
     static_assert(BP <= NT && BCO <= NT, "one table entry per thread");
     constexpr int STAGE_BYTES = (BCO + BP) * ROWB;
-    constexpr int SX_PER_T = (TAPS * BP + NT - 1) / NT;   // scale-table entries per thread
+    constexpr int SX_PER_T = (STAPS * BP + NT - 1) / NT;   // scale-table entries per thread
     constexpr uint32_t XCDS = 8;
     using Out = typename OutT<OUT>::type;
     using Ops = Packed<TM, TN>;
@@ -270,7 +284,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     // [stage][operand][row][ROWB bytes]
     __shared__ __attribute__((aligned(16))) uint8_t lds[NSTAGE * STAGE_BYTES];
     // two sets of per-tile tables: the set of tile k+1 is built while tile k is multiplied
-    __shared__ float s_sx[2][TAPS][BP];   // x_scale / 256 of the input pixel under tap t; 0 outside
+    __shared__ float s_sx[2][STAPS][BP];   // x_scale / 256 of the input pixel under tap t; 0 outside
     __shared__ int s_mask[2][BP];         // bit t: tap t of this output pixel is inside the image
     __shared__ __attribute__((aligned(16))) float s_sw[2][BCO];     // w_scale of the tile's channels
     __shared__ __attribute__((aligned(16))) float s_bias[2][BCO];   // bias (0 if absent)
@@ -329,9 +343,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
                 const int e = tid + j * NT;
                 const int t = e / BP, p = e % BP;
                 t_sx[j] = 0.f;
-                if (e < TAPS * BP && ((s_mask[k & 1][p] >> t) & 1)) {
-                    const int delta = TAPS > 1 ? (t / 3 - 1) * a.w + (t % 3 - 1) : 0;
-                    t_sx[j] = a.sx[static_cast<int64_t>(p0 + p) + delta];
+                if (e < STAPS * BP) {
+                    const int mask = s_mask[k & 1][p];
+                    if (PER_TAP ? ((mask >> t) & 1) : (mask != 0)) {
+                        const int delta = PER_TAP ? (t / 3 - 1) * a.w + (t % 3 - 1) : 0;
+                        t_sx[j] = a.sx[a.sx_static ? 0 : static_cast<int64_t>(p0 + p) + delta];
+                    }
                 }
             }
             if (tid < BCO && co0 + tid < a.n) {
@@ -349,7 +366,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
 #pragma unroll
             for (int j = 0; j < SX_PER_T; ++j) {
                 const int e = tid + j * NT;
-                if (e < TAPS * BP) (&s_sx[k & 1][0][0])[e] = t_sx[j] * (1.0f / 256.0f);
+                if (e < STAPS * BP) (&s_sx[k & 1][0][0])[e] = t_sx[j] * (1.0f / 256.0f);
             }
             if (tid < BCO) {
                 s_sw[k & 1][tid] = t_sw;
@@ -363,6 +380,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     uint32_t ld_b[B_SLOTS];      // activation rows: the same, at the tile's own pixel
     uint32_t ld_bmax[B_SLOTS];   // ... at the last pixel of the tensor
     uint32_t ld_bcur[B_SLOTS];   // ... at the pixel under the tap being fetched
+    int ld_mask[SUM ? B_SLOTS : 1];        // one sum over all taps: the row's tap mask ...
+    uint32_t ld_zero[SUM ? B_SLOTS : 1];   // ... and this lane's piece of the zero row
     uint32_t a_tap_off = 0;      // uniform: tap being fetched * kbytes
     uint32_t fk = 0;             // tile (index in this workgroup's list) being fetched
     int ftap = 0, fch = 0;
@@ -404,6 +423,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
             uint32_t pix = p0 + slot_row(i);
             pix = pix < a.pixels ? pix : a.pixels - 1;
             ld_b[j] = pix * kbytes + slot_byte(i);
+            if constexpr (SUM) {   // needs the masks of tile k to be visible
+                ld_mask[j] = i < B_INSTR ? s_mask[k & 1][slot_row(i)] : 0;
+                ld_zero[j] = slot_byte(i);
+            }
         }
         set_fetch_tap(0);
     };
@@ -419,7 +442,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
 #pragma unroll
         for (int j = 0; j < B_SLOTS; ++j) {
             const int i = j * NW + wave;
-            if (i < B_INSTR) load_to_lds16(base_b + ld_bcur[j], image + BCO * ROWB + i * 1024);
+            if (i < B_INSTR) {
+                const uint8_t *src = base_b + ld_bcur[j];
+                if constexpr (SUM) {
+                    if (!((ld_mask[j] >> ftap) & 1)) src = g_zero_row + ld_zero[j];
+                }
+                load_to_lds16(src, image + BCO * ROWB + i * 1024);
+            }
         }
         ++fetched;
         if (++fch == chunks_per_tap) {
@@ -434,13 +463,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     };
 
     // ---- prologue of the stream ---------------------------------------------------------------
+    build_masks(0);
+    if (my_tiles > 1) build_masks(1);
+    __syncthreads();
     set_fetch_tile(0);
 #pragma unroll
     for (int st = 0; st < NSTAGE - 1; ++st)
         if (fetched < stream_chunks) issue_loads(st);
-    build_masks(0);
-    if (my_tiles > 1) build_masks(1);
-    __syncthreads();
     load_scales(0);
     store_scales(0);
     __syncthreads();   // tables visible to every wave before the first raw barrier below
@@ -461,8 +490,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
         const uint32_t lds_a = lds_row + wm * TM * 32 * ROWB;
 
         v16i acc[TM][TN];
-        float facc[TAPS > 1 ? TM : 1][TAPS > 1 ? TN : 1][16];
-        if constexpr (TAPS > 1) {
+        float facc[PER_TAP ? TM : 1][PER_TAP ? TN : 1][16];
+        if constexpr (PER_TAP) {
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -532,32 +561,35 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
                 const uint32_t sa = lds_a + stage * STAGE_BYTES, sb = lds_b + stage * STAGE_BYTES;
                 Ops op[2];
                 read_packed<TM, TN, ROWB, 0>(op[0], sa, sb);
-                chunk_steps<0, KS, TM, TN, ROWB>(op, sa, sb, ch == 0, multiply);
+                chunk_steps<0, KS, TM, TN, ROWB>(op, sa, sb, SUM ? chunk == 0 : ch == 0, multiply);
             }
 
             if (++ch == chunks_per_tap) {
                 ch = 0;
-                if (active) {
-                // ---- end of a tap: fold the integer sums into the result ----------------------
+                // ---- end of a tap: fold the integer sums into the result (one sum over all taps:
+                // nothing to do before the last tap) ---------------------------------------------
+                if (active && (!SUM || tap == TAPS - 1)) {
                 if constexpr (OUT == kOutI32) {
                     int *yi = static_cast<int *>(a.y);
+                    constexpr int OUT_TAPS = SUM ? 1 : TAPS;   // sums stored per output pixel
 #pragma unroll
                     for (int tn = 0; tn < TN; ++tn) {
                         const int prow = (wave_n * TN + tn) * 32 + lrow;
                         const uint32_t pix = p0 + prow;
-                        const bool inside = (my_mask[tn] >> tap) & 1;   // also false for pixels >= pixels
+                        // a tap outside the image is written as 0 (also false for pixels >= pixels)
+                        const bool inside = SUM || ((my_mask[tn] >> tap) & 1);
 #pragma unroll
                         for (int tm = 0; tm < TM; ++tm) {
                             const int cbase = co0 + (wm * TM + tm) * 32 + 16 * lhalf;
                             if (pix < a.pixels) {
-                                int *dst = yi + (static_cast<int64_t>(pix) * TAPS + tap) * a.n + cbase;
+                                int *dst = yi + (static_cast<int64_t>(pix) * OUT_TAPS + (SUM ? 0 : tap)) * a.n + cbase;
 #pragma unroll
                                 for (int r = 0; r < 16; ++r)
                                     if (cbase + r < a.n) dst[r] = inside ? (acc[tm][tn][r] >> 8) : 0;
                             }
                         }
                     }
-                } else if constexpr (TAPS > 1) {
+                } else if constexpr (PER_TAP) {
                     float s[TN];
                     read_tap_scales<TN>(s, lds_sx + (tb * TAPS + tap) * BP * 4);
 #pragma unroll
@@ -604,7 +636,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         float s;
-                        if constexpr (TAPS > 1) s = facc[tm][tn][r];
+                        if constexpr (PER_TAP) s = facc[tm][tn][r];
                         else s = s_sx[tb][0][prow] * static_cast<float>(acc[tm][tn][r]);
                         out[r] = s * swv[r] + bv[r];
                     }
@@ -622,8 +654,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     }
 }
 
-template <int TM, int TN, int WAVES_M, int WAVES_N, int TAPS, int OUT, int KCH, int NSTAGE, int OCC>
+template <int TM, int TN, int WAVES_M, int WAVES_N, int KIND, int OUT, int KCH, int NSTAGE, int OCC>
 hq_status launch_tile(GemmArgs a, hipStream_t stream) {
+    constexpr int TAPS = KIND == kLinear ? 1 : 9;
     constexpr int BCO = 32 * TM * WAVES_M, BP = 32 * TN * WAVES_N;
     a.n_co_tiles = (a.n + BCO - 1) / BCO;
     const int64_t p_tiles = (static_cast<int64_t>(a.pixels) + BP - 1) / BP;
@@ -634,30 +667,35 @@ hq_status launch_tile(GemmArgs a, hipStream_t stream) {
     const unsigned grid = static_cast<unsigned>(tiles < slots ? tiles : slots);
     a.xcds = grid % 8 == 0 ? 1 : 0;
     a.cus = static_cast<uint32_t>(hq::compute_units());
-    hipLaunchKernelGGL((int_gemm_kernel<TM, TN, WAVES_M, WAVES_N, TAPS, OUT, KCH, NSTAGE, OCC>),
+    hipLaunchKernelGGL((int_gemm_kernel<TM, TN, WAVES_M, WAVES_N, KIND, OUT, KCH, NSTAGE, OCC>),
                        dim3(grid), dim3(64 * WAVES_M * WAVES_N), 0, stream, a);
     return hq::launch_status();
 }
 
-// All instantiations of one tile configuration: TAPS = 1 | 9, the three output types, and
-// K chunks of 192 codes (96 contiguous bytes per row) or, if WITH_64 is set, the 64-code
-// fallback for channel counts that are not a multiple of 192.
+// All instantiations of one tile configuration: the three kernel kinds (taps = 1: linear;
+// taps = 9: per-tap sums, or one sum if the activation scale is static), the three output
+// types, and K chunks of 192 codes (96 contiguous bytes per row) or, if WITH_64 is set, the
+// 64-code fallback for channel counts that are not a multiple of 192.
 template <int TM, int TN, int WAVES_M, int WAVES_N, int OCC, bool WITH_64, int NSTAGE_WIDE = 2>
 hq_status launch_config(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream_t stream) {
     const bool wide = a.k % 192 == 0;
     if (!wide && !WITH_64) return HQ_ERR_UNSUPPORTED;
-#define HQ_GEMM_CASE(TAPS, OUT)                                                                        \
-    if (wide) return launch_tile<TM, TN, WAVES_M, WAVES_N, TAPS, OUT, 6, NSTAGE_WIDE, OCC>(a, stream);           \
-    if constexpr (WITH_64) return launch_tile<TM, TN, WAVES_M, WAVES_N, TAPS, OUT, 2, 4, OCC>(a, stream); \
+#define HQ_GEMM_CASE(KIND, OUT)                                                                        \
+    if (wide) return launch_tile<TM, TN, WAVES_M, WAVES_N, KIND, OUT, 6, NSTAGE_WIDE, OCC>(a, stream);           \
+    if constexpr (WITH_64) return launch_tile<TM, TN, WAVES_M, WAVES_N, KIND, OUT, 2, 4, OCC>(a, stream); \
     return HQ_ERR_UNSUPPORTED;
     if (taps == 1) {
-        if (y_dtype == HQ_F16) { HQ_GEMM_CASE(1, kOutF16) }
-        if (y_dtype == HQ_F32) { HQ_GEMM_CASE(1, kOutF32) }
-        if (y_dtype == HQ_I32) { HQ_GEMM_CASE(1, kOutI32) }
+        if (y_dtype == HQ_F16) { HQ_GEMM_CASE(kLinear, kOutF16) }
+        if (y_dtype == HQ_F32) { HQ_GEMM_CASE(kLinear, kOutF32) }
+        if (y_dtype == HQ_I32) { HQ_GEMM_CASE(kLinear, kOutI32) }
+    } else if (taps == 9 && !a.sx_static) {
+        if (y_dtype == HQ_F16) { HQ_GEMM_CASE(kConvPerTap, kOutF16) }
+        if (y_dtype == HQ_F32) { HQ_GEMM_CASE(kConvPerTap, kOutF32) }
+        if (y_dtype == HQ_I32) { HQ_GEMM_CASE(kConvPerTap, kOutI32) }
     } else if (taps == 9) {
-        if (y_dtype == HQ_F16) { HQ_GEMM_CASE(9, kOutF16) }
-        if (y_dtype == HQ_F32) { HQ_GEMM_CASE(9, kOutF32) }
-        if (y_dtype == HQ_I32) { HQ_GEMM_CASE(9, kOutI32) }
+        if (y_dtype == HQ_F16) { HQ_GEMM_CASE(kConvSum, kOutF16) }
+        if (y_dtype == HQ_F32) { HQ_GEMM_CASE(kConvSum, kOutF32) }
+        if (y_dtype == HQ_I32) { HQ_GEMM_CASE(kConvSum, kOutI32) }
     }
 #undef HQ_GEMM_CASE
     return HQ_ERR_DTYPE;

@@ -96,6 +96,27 @@ def test_conv_argument_errors(lib):
     assert f(*args(y=P + 2)) == ALIGN
 
 
+def test_static_scale_argument_errors(lib):
+    q = lib.hq_act_hadamard_quant_static
+    assert q(P, 0, 8, 64, 64, 4, None, P, None) == NULL     # the scale is an input here
+    assert q(P, 0, 8, 64, 64, 4, P, None, None) == NULL
+    assert q(P, 0, 8, 64, 64, 4, P + 2, P, None) == ALIGN
+    assert q(P, 0, 8, 96, 64, 4, P, P, None) == SHAPE
+    assert q(P, 0, 8, 64, 64, 5, P, P, None) == BITS
+    lin = lib.hq_int_linear_static
+    assert lin(P, None, P, P, None, 8, 8, 64, P, 0, None) == NULL
+    assert lin(P, P, P, P, None, 8, 8, 32, P, 0, None) == SHAPE
+    conv = lib.hq_int_conv2d_static
+    args = lambda **kw: [kw.get(k, d) for k, d in [
+        ("xq", P), ("sx", P), ("wq", P), ("sw", P), ("bias", None), ("nb", 1), ("h", 4), ("w", 4),
+        ("cin", 64), ("cout", 8), ("r", 3), ("s", 3), ("stride", 1), ("pad", 1), ("y", P),
+        ("dt", 0), ("stream", None)]]
+    assert conv(*args(sx=None)) == NULL
+    assert conv(*args(stride=2)) == UNSUPPORTED
+    assert conv(*args(cin=14592)) == SHAPE      # 9 * 14592 codes in one sum: 256 * acc would overflow
+    assert conv(*args(cin=96)) == SHAPE
+
+
 def test_product_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2512_05746_amd")
     for dirpath, _, files in os.walk(pkg):

@@ -87,9 +87,100 @@ def run_layer(hq, layer, block=workloads.HAD_BLOCK):
     return flips, err
 
 
+def run_layer_static(hq, layer, block=workloads.HAD_BLOCK):
+    """The same three layers of checks with ONE caller-supplied activation scale (the paper's
+    learned per-timestep scale): active clamp, no scale output, and for a 3x3 convolution one
+    integer sum over all taps."""
+    print("layer (static scale)", layer.name, layer.kind, layer.x_shape, "->", layer.n_out, flush=True)
+    x, w, bias = workloads.make_x(layer), workloads.make_w(layer), workloads.make_bias(layer)
+    ydt = TORCH_DT[layer.dtype]
+    qmax = 2 ** (layer.a_bits - 1) - 1
+    # a scale below most tokens' own abs-max scale, so that the clamp is at work
+    _, sx_dyn, _ = oracle.act_hadamard_quant(x, block, layer.a_bits)
+    s = float(np.float32(0.7 * np.median(sx_dyn)))
+    s_d = torch.tensor([s], dtype=torch.float32, device="cuda")
+
+    xq_o, tx = oracle.act_hadamard_quant_static(x, block, layer.a_bits, s)
+    assert (tx > qmax + 0.5).any() and (tx < -qmax - 1.5).any(), "the test scale does not clamp"
+    wq_o, sw_o, _ = oracle.quantize_weights(w, block, layer.w_bits)
+
+    # (i) the activation quantiser (the weight path is that of the dynamic mode)
+    xq_g = hq.hq_act_hadamard_quant_static(dev(x), s_d, block, layer.a_bits)
+    xq_gc = unpack_codes(host(xq_g))
+    flips = check_codes(layer.name + " xq (static)", xq_gc, xq_o, tx, layer.a_bits)
+    assert xq_gc.min() == -qmax - 1 and xq_gc.max() == qmax
+    wq_g, sw_g = hq.hq_quantize_weights(dev(w), block, layer.w_bits)
+    wq_gc = unpack_codes(host(wq_g))
+
+    # (ii) integer stage on the oracle's codes, (iii) whole chain
+    xq_od, wq_od = dev(pack_codes(xq_o)), dev(pack_codes(wq_o))
+    bias_d = dev(bias) if bias is not None else None
+    sw_gh = host(sw_g).astype(np.float64)
+    if layer.kind == "linear":
+        acc_o, _ = oracle.int_linear_static(xq_o, s, wq_o[:, 0, :], sw_o, bias)
+        acc_g = host(hq.hq_int_linear_static(xq_od, None, wq_od, None, None, y_dtype=torch.int32))
+        assert np.array_equal(acc_g, acc_o), layer.name + " int32 sums (static)"
+        _, y_o = oracle.int_linear_static(xq_gc, s, wq_gc[:, 0, :], sw_gh, bias)
+        y_g = host(hq.hq_int_linear_static(xq_g, s_d, wq_g, sw_g, bias_d, y_dtype=ydt))
+    else:
+        ks = layer.ksize
+        wq4 = lambda c: c.reshape(layer.n_out, ks, ks, layer.k_in)
+        acc_o, _ = oracle.int_conv2d_static(xq_o, s, wq4(wq_o), sw_o, bias, stride=1, pad=layer.pad,
+                                            want_y=False)
+        acc_g = host(hq.hq_int_conv2d_static(xq_od, None, wq_od, None, None, ksize=ks, y_dtype=torch.int32))
+        assert np.array_equal(acc_g, acc_o), layer.name + " int32 sums over all taps (static)"
+        _, y_o = oracle.int_conv2d_static(xq_gc, s, wq4(wq_gc), sw_gh, bias, stride=1, pad=layer.pad,
+                                          want_acc=False)
+        y_g = host(hq.hq_int_conv2d_static(xq_g, s_d, wq_g, sw_g, bias_d, ksize=ks, y_dtype=ydt))
+    err = check_y(layer.name + " y (static)", y_g.reshape(y_o.shape), y_o)
+    print("   ok: tie flips %d, y err %.2e" % (flips, err), flush=True)
+    return flips, err
+
+
 @pytest.mark.parametrize("layer", workloads.tiny_layers(), ids=lambda l: l.name)
 def test_tiny_layers(hq, layer):
     run_layer(hq, layer)
+
+
+@pytest.mark.parametrize("layer", workloads.tiny_layers(), ids=lambda l: l.name)
+def test_tiny_layers_static_scale(hq, layer):
+    run_layer_static(hq, layer)
+
+
+@pytest.mark.parametrize("config", [1, 3, 4, 5])
+def test_benchmark_configs_full_size_static_scale(hq, config):
+    for layer in workloads.config_layers(config):
+        run_layer_static(hq, layer)
+
+
+@pytest.mark.parametrize("block,dtype,k", [(1, np.float32, 64), (8, np.float16, 264), (32, np.float32, 384),
+                                           (64, np.float32, 960), (128, np.float16, 256),
+                                           (64, np.float16, 2112), (64, np.float16, 16384)])
+def test_act_quant_static_paths(hq, block, dtype, k):
+    """Every kernel family of the quantiser with a given scale: butterfly (short and long rows,
+    fp32 and fp16, all block sizes) and the matrix-core kernel."""
+    rng = np.random.default_rng(300 + block + k)
+    x = rng.standard_normal((37, k))
+    x[:, 3] *= 20
+    x = x.astype(dtype)
+    for bits in (3, 4):
+        s = 0.4
+        q_o, t = oracle.act_hadamard_quant_static(x, block, bits, s)
+        q_g = hq.hq_act_hadamard_quant_static(dev(x), torch.tensor([s], dtype=torch.float32, device="cuda"),
+                                              block, bits)
+        check_codes("codes", unpack_codes(host(q_g)), q_o, t, bits)
+
+
+def test_static_scale_is_read_at_run_time(hq):
+    """The scale lives in device memory: the same call with another value there gives other codes."""
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((64, 192)).astype(np.float16)
+    s_d = torch.tensor([0.5], dtype=torch.float32, device="cuda")
+    xd = dev(x)
+    for s in (0.5, 0.125):
+        s_d.fill_(s)
+        q_o, t = oracle.act_hadamard_quant_static(x, 64, 4, s)
+        check_codes("codes", unpack_codes(host(hq.hq_act_hadamard_quant_static(xd, s_d, 64, 4))), q_o, t, 4)
 
 
 @pytest.mark.parametrize("config", [1, 2, 3, 4, 5])
