@@ -78,6 +78,12 @@ hq_status int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
     if (r == 3 && !sx_static && c_in % 192 == 0 && y_dtype != HQ_I32 &&
         tiles64 * 4 <= 5 * static_cast<int64_t>(hq::compute_units()))
         return hq_conv3x3_wave_launch(a, y_dtype, st_);
+    // With at least one 64 x 256 tile per CU, keeping the activation tile in LDS for all nine taps
+    // beats re-fetching it per tap when the per-tap flush does not double (one 192-channel slice)
+    // or there is no flush at all (static scale).
+    const int64_t tiles256 = ((pixels + 255) / 256) * ((c_out + 63) / 64);
+    if (r == 3 && (sx_static || c_in == 192) && tiles256 >= hq::compute_units() && hq_conv3x3_halo_fits(a, y_dtype))
+        return hq_conv3x3_halo_launch(a, y_dtype, st_);
     return launch_gemm(a, r * s, y_dtype, st_);
 }
 

@@ -709,3 +709,6 @@ hq_status hq_gemm_launch_64x128(const GemmArgs &a, int taps, hq_dtype y_dtype, h
 hq_status hq_gemm_launch_64x64(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream_t stream);
 // 3x3 convolution, one wave per 64x64 tile and K share (hq_conv3x3_wave.hip)
 hq_status hq_conv3x3_wave_launch(const GemmArgs &a, hq_dtype y_dtype, hipStream_t stream);
+// 3x3 convolution with the activation tile resident in LDS (hq_conv3x3_halo.hip)
+bool hq_conv3x3_halo_fits(const GemmArgs &a, hq_dtype y_dtype);
+hq_status hq_conv3x3_halo_launch(const GemmArgs &a, hq_dtype y_dtype, hipStream_t stream);
