@@ -167,6 +167,30 @@ def main():
             "quant_us": round(float(quant_us[i]), 2),
             "quant_gbs": round(q_bytes / quant_us[i] / 1e3, 1),
         })
+    # ---- the same layers with ONE static activation scale (the paper's learned per-timestep
+    # scale): no abs-max pass, and a 3x3 convolution keeps one integer sum over all taps ------
+    static_layers = []
+    for i, s in enumerate(state):
+        layer, x, wq, sw, xq, sx, y = s
+        sx1 = (0.7 * sx.float().median()).reshape(1).contiguous()
+
+        def run_quant_static(_s, x=x, sx1=sx1, xq=xq, layer=layer):
+            hq.hq_act_hadamard_quant_static(x, sx1, workloads.HAD_BLOCK, layer.a_bits, out=xq)
+
+        def run_int_static(_s, layer=layer, xq=xq, sx1=sx1, wq=wq, sw=sw, y=y):
+            if layer.kind == "conv":
+                hq.hq_int_conv2d_static(xq, sx1, wq, sw, None, ksize=layer.ksize, y_dtype=torch.float16, out=y)
+            else:
+                hq.hq_int_linear_static(xq, sx1, wq, sw, None, y_dtype=torch.float16, out=y)
+
+        run_quant_static(s)
+        q_us = batched_us(run_quant_static, s)
+        i_us = batched_us(run_int_static, s)
+        static_layers.append({"layer": layer.name, "int_us": round(i_us, 2),
+                              "int_tops": round(layer.ops / i_us / 1e6, 1), "quant_us": round(q_us, 2)})
+        run_quant(s)   # restore the dynamic codes for anything that follows
+    torch.cuda.synchronize()
+
     conv3 = [i for i, (l, *_r) in enumerate(state) if l.kind == "conv" and l.ksize == 3]
     conv3_ops = sum(state[i][0].ops for i in conv3)
     conv3_us = float(sum(int_us[i] for i in conv3))
@@ -245,6 +269,15 @@ def main():
             "rotating_buffers": nrot, "peak_gbs": HBM_PEAK_GBS,
         },
         "layers": per_layer,
+        "static_scale_mode": {
+            "what": "the same sweep through hq_*_static (one caller-supplied activation scale per tensor); "
+                    "not part of `value`",
+            "conv3x3_tops_kernel_time": round(conv3_ops / sum(static_layers[i]["int_us"] for i in conv3) / 1e6, 1),
+            "frac_int8_mfma_peak": round(conv3_ops / sum(static_layers[i]["int_us"] for i in conv3) / 1e6
+                                         / INT8_MFMA_PEAK_TOPS, 4),
+            "sum_kernel_us": round(sum(l["int_us"] + l["quant_us"] for l in static_layers), 1),
+            "layers": static_layers,
+        },
     }
 
     if not args.no_cpu_baseline:

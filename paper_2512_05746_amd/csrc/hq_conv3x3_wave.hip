@@ -36,7 +36,7 @@ struct WaveConvArgs {
     uint32_t pixels;
     int n, k, h, w;
     uint32_t w_magic, w_shift, h_magic, h_shift;   // exact division of a pixel index by w and by h
-    uint32_t n_co_tiles, n_tiles;
+    uint32_t n_px_tiles, n_tiles;
     int kg_log2;         // waves per tile: 1 << kg_log2 (1, 2 or 4)
 };
 
@@ -69,7 +69,12 @@ __global__ __launch_bounds__(256, 1) void conv3x3_wave_kernel(WaveConvArgs a) {
     const uint32_t last = a.pixels - 1;
 
     // ---- this wave's unit: tile and chunk range ---------------------------------------------
-    const uint32_t unit = blockIdx.x * 4 + wave;
+    // Workgroup b runs on XCD b % 8 (round-robin dispatch): give every XCD a contiguous range of
+    // units, and order the tiles channel-tile major, so that an XCD's L2 fetches only the weight
+    // rows of a few channel tiles (the weights are the large operand of the layers this kernel serves).
+    uint32_t wg = blockIdx.x;
+    if (gridDim.x % 8 == 0) wg = (blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8;
+    const uint32_t unit = wg * 4 + wave;
     const int kg = 1 << a.kg_log2;
     const int g = static_cast<int>(unit & (kg - 1));
     uint32_t tile = unit >> a.kg_log2;
@@ -77,8 +82,8 @@ __global__ __launch_bounds__(256, 1) void conv3x3_wave_kernel(WaveConvArgs a) {
     if (!active) tile = a.n_tiles - 1;
     const int c0 = active ? (g * chunks) >> a.kg_log2 : 0;
     const int c1 = active ? ((g + 1) * chunks) >> a.kg_log2 : 0;
-    const int co0 = static_cast<int>(tile % a.n_co_tiles) * 64;
-    const uint32_t p0 = (tile / a.n_co_tiles) * 64;
+    const int co0 = static_cast<int>(tile / a.n_px_tiles) * 64;
+    const uint32_t p0 = (tile % a.n_px_tiles) * 64;
 
     const uint32_t wave_base = lds_address(lds) + wave * WAVE_BYTES;
     const uint32_t lds_a = wave_base + lrow * ROWB + (lhalf ^ ((lrow >> 3) & 1)) * 16;
@@ -325,8 +330,8 @@ hq_status hq_conv3x3_wave_launch(const GemmArgs &g, hq_dtype y_dtype, hipStream_
     a.pixels = g.pixels; a.n = g.n; a.k = g.k; a.h = g.h; a.w = g.w;
     const Magic mw = magic_u31(static_cast<uint32_t>(g.w)), mh = magic_u31(static_cast<uint32_t>(g.h));
     a.w_magic = mw.m; a.w_shift = mw.s; a.h_magic = mh.m; a.h_shift = mh.s;
-    a.n_co_tiles = static_cast<uint32_t>((g.n + 63) / 64);
-    const int64_t tiles = ((static_cast<int64_t>(g.pixels) + 63) / 64) * a.n_co_tiles;
+    a.n_px_tiles = static_cast<uint32_t>((static_cast<int64_t>(g.pixels) + 63) / 64);
+    const int64_t tiles = static_cast<int64_t>(a.n_px_tiles) * ((g.n + 63) / 64);
     if (tiles > 0x1fffffff) return HQ_ERR_SHAPE;
     a.n_tiles = static_cast<uint32_t>(tiles);
     a.kg_log2 = hq_conv3x3_wave_split(tiles, 9 * (g.k / 192), hq::compute_units());
