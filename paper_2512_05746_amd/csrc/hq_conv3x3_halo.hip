@@ -26,6 +26,17 @@
 // away (a partial sum scales linearly, so per-tap sums need not be complete).  KIND = kConvSum
 // (one scale for the tensor): one integer sum over everything; a tap outside the image reads
 // a row of zeros instead of the activation row.
+//
+// Folding a (slice, tap) sum into the fp32 result costs one instruction per element, not two:
+// the integer accumulators start from the bit pattern of the float 1.5 * 2^23, so after the
+// MFMAs their bits, read as a float, are exactly 1.5 * 2^23 + S (|S| = 256 |sum| <= 256 * 192 * 64
+// < 2^22), and facc = fma(scale, that, facc) needs no int-to-float conversion.  The surplus
+// 1.5 * 2^23 * (sum of the scales used) is known per pixel beforehand and is what facc starts from,
+// negated.  The fp32 roundings this adds stay below 0.1 of one code product per output.
+//
+// Latency.  The loads of a tile's first slice and first weights are issued before the tile's
+// tables are built, and those of the next tile before the current tile's results are scaled
+// and stored, so neither waits for the other.
 #include <type_traits>
 
 #include "hq_int_gemm_kernel.h"
@@ -71,6 +82,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(HaloArgs a) {
     __shared__ int s_mask[BP];                        // bit t: tap t of this output pixel is inside its image
     __shared__ __attribute__((aligned(16))) float s_sw[BCO];
     __shared__ __attribute__((aligned(16))) float s_bias[BCO];
+    __shared__ float s_start[PER_TAP ? BP : 1];       // what a pixel's fp32 sums start from (see above)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -110,17 +122,71 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(HaloArgs a) {
         pat_byte[r] = static_cast<uint32_t>(((q % KCH) ^ ((pat_row[r] >> 3) & 1)) * 16);
     }
 
-    uint32_t loaded_p0 = 0xffffffffu;   // pixel tile whose slice 0 is in s_halo (single-slice layers only)
+    // weight rows of a tile: this wave's loads i = wave, wave + 4 (< 6) of every (tap, slice)
+    uint32_t ld_a[2];
+    auto set_weight_rows = [&](int co0) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int i = s * NW + wave, r = i % 3;
+            const int row = pat_row[r] + 32 * (i / 3);
+            int co = co0 + (row & ~31) + tile_row_to_channel(row & 31);
+            co = co < a.n ? co : a.n - 1;
+            ld_a[s] = static_cast<uint32_t>(co) * TAPS * kbytes + pat_byte[r];
+        }
+    };
+    auto issue_weights = [&](int tap, int slice, int stage) {
+        const uint8_t *base = a.wq + (static_cast<uint32_t>(tap) * kbytes + slice * ROWB);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int i = s * NW + wave;
+            if (i < 6) load_to_lds16(base + ld_a[s], s_a[stage] + i * 1024);
+        }
+    };
+    // activation rows p0 - halo .. of one slice into LDS rows 1..; load i covers rows 32 (i/3) + ...
+    auto issue_halo = [&](uint32_t p0, int slice) {
+        const int64_t first = static_cast<int64_t>(p0) - halo;
+        const bool inside = first >= 0 && first + kHaloRows - 1 <= static_cast<int64_t>(last);
+        const int loads = 3 * ((rows_needed + 31) / 32);
+        for (int i = wave; i < loads; i += NW) {
+            const int r = i % 3, g = i / 3;
+            uint8_t *dst = s_halo + ROWB + i * 1024;
+            if (inside) {
+                const uint8_t *base = a.xq + (static_cast<uint64_t>(first) + 32 * g) * kbytes + slice * ROWB;
+                load_to_lds16(base + (static_cast<uint32_t>(pat_row[r]) * kbytes + pat_byte[r]), dst);
+            } else {
+                int64_t pix = first + 32 * g + pat_row[r];
+                pix = pix < 0 ? 0 : (pix > static_cast<int64_t>(last) ? last : pix);
+                load_to_lds16(a.xq + (static_cast<uint64_t>(pix) * kbytes + slice * ROWB + pat_byte[r]), dst);
+            }
+        }
+    };
+
+    const uint32_t lds_halo = lds_address(s_halo);
+    const uint32_t lds_a0 = lds_address(s_a) + lrow * ROWB + (lhalf ^ ((lrow >> 3) & 1)) * 16;
+    const uint32_t lds_sx = lds_address(&s_sx[0][0]) + (wave * 64 + lrow) * 4;
+    const uint32_t lds_sw = lds_address(s_sw) + lhalf * 64;
+    const uint32_t lds_bias = lds_address(s_bias) + lhalf * 64;
+
+    // integer accumulators start from the bits of 1.5 * 2^23 when their sums are folded per tap
+    constexpr int kBiasBits = 0x4B400000;
+    constexpr float kBias = 12582912.0f;
+    v16i acc_start;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc_start[r] = PER_TAP ? kBiasBits : 0;
+    if constexpr (PER_TAP) asm volatile("" : "+v"(acc_start));   // kept in registers, not rebuilt per tap
+
+    if (my_tiles > 0) {   // loads of the first tile (the zero row above is not touched by them)
+        set_weight_rows(static_cast<int>(t_first % a.n_co_tiles) * BCO);
+        issue_halo((t_first / a.n_co_tiles) * BP, 0);
+        issue_weights(0, 0, 0);
+    }
 
     for (uint32_t kt = 0; kt < my_tiles; ++kt) {
         const uint32_t tile = t_first + kt;
         const int co0 = static_cast<int>(tile % a.n_co_tiles) * BCO;
         const uint32_t p0 = (tile / a.n_co_tiles) * BP;
-        const bool keep_halo = slices == 1 && p0 == loaded_p0;
 
-        __syncthreads();   // everyone is done with the previous tile's LDS contents
-
-        // ---- tables of the tile -----------------------------------------------------------------
+        // ---- tables of the tile (its first loads are in flight) ---------------------------------
         int my_mask;
         {
             const uint32_t pix = p0 + tid;
@@ -137,10 +203,16 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(HaloArgs a) {
                 for (int t = 0; t < TAPS; ++t) {
                     uint32_t ip = pix + static_cast<uint32_t>((t / 3 - 1) * a.w + (t % 3 - 1));   // wraps below 0
                     ip = ip < last ? ip : last;
-                    v[t] = a.sx[a.sx_static ? 0 : ip];
+                    v[t] = a.sx[ip];
                 }
+                float total = 0.f;
 #pragma unroll
-                for (int t = 0; t < TAPS; ++t) s_sx[t][tid] = ((my_mask >> t) & 1) ? v[t] * (1.0f / 256.0f) : 0.f;
+                for (int t = 0; t < TAPS; ++t) {
+                    v[t] = ((my_mask >> t) & 1) ? v[t] * (1.0f / 256.0f) : 0.f;
+                    s_sx[t][tid] = v[t];
+                    total += v[t];
+                }
+                s_start[tid] = -kBias * static_cast<float>(slices) * total;
             } else {
                 s_sx[0][tid] = my_mask ? a.sx[0] * (1.0f / 256.0f) : 0.f;
             }
@@ -152,53 +224,8 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(HaloArgs a) {
             }
         }
 
-        // weight rows of this tile: this wave's loads i = wave, wave + 4 (< 6) of every (tap, slice)
-        uint32_t ld_a[2];
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            const int i = s * NW + wave, r = i % 3;
-            const int row = pat_row[r] + 32 * (i / 3);
-            int co = co0 + (row & ~31) + tile_row_to_channel(row & 31);
-            co = co < a.n ? co : a.n - 1;
-            ld_a[s] = static_cast<uint32_t>(co) * TAPS * kbytes + pat_byte[r];
-        }
-        auto issue_weights = [&](int tap, int slice, int stage) {
-            const uint8_t *base = a.wq + (static_cast<uint32_t>(tap) * kbytes + slice * ROWB);
-#pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                const int i = s * NW + wave;
-                if (i < 6) load_to_lds16(base + ld_a[s], s_a[stage] + i * 1024);
-            }
-        };
-        // activation rows p0 - halo .. of one slice into LDS rows 1..; load i covers rows 32 (i/3) + ...
-        auto issue_halo = [&](int slice) {
-            const int64_t first = static_cast<int64_t>(p0) - halo;
-            const bool inside = first >= 0 && first + kHaloRows - 1 <= static_cast<int64_t>(last);
-            const int loads = 3 * ((rows_needed + 31) / 32);
-            for (int i = wave; i < loads; i += NW) {
-                const int r = i % 3, g = i / 3;
-                uint8_t *dst = s_halo + ROWB + i * 1024;
-                if (inside) {
-                    const uint8_t *base = a.xq + (static_cast<uint64_t>(first) + 32 * g) * kbytes + slice * ROWB;
-                    load_to_lds16(base + (static_cast<uint32_t>(pat_row[r]) * kbytes + pat_byte[r]), dst);
-                } else {
-                    int64_t pix = first + 32 * g + pat_row[r];
-                    pix = pix < 0 ? 0 : (pix > static_cast<int64_t>(last) ? last : pix);
-                    load_to_lds16(a.xq + (static_cast<uint64_t>(pix) * kbytes + slice * ROWB + pat_byte[r]), dst);
-                }
-            }
-        };
-
         v16i acc[TM][TN];
         float facc[PER_TAP ? TM : 1][PER_TAP ? TN : 1][16];
-        if constexpr (PER_TAP) {
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) facc[tm][tn][r] = 0.f;
-        }
         auto multiply = [&](Ops &o, bool first) {
             v4i a0[TM], a1[TM], b0[TN], b1[TN];
 #pragma unroll
@@ -206,12 +233,11 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(HaloArgs a) {
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) { pin(o.b[tn]); expand(o.b[tn], b0[tn], b1[tn]); }
             if (first) {
-                const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
                     for (int tn = 0; tn < TN; ++tn)
-                        acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[tm], b0[tn], zero, 0, 0, 0);
+                        acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[tm], b0[tn], acc_start, 0, 0, 0);
             } else {
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm)
@@ -226,24 +252,32 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(HaloArgs a) {
                     acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[tm], b1[tn], acc[tm][tn], 0, 0, 0);
         };
 
-        // this lane's pixels: local index wave * 64 + tn * 32 + lrow; their masks (one sum only)
-        int pix_mask[TN];
-        if constexpr (SUM) {
-            __syncthreads();
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) pix_mask[tn] = s_mask[wave * 64 + tn * 32 + lrow];
-        }
-        const uint32_t lds_halo = lds_address(s_halo);
-        const uint32_t lds_a0 = lds_address(s_a) + lrow * ROWB + (lhalf ^ ((lrow >> 3) & 1)) * 16;
-        const uint32_t lds_sx = lds_address(&s_sx[0][0]) + (wave * 64 + lrow) * 4;
+        int pix_mask[TN];   // masks of this lane's pixels, local index wave * 64 + tn * 32 + lrow (one sum only)
 
         for (int slice = 0; slice < slices; ++slice) {
-            if (slice > 0) __syncthreads();   // the previous slice is no longer read
-            if (!(keep_halo && slice == 0)) issue_halo(slice);
-#pragma unroll
-            for (int t = 0; t < NA - 1; ++t) issue_weights(t, slice, t);
+            if (slice > 0) {
+                __syncthreads();   // the previous slice is no longer read
+                issue_halo(p0, slice);
+                issue_weights(0, slice, 0);
+            }
             wait_vmem<0>();
             __syncthreads();   // slice, first weights and tables visible
+            if (slice == 0) {
+                if constexpr (SUM) {
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn) pix_mask[tn] = s_mask[wave * 64 + tn * 32 + lrow];
+                }
+                if constexpr (PER_TAP) {
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn) {
+                        const float f0 = s_start[wave * 64 + tn * 32 + lrow];
+#pragma unroll
+                        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) facc[tm][tn][r] = f0;
+                    }
+                }
+            }
 
             int stage = 0;
 #pragma unroll 1
@@ -290,7 +324,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(HaloArgs a) {
                         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
                             for (int r = 0; r < 16; ++r)
-                                facc[tm][tn][r] += s[tn] * static_cast<float>(acc[tm][tn][r]);
+                                facc[tm][tn][r] = __builtin_fmaf(s[tn], __int_as_float(acc[tm][tn][r]), facc[tm][tn][r]);
                 }
                 // this wave's share of the next tap's weights has landed once only the loads of the
                 // taps after it are pending (waves 0 and 1 issue two loads per tap, 2 and 3 one)
@@ -306,35 +340,47 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(HaloArgs a) {
                 stage = stage + 1 == NA ? 0 : stage + 1;
             }
         }
-        loaded_p0 = p0;
 
-        // ---- dequantising epilogue -------------------------------------------------------------
+        // ---- loads of the next tile: the activation slice and the weight stages are free ---------
+        if (kt + 1 < my_tiles) {
+            const uint32_t next = tile + 1;
+            const uint32_t next_p0 = (next / a.n_co_tiles) * BP;
+            set_weight_rows(static_cast<int>(next % a.n_co_tiles) * BCO);
+            if (!(slices == 1 && next_p0 == p0)) issue_halo(next_p0, 0);
+            issue_weights(0, 0, 0);
+        }
+
+        // ---- dequantising epilogue (LDS reads by hand: loads of the next tile are in flight) ------
         Out *y = static_cast<Out *>(a.y);
         const bool vec_ok = (a.n & 15) == 0;
+        float sxv[TN];
+        if constexpr (SUM) read_tap_scales<TN>(sxv, lds_sx);
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
-            const int clocal = tm * 32 + 16 * lhalf;
-            const int cbase = co0 + clocal;
-            float swv[16], bv[16];
+            const int cbase = co0 + tm * 32 + 16 * lhalf;
+            v4i swq[4], bq[4];
+            lds_read16<0>(swq[0], lds_sw + tm * 128);
+            lds_read16<16>(swq[1], lds_sw + tm * 128);
+            lds_read16<32>(swq[2], lds_sw + tm * 128);
+            lds_read16<48>(swq[3], lds_sw + tm * 128);
+            lds_read16<0>(bq[0], lds_bias + tm * 128);
+            lds_read16<16>(bq[1], lds_bias + tm * 128);
+            lds_read16<32>(bq[2], lds_bias + tm * 128);
+            lds_read16<48>(bq[3], lds_bias + tm * 128);
+            wait_lds<0>();
 #pragma unroll
-            for (int r = 0; r < 16; r += 4) {
-                const float4 s4 = *reinterpret_cast<const float4 *>(&s_sw[clocal + r]);
-                const float4 b4 = *reinterpret_cast<const float4 *>(&s_bias[clocal + r]);
-                swv[r] = s4.x; swv[r + 1] = s4.y; swv[r + 2] = s4.z; swv[r + 3] = s4.w;
-                bv[r] = b4.x; bv[r + 1] = b4.y; bv[r + 2] = b4.z; bv[r + 3] = b4.w;
-            }
+            for (int i = 0; i < 4; ++i) { pin(swq[i]); pin(bq[i]); }
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
-                const int prow = wave * 64 + tn * 32 + lrow;
-                const uint32_t pix = p0 + prow;
+                const uint32_t pix = p0 + wave * 64 + tn * 32 + lrow;
                 if (pix >= a.pixels) continue;
                 float out[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    float s;
-                    if constexpr (PER_TAP) s = facc[tm][tn][r];
-                    else s = s_sx[0][prow] * static_cast<float>(acc[tm][tn][r]);
-                    out[r] = s * swv[r] + bv[r];
+                    float v;
+                    if constexpr (PER_TAP) v = facc[tm][tn][r];
+                    else v = sxv[tn] * static_cast<float>(acc[tm][tn][r]);
+                    out[r] = __builtin_fmaf(v, __int_as_float(swq[r >> 2][r & 3]), __int_as_float(bq[r >> 2][r & 3]));
                 }
                 Out *dst = y + static_cast<int64_t>(pix) * a.n + cbase;
                 if (vec_ok && cbase + 16 <= a.n) {
@@ -346,6 +392,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(HaloArgs a) {
                 }
             }
         }
+        __syncthreads();   // the tables are free for the next tile
     }
 }
 
