@@ -230,15 +230,16 @@ __global__ __launch_bounds__(kThreads) void rowquant_large(const T *__restrict__
 // operand and 16 tokens as the columns of "B" of v_mfma_f32_16x16x32_f16, accumulated in
 // fp32; the products are exact, so only the summation order differs from the butterfly.
 //
-// Decomposition.  A workgroup has one wave per 64-channel block of the row and handles groups
-// of 16 tokens; wave b transforms block b of the group's tokens.  Lane l owns token l % 16
-// and K slice q = l / 16: its B operands are the two 16-byte pieces at channels 32 h + 8 q
-// (h = 0, 1) of the block, so activations go from HBM straight into the matrix core.  The rows
-// of H are permuted so that the 16 results of a lane are the 16 consecutive channels
-// 16 q .. 16 q + 15 of the block: 8 packed bytes, and the four lanes of a token write 32
-// contiguous bytes.  The abs-max of a token needs every block of its row: the waves exchange
-// their maxima through LDS (one barrier per group, two sets of slots).  Workgroups are
-// persistent and fetch the next group's pieces before they work on the current one.
+// Decomposition.  One wave transforms and quantises 16 whole tokens: lane l owns token l % 16
+// and K slice q = l / 16; its B operands of block b are the two 16-byte pieces at channels
+// 64 b + 32 h + 8 q (h = 0, 1), so activations go from HBM straight into the matrix core.  All
+// loads of the wave are issued first.  The rows of H are permuted so that the 16 results of a
+// lane per block are the 16 consecutive channels 16 q .. 16 q + 15 of the block: 8 packed
+// bytes, and the four lanes of a token write 32 contiguous bytes.  The abs-max of a token is
+// a maximum over the lane's values and over the four lanes of the token (two lane exchanges):
+// no LDS, no barrier, waves are independent.  Rows of up to four blocks keep the transformed
+// values in registers; longer rows keep the fp16 inputs instead and run the (cheap) MFMAs a
+// second time once the scale is known.
 //
 // Only pairing matters for the K index: element e of K slice q of operand h is channel
 // 32 h + 8 q + e for both operands, whatever order the hardware sums them in.
@@ -253,7 +254,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr float kMagic = 12582920.0f;                                 // 1.5 * 2^23 + 8
 constexpr uint32_t kMagicSum = 0x4B400000u * 0x11111111u;             // sum_i 0x4B400000 << 4i (mod 2^32)
-constexpr int kMaxBlocks = 16;                                        // waves per workgroup
+constexpr int kMaxBlocks = 16;                                        // 64-channel blocks per row
 
 __device__ __forceinline__ uint32_t pack8_magic(const float *v, float inv) {
     uint32_t w = __float_as_uint(__builtin_fmaf(v[7], inv, kMagic));
@@ -271,10 +272,114 @@ __device__ __forceinline__ uint32_t pack8_magic_clamped(const float *v, float in
     return pack8_magic(c, inv);
 }
 
-// STATIC: the scale is given (one for the tensor): no abs-max, no exchange, clamp active, no
-// scale output; `given` points to it.
+// STATIC: the scale is given (one for the tensor): no abs-max, clamp active, no scale output;
+// `given` points to it.  NBLK: 64-channel blocks per row.  Four waves (token groups) per workgroup.
+template <int NBLK, bool STATIC>
+__global__ __launch_bounds__(256) void hadamard64_quant_f16(const __half *__restrict__ x, int64_t m, float qmax,
+                                                           uint8_t *__restrict__ xq, float *__restrict__ scale,
+                                                           const float *__restrict__ given) {
+    constexpr int K = 64 * NBLK;
+    constexpr bool KEEP = STATIC || NBLK <= 4;   // transformed values stay in registers
+    const int lane = threadIdx.x & 63;
+    const int tok = lane & 15, q = lane >> 4;
+    const int64_t grp = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (grp * 16 >= m) return;   // no barrier below: a wave without tokens just leaves
+    const int64_t token = grp * 16 + tok;
+    const bool live = token < m;
+
+    v8h b[NBLK][2];
+    {
+        const __half *src = x + (live ? token : m - 1) * K + 8 * q;
+#pragma unroll
+        for (int blk = 0; blk < NBLK; ++blk) {
+            b[blk][0] = *reinterpret_cast<const v8h *>(src + 64 * blk);
+            b[blk][1] = *reinterpret_cast<const v8h *>(src + 64 * blk + 32);
+        }
+    }
+
+    // "A" operands: tile ct (4 tiles of 16 rows) x K half h.  Row i of tile ct is channel
+    // c = 16 (i / 4) + 4 ct + i % 4, so lane (token, q) ends up with channels 16 q + 4 ct + r.
+    // Sign of H[c][kk] = parity of popcount(c & kk), kk = 32 h + 8 q' + e with q' = this lane's
+    // K slice: the bits of e (0..2) and of 32 h + 8 q' (3..5) do not overlap, so the sign is
+    // (pattern over e from c & 7) xor (one bit from c & (32 h + 8 q')).
+    v8h hmat[4][2];
+    {
+        const int i = lane & 15;
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+            const int c = 16 * (i >> 2) + 4 * ct + (i & 3);
+            uint32_t pat[4];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                const uint32_t s0 = __popc(c & (2 * e2)) & 1, s1 = __popc(c & (2 * e2 + 1)) & 1;
+                pat[e2] = 0x3C003C00u ^ (s0 << 15) ^ (s1 << 31);   // +-1.0 in fp16
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t flip = (__popc(c & (32 * h + 8 * q)) & 1) ? 0x80008000u : 0u;
+                const uint4 w = uint4{pat[0] ^ flip, pat[1] ^ flip, pat[2] ^ flip, pat[3] ^ flip};
+                hmat[ct][h] = __builtin_bit_cast(v8h, w);
+            }
+        }
+    }
+    // the 16 sums of this lane for one block: 8 x the orthonormal transform
+    auto transform = [&](int blk, float (&v)[16]) {
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+            v4f acc = {0.f, 0.f, 0.f, 0.f};
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(hmat[ct][0], b[blk][0], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(hmat[ct][1], b[blk][1], acc, 0, 0, 0);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[4 * ct + r] = acc[r];
+        }
+    };
+    uint8_t *dst = xq + token * (K / 2) + 8 * q;
+
+    if constexpr (STATIC) {
+        const float inv = 0.125f / given[0];
+        const float lo = (-qmax - 1.0f) / inv, hi = qmax / inv;
+#pragma unroll
+        for (int blk = 0; blk < NBLK; ++blk) {
+            float v[16];
+            transform(blk, v);
+            uint2 w;
+            w.x = pack8_magic_clamped(v, inv, lo, hi);
+            w.y = pack8_magic_clamped(v + 8, inv, lo, hi);
+            if (live) *reinterpret_cast<uint2 *>(dst + 32 * blk) = w;
+        }
+    } else {
+        float v[KEEP ? NBLK : 1][16];
+        float amax = 0.f;
+#pragma unroll
+        for (int blk = 0; blk < NBLK; ++blk) {
+            float (&vb)[16] = v[KEEP ? blk : 0];
+            transform(blk, vb);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) amax = fmaxf(amax, fabsf(vb[r]));
+        }
+        amax = fmaxf(amax, __shfl_xor(amax, 16));   // the token's other three K slices
+        amax = fmaxf(amax, __shfl_xor(amax, 32));
+        const float inv = amax > 0.f ? qmax / amax : 0.f;
+        if (live && q == 0) scale[token] = amax > 0.f ? (amax * 0.125f) / qmax : 1.0f;
+#pragma unroll
+        for (int blk = 0; blk < NBLK; ++blk) {
+            float (&vb)[16] = v[KEEP ? blk : 0];
+            if constexpr (!KEEP) transform(blk, vb);
+            uint2 w;
+            w.x = pack8_magic(vb, inv);
+            w.y = pack8_magic(vb + 8, inv);
+            if (live) *reinterpret_cast<uint2 *>(dst + 32 * blk) = w;
+        }
+    }
+}
+
+// The same for tensors with too few tokens to fill the chip with one wave per 16 tokens: a
+// workgroup has one wave per 64-channel block of the row and handles groups of 16 tokens; wave b
+// transforms block b.  The abs-max of a token then needs every wave: they exchange their maxima
+// through LDS (one barrier per group, two sets of slots).  Workgroups are persistent and fetch
+// the next group's pieces before they work on the current one.
 template <bool STATIC>
-__global__ __launch_bounds__(64 * kMaxBlocks) void hadamard64_quant_f16(const __half *__restrict__ x, int64_t m,
+__global__ __launch_bounds__(64 * kMaxBlocks) void hadamard64_quant_split_f16(const __half *__restrict__ x, int64_t m,
                                                                         int k, float qmax,
                                                                         uint8_t *__restrict__ xq,
                                                                         float *__restrict__ scale,
@@ -374,7 +479,7 @@ __global__ __launch_bounds__(64 * kMaxBlocks) void hadamard64_quant_f16(const __
     }
 }
 
-hq_status launch_hadamard64(const __half *x, int64_t m, int k, int bits, uint8_t *xq, float *scale,
+hq_status launch_hadamard64_split(const __half *x, int64_t m, int k, int bits, uint8_t *xq, float *scale,
                             const float *given, hipStream_t stream) {
     const float qmax = static_cast<float>((1 << (bits - 1)) - 1);
     const int nblk = k / 64;
@@ -384,11 +489,44 @@ hq_status launch_hadamard64(const __half *x, int64_t m, int k, int bits, uint8_t
     const int64_t rounds = (groups + cap - 1) / cap;          // groups per workgroup
     const int64_t grid = (groups + rounds - 1) / rounds;      // the same number for (almost) all of them
     if (given)
-        hipLaunchKernelGGL(hadamard64_quant_f16<true>, dim3(static_cast<unsigned>(grid)), dim3(64 * nblk), 0,
+        hipLaunchKernelGGL(hadamard64_quant_split_f16<true>, dim3(static_cast<unsigned>(grid)), dim3(64 * nblk), 0,
                            stream, x, m, k, qmax, xq, scale, given);
     else
-        hipLaunchKernelGGL(hadamard64_quant_f16<false>, dim3(static_cast<unsigned>(grid)), dim3(64 * nblk), 0,
+        hipLaunchKernelGGL(hadamard64_quant_split_f16<false>, dim3(static_cast<unsigned>(grid)), dim3(64 * nblk), 0,
                            stream, x, m, k, qmax, xq, scale, given);
+    return hq::launch_status();
+}
+
+template <int NBLK>
+void launch_hadamard64_blocks(const __half *x, int64_t m, float qmax, uint8_t *xq, float *scale,
+                              const float *given, unsigned grid, hipStream_t stream) {
+    if (given)
+        hipLaunchKernelGGL((hadamard64_quant_f16<NBLK, true>), dim3(grid), dim3(256), 0, stream, x, m, qmax, xq,
+                           scale, given);
+    else
+        hipLaunchKernelGGL((hadamard64_quant_f16<NBLK, false>), dim3(grid), dim3(256), 0, stream, x, m, qmax, xq,
+                           scale, given);
+}
+
+hq_status launch_hadamard64(const __half *x, int64_t m, int k, int bits, uint8_t *xq, float *scale,
+                            const float *given, hipStream_t stream) {
+    // one wave per 16 tokens needs about two waves per SIMD to hide the latency of its loads
+    if ((m + 15) / 16 < 8 * static_cast<int64_t>(hq::compute_units()))
+        return launch_hadamard64_split(x, m, k, bits, xq, scale, given, stream);
+    const float qmax = static_cast<float>((1 << (bits - 1)) - 1);
+    const int64_t wgs = ((m + 15) / 16 + 3) / 4;   // 16 tokens per wave, four waves per workgroup
+    if (wgs > 0x7fffffffLL) return HQ_ERR_SHAPE;
+    const unsigned grid = static_cast<unsigned>(wgs);
+    switch (k / 64) {
+#define HQ_BLOCKS_CASE(N) \
+    case N: launch_hadamard64_blocks<N>(x, m, qmax, xq, scale, given, grid, stream); break;
+        HQ_BLOCKS_CASE(1) HQ_BLOCKS_CASE(2) HQ_BLOCKS_CASE(3) HQ_BLOCKS_CASE(4)
+        HQ_BLOCKS_CASE(5) HQ_BLOCKS_CASE(6) HQ_BLOCKS_CASE(7) HQ_BLOCKS_CASE(8)
+        HQ_BLOCKS_CASE(9) HQ_BLOCKS_CASE(10) HQ_BLOCKS_CASE(11) HQ_BLOCKS_CASE(12)
+        HQ_BLOCKS_CASE(13) HQ_BLOCKS_CASE(14) HQ_BLOCKS_CASE(15) HQ_BLOCKS_CASE(16)
+#undef HQ_BLOCKS_CASE
+        default: return HQ_ERR_SHAPE;
+    }
     return hq::launch_status();
 }
 

@@ -220,6 +220,28 @@ def test_act_quant_shapes(hq, m, k):
     check_codes("codes", unpack_codes(host(q_g)), q_o, t, 4)
 
 
+@pytest.mark.parametrize("k", [64, 192, 320, 1024])
+def test_act_quant_many_tokens(hq, k):
+    """Enough tokens for the matrix-core kernel that gives a wave 16 whole tokens (values kept in
+    registers up to four blocks per row, recomputed beyond), ragged last group; both scale modes."""
+    m = 16 * 8 * 256 + 16 * 3 + 5
+    rng = np.random.default_rng(900 + k)
+    x = rng.standard_normal((m, k))
+    x[:, 7] *= 20
+    x[11] = 0.0
+    x = x.astype(np.float16)
+    xd = dev(x)
+    bits = 3 if k == 320 else 4
+    q_o, s_o, t = oracle.act_hadamard_quant(x, 64, bits)
+    q_g, s_g = hq.hq_act_hadamard_quant(xd, 64, bits)
+    check_scales("scale", host(s_g), s_o)
+    check_codes("codes", unpack_codes(host(q_g)), q_o, t, bits)
+    s = float(np.median(s_o)) * 0.7
+    q_o, t = oracle.act_hadamard_quant_static(x, 64, bits, s)
+    q_g = hq.hq_act_hadamard_quant_static(xd, torch.tensor([s], dtype=torch.float32, device="cuda"), 64, bits)
+    check_codes("static codes", unpack_codes(host(q_g)), q_o, t, bits)
+
+
 def test_act_quant_degenerate_rows(hq):
     """All-zero tokens (scale 1, codes 0), the paper's two worked examples, and exact ties."""
     x = np.zeros((5, 192), dtype=np.float16)
