@@ -43,7 +43,7 @@
 
 namespace {
 
-constexpr int kHaloRows = 416;   // activation rows a tile can hold: 256 + 2 (W + 1), rounded up to 32
+constexpr int kHaloRows = 400;   // activation rows a tile can hold: 256 + 2 (W + 1) for W <= 71
 
 struct HaloArgs {
     const uint8_t *xq;   // [pixels, k/2]
@@ -64,7 +64,7 @@ __device__ __forceinline__ uint32_t div_magic31(uint32_t n, uint32_t d, uint32_t
 }
 
 template <int KIND, int OUT>
-__global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(HaloArgs a) {
+__global__ __launch_bounds__(256, KIND == kConvSum ? 3 : 2) void conv3x3_halo_kernel(HaloArgs a) {
     constexpr bool PER_TAP = KIND == kConvPerTap;
     constexpr bool SUM = KIND == kConvSum;
     constexpr int TM = 2, TN = 2, NW = 4, KCH = 6, ROWB = KCH * 16, KS = KCH / 2, TAPS = 9;
@@ -150,6 +150,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(HaloArgs a) {
         for (int i = wave; i < loads; i += NW) {
             const int r = i % 3, g = i / 3;
             uint8_t *dst = s_halo + ROWB + i * 1024;
+            if (32 * g + pat_row[r] >= rows_needed) continue;   // lanes past the last row needed load nothing
             if (inside) {
                 const uint8_t *base = a.xq + (static_cast<uint64_t>(first) + 32 * g) * kbytes + slice * ROWB;
                 load_to_lds16(base + (static_cast<uint32_t>(pat_row[r]) * kbytes + pat_byte[r]), dst);
@@ -427,7 +428,8 @@ hq_status hq_conv3x3_halo_launch(const GemmArgs &g, hq_dtype y_dtype, hipStream_
     const int64_t tiles = ((static_cast<int64_t>(g.pixels) + 255) / 256) * a.n_co_tiles;
     if (tiles > 0x7fffffffLL) return HQ_ERR_SHAPE;
     a.n_tiles = static_cast<uint32_t>(tiles);
-    const int64_t slots = 2 * static_cast<int64_t>(hq::compute_units());
+    // workgroups per CU: the one-sum kernel needs no fp32 sums beside the integer ones and fits three
+    const int64_t slots = (g.sx_static ? 3 : 2) * static_cast<int64_t>(hq::compute_units());
     const unsigned grid = static_cast<unsigned>(tiles < slots ? tiles : slots);
     a.xcds = grid % 8 == 0 ? 1 : 0;
     const dim3 block(256);
