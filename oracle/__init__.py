@@ -10,10 +10,13 @@ from .hq_oracle import (  # noqa: F401
     int_conv2d,
     int_conv2d_static,
     int_gemm,
+    int_gemm_single,
     int_linear,
+    int_linear_single,
     int_linear_static,
     max_threads,
     quantize_rows,
     quantize_static,
     quantize_weights,
+    quantize_weights_single,
 )

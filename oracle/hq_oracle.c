@@ -38,6 +38,15 @@
  *     clamp is then active (codes reach -2^(b-1)), and a convolution is the
  *     paper's form: ONE integer sum over all taps and input channels followed
  *     by one product of scales, y = S_x s_w[co] * sum + bias.
+ *   - Single scheme (the *_single functions): the paper's own linear layer
+ *     (Method, linear-layer equation and "Single Hadamard Transformation"):
+ *     the weights are quantised WITHOUT the transform, W_int = Q(W), one
+ *     abs-max scale per output channel, and the transform of the contracted
+ *     axis stays in the integer domain between the two quantised operands:
+ *         Y ~ S_XH S_W 2^(-k/2) ( (XH)_int  H_raw  W_int^T ),
+ *     H_raw the +-1 matrix, block-diagonal over the input channels.  The steps
+ *     are taken in that order: the activation codes times H_raw first
+ *     (integers up to 8 * block in magnitude), then times the weight codes.
  *
  * All arrays are row-major and owned by the caller.
  */
@@ -269,4 +278,47 @@ int hqo_int_conv2d_static(const int8_t *xq, double sx, const int8_t *wq, const d
         }
     }
     return 0;
+}
+
+/* Single scheme, integer stage (Method, linear-layer equation):
+ * acc[i, j] = sum_c u[i, c] * wq[j, c]  with  u[i, :] = xq[i, :] * BlockDiag(H_raw),
+ * H_raw the +-1 Sylvester matrix of size `block` (block = 1: u = xq).  All int64.
+ * xq: [m, k] activation codes (of the transformed activations), wq: [n, k] codes of the
+ * un-transformed weights.  Returns -1 if block does not divide k or is not a power of two. */
+int hqo_int_gemm_single(const int8_t *xq, const int8_t *wq, int64_t m, int n, int k, int block,
+                        int64_t *acc)
+{
+    if (block < 1 || (block & (block - 1)) || k % block) return -1;
+    double *h = (double *)malloc(sizeof(double) * (size_t)block * block);
+    if (!h) return -2;
+    hqo_hadamard_raw(block, h);
+    int failed = 0;
+#pragma omp parallel
+    {
+        int64_t *u = (int64_t *)malloc(sizeof(int64_t) * (size_t)k);
+        if (!u) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(static)
+        for (int64_t i = 0; i < m; ++i) {
+            if (!u) continue;
+            const int8_t *xr = xq + (size_t)i * k;
+            for (int b0 = 0; b0 < k; b0 += block)
+                for (int c = 0; c < block; ++c) {
+                    int64_t v = 0;
+                    for (int e = 0; e < block; ++e)
+                        v += (int64_t)xr[b0 + e] * (int64_t)h[(size_t)e * block + c];
+                    u[b0 + c] = v;
+                }
+            for (int j = 0; j < n; ++j) {
+                int64_t a = 0;
+                for (int c = 0; c < k; ++c) a += u[c] * (int64_t)wq[(size_t)j * k + c];
+                acc[(size_t)i * n + j] = a;
+            }
+        }
+        free(u);
+    }
+    free(h);
+    return failed ? -2 : 0;
 }

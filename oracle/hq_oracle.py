@@ -64,6 +64,8 @@ def _load():
         lib.hqo_int_conv2d_static.argtypes = ([c_i8p, ctypes.c_double, c_i8p, c_dp, c_dp] + [i32] * 9
                                               + [c_i64p, c_dp])
         lib.hqo_int_conv2d_static.restype = i32
+        lib.hqo_int_gemm_single.argtypes = [c_i8p, c_i8p, i64, i32, i32, i32, c_i64p]
+        lib.hqo_int_gemm_single.restype = i32
         lib.hqo_max_threads.argtypes = []
         lib.hqo_max_threads.restype = i32
         _lib = lib
@@ -246,4 +248,41 @@ def int_conv2d_static(xq, sx: float, wq, sw, bias=None, stride: int = 1, pad: in
         raise ValueError("bad convolution shape")
     if acc is not None:
         assert np.abs(acc).max(initial=0) < 2**31
+    return acc, y
+
+
+# ---- Single scheme: weights quantised without the transform, integer H between the operands ----
+
+def quantize_weights_single(w, bits: int):
+    """Weights of the paper's own linear layer (Method, "Single Hadamard Transformation"): quantised
+    as they are, one abs-max scale per output channel.  w [n_out, k_in].
+    Returns (codes [n_out, k_in] int8, scale [n_out] fp64, t fp64)."""
+    w64 = _f64(w)
+    assert w64.ndim == 2
+    return quantize_rows(w64, bits)
+
+
+def int_gemm_single(xq, wq, block: int) -> np.ndarray:
+    """acc = (xq BlockDiag(H_raw)) wq^T in int64 (Method, linear-layer equation)."""
+    xq = np.ascontiguousarray(xq, dtype=np.int8)
+    wq = np.ascontiguousarray(wq, dtype=np.int8)
+    m, k = xq.shape
+    n, k2 = wq.shape
+    assert k == k2
+    acc = np.empty((m, n), dtype=np.int64)
+    rc = _load().hqo_int_gemm_single(_i8p(xq), _i8p(wq), m, n, k, int(block), _i64p(acc))
+    if rc != 0:
+        raise ValueError("block %d does not fit k = %d" % (block, k))
+    return acc
+
+
+def int_linear_single(xq, sx, wq, sw, block: int, bias=None):
+    """y = S_XH S_W 2^(-log2(block)/2) ((XH)_int H_raw W_int^T) + bias.
+    Returns (acc int64 [m, n], y fp64 [m, n])."""
+    acc = int_gemm_single(xq, wq, block)
+    assert np.abs(acc).max(initial=0) < 2**31
+    m, n = acc.shape
+    y = acc.astype(np.float64) * _f64(sx).reshape(m, 1) * _f64(sw).reshape(1, n) / np.sqrt(float(block))
+    if bias is not None:
+        y = y + _f64(bias).reshape(1, n)
     return acc, y

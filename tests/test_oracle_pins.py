@@ -377,3 +377,81 @@ def test_static_conv_vs_brute_force_and_library(ksize, stride, pad):
     wh = torch.from_numpy(sw[:, None, None, None] * wq).permute(0, 3, 1, 2)
     ref = torch.nn.functional.conv2d(xh, wh, torch.from_numpy(bias), stride=stride, padding=pad)
     assert np.allclose(y, ref.permute(0, 2, 3, 1).numpy(), rtol=1e-12, atol=1e-12)
+
+
+# ---- Single scheme: un-transformed quantised weights, integer H between the operands ----------
+
+def test_single_integer_stage_against_library_hadamard():
+    """(XH)_int H_raw W_int^T against SciPy's Sylvester-ordered Hadamard matrix and NumPy integer
+    products, non-square so that a transposed operand or a wrong block offset shows."""
+    from scipy.linalg import hadamard
+    rng = np.random.default_rng(21)
+    m, k, n = 11, 192, 7
+    xq = rng.integers(-8, 8, (m, k)).astype(np.int8)
+    wq = rng.integers(-8, 8, (n, k)).astype(np.int8)
+    for block in (1, 2, 16, 64):
+        hb = np.kron(np.eye(k // block, dtype=np.int64), hadamard(block).astype(np.int64))
+        want = (xq.astype(np.int64) @ hb) @ wq.astype(np.int64).T
+        assert np.array_equal(oracle.int_gemm_single(xq, wq, block), want)
+    with pytest.raises(ValueError):
+        oracle.int_gemm_single(xq, wq, 128)   # 128 does not divide 192
+
+
+def test_single_block_1_is_the_plain_quantised_linear():
+    rng = np.random.default_rng(22)
+    x, w, b = rng.standard_normal((12, 40)), rng.standard_normal((9, 40)), rng.standard_normal(9)
+    xq, sx, _ = oracle.act_hadamard_quant(x, 1, 4)
+    wq, sw, _ = oracle.quantize_weights_single(w, 4)
+    acc1, y1 = oracle.int_linear_single(xq, sx, wq, sw, 1, b)
+    acc0, y0 = oracle.int_linear(xq, sx, wq, sw, b)
+    assert np.array_equal(acc1, acc0) and np.array_equal(y1, y0)
+
+
+def test_single_is_matmul_of_dequantised_tensors_through_h():
+    """y = (S_x X_int) H (S_w W_int)^T with the orthonormal H: the plain definition of the scheme."""
+    layer = workloads.tiny_layers()[0]
+    x, w, b = workloads.make_x(layer), workloads.make_w(layer)[:, 0, :], workloads.make_bias(layer)
+    xq, sx, _ = oracle.act_hadamard_quant(x, 64, 4)
+    wq, sw, _ = oracle.quantize_weights_single(w, 4)
+    assert np.array_equal(sw, np.abs(w.astype(np.float64)).max(axis=1) / 7)   # scale of the UN-transformed rows
+    acc, y = oracle.int_linear_single(xq, sx, wq, sw, 64, b)
+    assert acc.shape == (layer.m, layer.n_out)
+    hn = np.kron(np.eye(layer.k_in // 64), sylvester_closed_form(64) / 8.0)
+    ref = ((sx[:, None] * xq) @ hn) @ (sw[:, None] * wq).T + b.astype(np.float64)
+    assert np.allclose(y, ref, rtol=1e-12, atol=1e-12)
+
+
+def test_single_lossless_case_reduces_to_plain_matmul():
+    """Integer-valued W (times a power of two) and X = (s Qx) H quantise without loss; the scheme
+    must then return the fp64 product X W^T of the original tensors."""
+    rng = np.random.default_rng(23)
+    m, k, n = 17, 128, 21
+    qx = rng.integers(-7, 8, (m, k)); qx[:, 3] = -7
+    qw = rng.integers(-7, 8, (n, k)); qw[:, 5] = 7
+    sxp = 2.0 ** rng.integers(-5, 3, m)
+    swp = 2.0 ** rng.integers(-7, -1, n)
+    hn = np.kron(np.eye(k // 64), sylvester_closed_form(64) / 8.0)
+    x = (sxp[:, None] * qx) @ hn
+    w = swp[:, None] * qw
+    xq, sx, _ = oracle.act_hadamard_quant(x, 64, 4)
+    wq, sw, _ = oracle.quantize_weights_single(w, 4)
+    assert np.array_equal(xq, qx) and np.array_equal(wq, qw)
+    _, y = oracle.int_linear_single(xq, sx, wq, sw, 64)
+    assert np.allclose(y, x @ w.T, rtol=1e-12, atol=1e-12)
+
+
+def test_single_integer_range_and_transform_helps():
+    """|(XH)_int H_raw| <= 8 * block, so the integer sums stay far inside int32; and on data with
+    outlier channels the scheme is closer to the fp64 product than quantising without H."""
+    layer = workloads.config_layers(2)[0]
+    x = workloads.make_x(layer)[:256]
+    w = workloads.make_w(layer)[:, 0, :]
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+    wq, sw, _ = oracle.quantize_weights_single(w, 4)
+    err = {}
+    for block in (1, 64):
+        xq, sx, _ = oracle.act_hadamard_quant(x, block, 4)
+        acc, y = oracle.int_linear_single(xq, sx, wq, sw, block)
+        assert np.abs(acc).max() <= 8 * block * 8 * layer.k_in
+        err[block] = np.linalg.norm(y - ref) / np.linalg.norm(ref)
+    assert err[64] < 0.8 * err[1]
