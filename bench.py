@@ -191,6 +191,28 @@ def main():
         run_quant(s)   # restore the dynamic codes for anything that follows
     torch.cuda.synchronize()
 
+    # ---- the linear / 1x1 layers in the paper's Single scheme: weights quantised without the
+    # transform, the integer H_raw folded into three digit planes (three integer passes) -------
+    single_layers = []
+    for i, s in enumerate(state):
+        layer, x, wq, sw, xq, sx, y = s
+        if layer.kind == "conv" and layer.ksize != 1:
+            continue
+        w2 = torch.from_numpy(workloads.make_w(layer)[:, 0, :].copy()).cuda()
+        wq3, sw3 = hq.hq_quantize_weights_single(w2, workloads.HAD_BLOCK, layer.w_bits)
+        xq2, y2 = xq.reshape(layer.m, -1), y.reshape(layer.m, -1)
+
+        def run_int_single(_s, xq2=xq2, sx=sx, wq3=wq3, sw3=sw3, y2=y2):
+            hq.hq_int_linear_single(xq2, sx.reshape(-1), wq3, sw3, None, workloads.HAD_BLOCK,
+                                    y_dtype=torch.float16, out=y2)
+
+        run_int_single(s)
+        i_us = batched_us(run_int_single, s)
+        single_layers.append({"layer": layer.name, "int_us": round(i_us, 2),
+                              "int_tops_useful": round(layer.ops / i_us / 1e6, 1),
+                              "int_tops_issued": round(3 * layer.ops / i_us / 1e6, 1)})
+    torch.cuda.synchronize()
+
     conv3 = [i for i, (l, *_r) in enumerate(state) if l.kind == "conv" and l.ksize == 3]
     conv3_ops = sum(state[i][0].ops for i in conv3)
     conv3_us = float(sum(int_us[i] for i in conv3))
@@ -284,6 +306,12 @@ def main():
                                          / INT8_MFMA_PEAK_TOPS, 4),
             "sum_kernel_us": round(sum(l["int_us"] + l["quant_us"] for l in static_layers), 1),
             "layers": static_layers,
+        },
+        "single_scheme_mode": {
+            "what": "linear and 1x1 layers through hq_int_linear_single (un-transformed quantised weights, "
+                    "integer H_raw in three digit planes); useful = 2*M*N*K, issued = three integer passes; "
+                    "not part of `value`",
+            "layers": single_layers,
         },
     }
 

@@ -176,6 +176,51 @@ hq_status hq_int_conv2d_static(const uint8_t *xq, const float *x_scale, const ui
                                int c_in, int c_out, int r, int s, int stride, int pad,
                                void *y, hq_dtype y_dtype, void *stream);
 
+/*
+ * ---- Single Hadamard scheme (linear layers) ------------------------------------
+ *
+ * The paper's own linear layer (Method, linear-layer equation; "Single Hadamard
+ * Transformation") quantises the weights WITHOUT the transform and keeps the
+ * transform of the contracted axis in the integer domain, between the two
+ * quantised operands:
+ *
+ *   Y ~ S_XH S_W 2^(-k/2) ( (XH)_int  H_raw  W_int^T ),   H_raw = BlockDiag of +-1 blocks.
+ *
+ * The activation side is hq_act_hadamard_quant unchanged.  The two calls below are
+ * the weight side and the integer stage.  A 1x1 convolution is this linear layer
+ * with m = N*H*W.
+ */
+
+/*
+ * Offline: W_int = clamp(rne(W / w_scale)) with w_scale[j] = max |W[j, :]| / (2^(w_bits-1) - 1)
+ * (1.0 for an all-zero row), then B = W_int * BlockDiag(H_raw) in exact integers
+ * (|B| <= 2^(w_bits-1) * had_block), stored as three signed base-16 digit planes:
+ * B = d0 + 16 d1 + 256 d2, every digit in [-8, 7], each plane in the packed-nibble format.
+ *
+ *   w        [n_out, k_in] of w_dtype (HQ_F16 | HQ_F32), k_in even.
+ *   had_block power of two in 1..128 dividing k_in (the block size the activations use).
+ *   w_bits   4 or 3.
+ *   wq3      out, [n_out, 3, k_in / 2] packed digits, plane p at [:, p, :].
+ *   w_scale  out, [n_out] fp32.
+ */
+hq_status hq_quantize_weights_single(const void *w, hq_dtype w_dtype, int n_out, int k_in,
+                                     int had_block, int w_bits, uint8_t *wq3, float *w_scale,
+                                     void *stream);
+
+/*
+ * Integer stage and dequantisation of the Single scheme:
+ *
+ *   acc_p[i, j] = sum_c xq[i, c] * d_p[j, c]                      (int32, p = 0, 1, 2)
+ *   y[i, j]     = (acc_0 + 16 acc_1 + 256 acc_2) * x_scale[i] * w_scale[j] / sqrt(had_block) + bias[j]
+ *
+ * acc_0 + 16 acc_1 + 256 acc_2 is the integer (XH)_int H_raw W_int^T of the paper's equation;
+ * the three sums are combined in fp32.  Shapes as in hq_int_linear, with wq3 [n, 3, k/2].
+ * y_dtype == HQ_I32 writes the three sums, [m, 3, n] (bias and scales ignored).
+ */
+hq_status hq_int_linear_single(const uint8_t *xq, const float *x_scale, const uint8_t *wq3,
+                               const float *w_scale, const void *bias, int64_t m, int n, int k,
+                               int had_block, void *y, hq_dtype y_dtype, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -6,8 +6,10 @@ from .binding import (  # noqa: F401
     hq_int_conv2d,
     hq_int_conv2d_static,
     hq_int_linear,
+    hq_int_linear_single,
     hq_int_linear_static,
     hq_quantize_weights,
+    hq_quantize_weights_single,
     load_library,
     status_string,
 )

@@ -20,7 +20,8 @@ _DTYPES = {torch.float16: HQ_F16, torch.float32: HQ_F32, torch.int32: HQ_I32}
 
 SYMBOLS = ("hq_status_string", "hq_quantize_weights", "hq_act_hadamard_quant",
            "hq_int_linear", "hq_int_conv2d", "hq_act_hadamard_quant_static",
-           "hq_int_linear_static", "hq_int_conv2d_static")
+           "hq_int_linear_static", "hq_int_conv2d_static",
+           "hq_quantize_weights_single", "hq_int_linear_single")
 
 
 class HqError(RuntimeError):
@@ -51,6 +52,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.hq_act_hadamard_quant_static.argtypes = [vp, i32, i64, i32, i32, i32, vp, vp, vp]
     lib.hq_int_linear_static.argtypes = lib.hq_int_linear.argtypes
     lib.hq_int_conv2d_static.argtypes = lib.hq_int_conv2d.argtypes
+    lib.hq_quantize_weights_single.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp]
+    lib.hq_int_linear_single.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, vp, i32, vp]
     for name in SYMBOLS[1:]:
         getattr(lib, name).restype = i32
     _lib = lib
@@ -211,4 +214,40 @@ def hq_int_conv2d_static(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: 
     _check("hq_int_conv2d_static", load_library().hq_int_conv2d_static(
         _ptr(xq), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), nb, h, w, cb * 2, cout,
         ksize, ksize, stride, pad, _ptr(y), _DTYPES[y_dtype], _stream()))
+    return y
+
+
+# ---- Single scheme: un-transformed quantised weights, integer H folded into digit planes -------
+
+def hq_quantize_weights_single(w: torch.Tensor, had_block: int = 64, w_bits: int = 4
+                               ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """w [n_out, k_in] fp16/fp32 -> (wq3 uint8 [n_out, 3, k_in/2] digit planes, w_scale fp32 [n_out])."""
+    _dev(w, "w")
+    if w.dim() != 2:
+        raise ValueError("w must be [n_out, k_in]")
+    n_out, k_in = w.shape
+    wq3 = torch.empty((n_out, 3, k_in // 2), dtype=torch.uint8, device=w.device)
+    ws = torch.empty((n_out,), dtype=torch.float32, device=w.device)
+    _check("hq_quantize_weights_single", load_library().hq_quantize_weights_single(
+        _ptr(w), _DTYPES[w.dtype], n_out, k_in, had_block, w_bits, _ptr(wq3), _ptr(ws), _stream()))
+    return wq3, ws
+
+
+def hq_int_linear_single(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq3: torch.Tensor,
+                         w_scale: Optional[torch.Tensor], bias: Optional[torch.Tensor] = None,
+                         had_block: int = 64, y_dtype: torch.dtype = torch.float16,
+                         out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """xq [m, k/2], wq3 [n, 3, k/2] -> y [m, n]; y_dtype int32 returns the three sums [m, 3, n]."""
+    _dev(xq, "xq"), _dev(wq3, "wq3")
+    m, kb = xq.shape
+    n = wq3.shape[0]
+    if wq3.numel() != n * 3 * kb:
+        raise ValueError("wq3 does not match xq in k")
+    if bias is not None and bias.dtype != y_dtype:
+        raise ValueError("bias must have the output dtype")
+    shape = (m, 3, n) if y_dtype == torch.int32 else (m, n)
+    y = out if out is not None else torch.empty(shape, dtype=y_dtype, device=xq.device)
+    _check("hq_int_linear_single", load_library().hq_int_linear_single(
+        _ptr(xq), _ptr(x_scale), _ptr(wq3), _ptr(w_scale), _ptr(bias), m, n, kb * 2, had_block,
+        _ptr(y), _DTYPES[y_dtype], _stream()))
     return y

@@ -1,5 +1,7 @@
 // Entry points of the integer GEMM / convolution: argument checks and the choice of the
 // workgroup tile.  The kernels live in hq_int_gemm_kernel.h.
+#include <math.h>
+
 #include "hq_int_gemm_kernel.h"
 
 namespace {
@@ -51,8 +53,23 @@ hq_status int_linear(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
     hq_status st = check_common(xq, x_scale, wq, w_scale, bias, m, n, k, y, y_dtype);
     if (st != HQ_OK) return st;
     if (!fits_32bit(m, 1, n, 1, k)) return HQ_ERR_UNSUPPORTED;
-    GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(m), n, k, 1, 1, 0, 0, 0, 1, sx_static};
+    GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(m), n, k, 1, 1, 0, 0, 0, 1, sx_static,
+               1.0f};
     return launch_gemm(a, 1, y_dtype, static_cast<hipStream_t>(stream));
+}
+
+// Linear layer of the Single scheme: the weights are three digit planes, the kernel keeps one
+// integer sum per plane and weighs plane p by 16^p when it folds the sums into the fp32 result.
+hq_status int_linear_single(const uint8_t *xq, const float *x_scale, const uint8_t *wq3, const float *w_scale,
+                            const void *bias, int64_t m, int n, int k, int had_block, void *y, hq_dtype y_dtype,
+                            void *stream) {
+    hq_status st = check_common(xq, x_scale, wq3, w_scale, bias, m, n, k, y, y_dtype);
+    if (st != HQ_OK) return st;
+    if (!hq::pow2_upto_128(had_block) || k % had_block != 0) return HQ_ERR_SHAPE;
+    if (!fits_32bit(m, 1, n, 3, k)) return HQ_ERR_UNSUPPORTED;
+    const float norm = static_cast<float>(1.0 / sqrt(static_cast<double>(had_block)));
+    GemmArgs a{xq, x_scale, wq3, w_scale, bias, y, static_cast<uint32_t>(m), n, k, 1, 1, 0, 0, 0, 1, 0, norm};
+    return launch_gemm(a, 3, y_dtype, static_cast<hipStream_t>(stream));
 }
 
 hq_status int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq, const float *w_scale,
@@ -70,7 +87,7 @@ hq_status int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
     // one sum over all taps: 256 * (64 per product) * (codes per sum) must stay below 2^31
     if (sx_static && static_cast<int64_t>(c_in) * r * s >= 131072) return HQ_ERR_SHAPE;
     GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(pixels), c_out, c_in, h, w, 0, 0, 0, 1,
-               sx_static};
+               sx_static, 1.0f};
     hipStream_t st_ = static_cast<hipStream_t>(stream);
     // A 3x3 layer with about one 64x64 output tile per CU or fewer cannot fill the machine with
     // whole tiles: it takes the kernel that also splits a tile's K range over waves.
@@ -115,4 +132,10 @@ extern "C" hq_status hq_int_conv2d_static(const uint8_t *xq, const float *x_scal
                                           hq_dtype y_dtype, void *stream) {
     return int_conv2d(xq, x_scale, wq, w_scale, bias, nb, h, w, c_in, c_out, r, s, stride, pad, y, y_dtype, 1,
                       stream);
+}
+
+extern "C" hq_status hq_int_linear_single(const uint8_t *xq, const float *x_scale, const uint8_t *wq3,
+                                          const float *w_scale, const void *bias, int64_t m, int n, int k,
+                                          int had_block, void *y, hq_dtype y_dtype, void *stream) {
+    return int_linear_single(xq, x_scale, wq3, w_scale, bias, m, n, k, had_block, y, y_dtype, stream);
 }

@@ -49,6 +49,7 @@ struct GemmArgs {
     uint32_t cus;        // compute units of the device (workgroups b and b + cus tend to share a CU)
     int sx_static;       // sx is ONE scale for the whole activation tensor (a 3x3 convolution then keeps
                          // one integer sum over all taps)
+    float out_scale;     // factor applied with w_scale (1, or 2^(-log2(block)/2) for digit-plane weights)
 };
 
 namespace {
@@ -59,8 +60,12 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int kOutF16 = 0, kOutF32 = 1, kOutI32 = 2;
 // What a kernel instance computes: a linear layer / 1x1 convolution; a 3x3 convolution whose
 // integer sums are kept per tap (every input pixel has its own scale); a 3x3 convolution with
-// one integer sum over all taps (one scale for the tensor).
-constexpr int kLinear = 0, kConvPerTap = 1, kConvSum = 2;
+// one integer sum over all taps (one scale for the tensor); a linear layer whose weights are
+// three base-16 digit planes [n, 3, k/2] of wider integers (one integer sum per plane, plane p
+// weighted by 16^p when the sums are combined in fp32) - three "taps" that all read the same row.
+constexpr int kLinear = 0, kConvPerTap = 1, kConvSum = 2, kPlanes = 3;
+
+constexpr int taps_of(int kind) { return kind == kLinear ? 1 : (kind == kPlanes ? 3 : 9); }
 
 
 // Output channel handled by row i of a 32-row MFMA tile.  Chosen so that the
@@ -254,8 +259,9 @@ __device__ __forceinline__ void store16(float *dst, const float (&v)[16]) {
 // has scale 0 (int32 output: written as 0).
 template <int TM, int TN, int WAVES_M, int WAVES_N, int KIND, int OUT, int KCH, int NSTAGE, int OCC>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(GemmArgs a) {
-    constexpr int TAPS = KIND == kLinear ? 1 : 9;
-    constexpr bool PER_TAP = KIND == kConvPerTap;   // per-tap sums, combined in fp32 with per-pixel scales
+    constexpr int TAPS = taps_of(KIND);
+    constexpr bool CONV = KIND == kConvPerTap || KIND == kConvSum;   // taps read shifted pixels
+    constexpr bool PER_TAP = KIND == kConvPerTap || KIND == kPlanes; // per-tap sums, combined in fp32
     constexpr bool SUM = KIND == kConvSum;          // one sum over all taps; padding taps load zeros
     constexpr int STAPS = PER_TAP ? TAPS : 1;       // rows of the activation-scale table
     constexpr int NW = WAVES_M * WAVES_N;
@@ -330,7 +336,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
         tile_origin(k, co0, p0);
         if (tid < BP) {
             const uint32_t pix = p0 + tid;
-            s_mask[k & 1][tid] = pix < a.pixels ? tap_mask<TAPS>(pix, a.h, a.w) : 0;
+            int mask = 0;
+            if (pix < a.pixels) {
+                if constexpr (CONV) mask = tap_mask<TAPS>(pix, a.h, a.w);
+                else mask = (1 << TAPS) - 1;
+            }
+            s_mask[k & 1][tid] = mask;
         }
     };
     float t_sx[SX_PER_T], t_sw = 0.f, t_bias = 0.f;
@@ -346,13 +357,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
                 if (e < STAPS * BP) {
                     const int mask = s_mask[k & 1][p];
                     if (PER_TAP ? ((mask >> t) & 1) : (mask != 0)) {
-                        const int delta = PER_TAP ? (t / 3 - 1) * a.w + (t % 3 - 1) : 0;
+                        const int delta = KIND == kConvPerTap ? (t / 3 - 1) * a.w + (t % 3 - 1) : 0;
                         t_sx[j] = a.sx[a.sx_static ? 0 : static_cast<int64_t>(p0 + p) + delta];
                     }
                 }
             }
             if (tid < BCO && co0 + tid < a.n) {
-                t_sw = a.sw[co0 + tid];
+                t_sw = a.sw[co0 + tid] * a.out_scale;
                 const Out *bias = static_cast<const Out *>(a.bias);
                 t_bias = bias ? to_float(bias[co0 + tid]) : 0.f;
             } else {
@@ -366,7 +377,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
 #pragma unroll
             for (int j = 0; j < SX_PER_T; ++j) {
                 const int e = tid + j * NT;
-                if (e < STAPS * BP) (&s_sx[k & 1][0][0])[e] = t_sx[j] * (1.0f / 256.0f);
+                // the sums carry a factor 256 (both operands are 16 x code); digit plane t weighs 16^t
+                const float unit = KIND == kPlanes ? static_cast<float>(1 << (4 * (e / BP))) / 256.0f : 1.0f / 256.0f;
+                if (e < STAPS * BP) (&s_sx[k & 1][0][0])[e] = t_sx[j] * unit;
             }
             if (tid < BCO) {
                 s_sw[k & 1][tid] = t_sw;
@@ -398,7 +411,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
         a_tap_off = static_cast<uint32_t>(t) * kbytes;
 #pragma unroll
         for (int j = 0; j < B_SLOTS; ++j) {
-            if constexpr (TAPS > 1) {
+            if constexpr (CONV) {
                 const uint32_t shift = static_cast<uint32_t>(((t / 3 - 1) * a.w + (t % 3 - 1)) * kbytes);
                 const uint32_t o = ld_b[j] + shift;
                 ld_bcur[j] = o < ld_bmax[j] ? o : ld_bmax[j];
@@ -656,7 +669,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
 
 template <int TM, int TN, int WAVES_M, int WAVES_N, int KIND, int OUT, int KCH, int NSTAGE, int OCC>
 hq_status launch_tile(GemmArgs a, hipStream_t stream) {
-    constexpr int TAPS = KIND == kLinear ? 1 : 9;
+    constexpr int TAPS = taps_of(KIND);
     constexpr int BCO = 32 * TM * WAVES_M, BP = 32 * TN * WAVES_N;
     a.n_co_tiles = (a.n + BCO - 1) / BCO;
     const int64_t p_tiles = (static_cast<int64_t>(a.pixels) + BP - 1) / BP;
@@ -672,8 +685,8 @@ hq_status launch_tile(GemmArgs a, hipStream_t stream) {
     return hq::launch_status();
 }
 
-// All instantiations of one tile configuration: the three kernel kinds (taps = 1: linear;
-// taps = 9: per-tap sums, or one sum if the activation scale is static), the three output
+// All instantiations of one tile configuration: the four kernel kinds (taps = 1: linear;
+// taps = 9: per-tap sums, or one sum if the activation scale is static; taps = 3: digit planes), the three output
 // types, and K chunks of 192 codes (96 contiguous bytes per row) or, if WITH_64 is set, the
 // 64-code fallback for channel counts that are not a multiple of 192.
 template <int TM, int TN, int WAVES_M, int WAVES_N, int OCC, bool WITH_64, int NSTAGE_WIDE = 2>
@@ -696,6 +709,10 @@ hq_status launch_config(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream
         if (y_dtype == HQ_F16) { HQ_GEMM_CASE(kConvSum, kOutF16) }
         if (y_dtype == HQ_F32) { HQ_GEMM_CASE(kConvSum, kOutF32) }
         if (y_dtype == HQ_I32) { HQ_GEMM_CASE(kConvSum, kOutI32) }
+    } else if (taps == 3) {
+        if (y_dtype == HQ_F16) { HQ_GEMM_CASE(kPlanes, kOutF16) }
+        if (y_dtype == HQ_F32) { HQ_GEMM_CASE(kPlanes, kOutF32) }
+        if (y_dtype == HQ_I32) { HQ_GEMM_CASE(kPlanes, kOutI32) }
     }
 #undef HQ_GEMM_CASE
     return HQ_ERR_DTYPE;

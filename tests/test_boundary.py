@@ -117,6 +117,25 @@ def test_static_scale_argument_errors(lib):
     assert conv(*args(cin=96)) == SHAPE
 
 
+def test_single_scheme_argument_errors(lib):
+    wq = lib.hq_quantize_weights_single
+    assert wq(None, 0, 8, 64, 64, 4, P, P, None) == NULL
+    assert wq(P, 2, 8, 64, 64, 4, P, P, None) == DTYPE
+    assert wq(P, 0, 8, 64, 64, 8, P, P, None) == BITS
+    assert wq(P, 0, 0, 64, 64, 4, P, P, None) == SHAPE
+    assert wq(P, 0, 8, 63, 1, 4, P, P, None) == SHAPE        # odd row length
+    assert wq(P, 0, 8, 96, 64, 4, P, P, None) == SHAPE       # block does not divide the row
+    assert wq(P, 0, 8, 768, 256, 4, P, P, None) == SHAPE     # block above 128
+    assert wq(P + 2, 0, 8, 64, 64, 4, P, P, None) == ALIGN
+    lin = lib.hq_int_linear_single
+    assert lin(P, P, None, P, None, 8, 8, 64, 64, P, 0, None) == NULL
+    assert lin(P, None, P, P, None, 8, 8, 64, 64, P, 0, None) == NULL     # scales needed for fp output
+    assert lin(P, P, P, P, None, 8, 8, 96, 32, P, 0, None) == SHAPE       # k not a multiple of 64
+    assert lin(P, P, P, P, None, 8, 8, 192, 128, P, 0, None) == SHAPE     # block does not divide k
+    assert lin(P, P, P, P, None, 8, 8, 64, 64, P, 3, None) == DTYPE
+    assert lin(P, P, P, P, None, 8, 8, 64, 64, P + 4, 0, None) == ALIGN
+
+
 def test_product_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2512_05746_amd")
     for dirpath, _, files in os.walk(pkg):

@@ -137,6 +137,102 @@ def run_layer_static(hq, layer, block=workloads.HAD_BLOCK):
     return flips, err
 
 
+def digit_planes_to_int(planes):
+    """uint8 [n, 3, k/2] signed base-16 digit planes -> int64 [n, k] = d0 + 16 d1 + 256 d2."""
+    d = unpack_codes(planes).astype(np.int64)
+    return d[:, 0] + 16 * d[:, 1] + 256 * d[:, 2]
+
+
+def int_to_digit_planes(b):
+    """int64 [n, k] -> uint8 [n, 3, k/2]: digits in [-8, 7], least significant plane first."""
+    b = b.astype(np.int64)
+    d0 = ((b + 8) % 16) - 8
+    r = (b - d0) // 16
+    d1 = ((r + 8) % 16) - 8
+    d2 = (r - d1) // 16
+    assert np.abs(d2).max(initial=0) <= 7
+    return pack_codes(np.stack([d0, d1, d2], axis=1).astype(np.int8))
+
+
+def run_linear_single(hq, layer, block=workloads.HAD_BLOCK):
+    """The paper's Single scheme on a linear layer: weights quantised without the transform, the
+    integer H_raw folded into three digit planes; the same three layers of checks."""
+    print("layer (single scheme)", layer.name, layer.x_shape, "->", layer.n_out, "block", block, flush=True)
+    x, w, bias = workloads.make_x(layer), workloads.make_w(layer)[:, 0, :], workloads.make_bias(layer)
+    x = x.reshape(-1, layer.k_in)
+    ydt = TORCH_DT[layer.dtype]
+    hb = np.kron(np.eye(layer.k_in // block, dtype=np.int64), np.rint(oracle.hadamard_raw(block)).astype(np.int64))
+
+    xq_o, sx_o, tx = oracle.act_hadamard_quant(x, block, layer.a_bits)
+    wq_o, sw_o, tw = oracle.quantize_weights_single(w, layer.w_bits)
+
+    # (i) quantisers: the digit planes must decode to W_int H_raw for a W_int that matches the oracle's
+    xq_g, sx_g = hq.hq_act_hadamard_quant(dev(x), block, layer.a_bits)
+    wq3_g, sw_g = hq.hq_quantize_weights_single(dev(w), block, layer.w_bits)
+    b_g = digit_planes_to_int(host(wq3_g))
+    back = b_g @ hb                                          # = block * W_int, H_raw H_raw = block I
+    assert (back % block == 0).all(), layer.name + ": planes are not W_int H_raw for any integer W_int"
+    wq_gc = (back // block).astype(np.int8)
+    xq_gc = unpack_codes(host(xq_g))
+    check_scales(layer.name + " x_scale", host(sx_g), sx_o)
+    check_scales(layer.name + " w_scale", host(sw_g), sw_o)
+    flips = check_codes(layer.name + " xq", xq_gc, xq_o, tx, layer.a_bits)
+    flips += check_codes(layer.name + " wq (un-transformed)", wq_gc, wq_o, tw, layer.w_bits)
+
+    # (ii) integer stage on the oracle's codes: the three sums, combined exactly, are the paper's integer
+    acc_o, y_o = oracle.int_linear_single(xq_o, sx_o, wq_o, sw_o, block, bias)
+    planes_o = dev(int_to_digit_planes(wq_o.astype(np.int64) @ hb))
+    acc3 = host(hq.hq_int_linear_single(dev(pack_codes(xq_o)), None, planes_o, None, None, block,
+                                        y_dtype=torch.int32)).astype(np.int64)
+    assert acc3.shape == (x.shape[0], 3, layer.n_out)
+    assert np.array_equal(acc3[:, 0] + 16 * acc3[:, 1] + 256 * acc3[:, 2], acc_o), layer.name + " integer sums"
+    del acc3, acc_o
+
+    # (iii) whole chain
+    if flips:
+        _, y_o = oracle.int_linear_single(xq_gc, sx_o, wq_gc, sw_o, block, bias)
+    bias_d = dev(bias) if bias is not None else None
+    y_g = host(hq.hq_int_linear_single(xq_g, sx_g, wq3_g, sw_g, bias_d, block, y_dtype=ydt))
+    err = check_y(layer.name + " y (single)", y_g, y_o)
+    print("   ok: tie flips %d, y err %.2e" % (flips, err), flush=True)
+    return flips, err
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2])
+def test_single_scheme_tiny_linears(hq, idx):
+    run_linear_single(hq, workloads.tiny_layers()[idx])
+
+
+@pytest.mark.parametrize("block", [1, 16, 128])
+def test_single_scheme_other_block_sizes(hq, block):
+    """H = I (all higher digits zero), a small block, and the largest block (sums up to 8 * 128)."""
+    layer = workloads.tiny_layers()[1]          # k = 128, fp32 input
+    run_linear_single(hq, layer, block)
+
+
+def test_single_scheme_extreme_codes(hq):
+    """Weight rows of constant sign drive W_int H_raw to +-8 * 64 (third digit +-2); the sums of
+    every plane and their combination stay exact."""
+    m, n, k = 70, 40, 192
+    rng = np.random.default_rng(77)
+    xq = rng.integers(-8, 8, (m, k)).astype(np.int8)
+    xq[0], xq[1] = 7, -8
+    wq = rng.integers(-8, 8, (n, k)).astype(np.int8)
+    wq[0], wq[1], wq[2, :64] = -8, 7, -8
+    hb = np.kron(np.eye(k // 64, dtype=np.int64), np.rint(oracle.hadamard_raw(64)).astype(np.int64))
+    b = wq.astype(np.int64) @ hb
+    assert b.min() == -512 and b.max() == 448
+    acc3 = host(hq.hq_int_linear_single(dev(pack_codes(xq)), None, dev(int_to_digit_planes(b)), None, None, 64,
+                                        y_dtype=torch.int32)).astype(np.int64)
+    assert np.array_equal(acc3[:, 0] + 16 * acc3[:, 1] + 256 * acc3[:, 2], oracle.int_gemm_single(xq, wq, 64))
+
+
+@pytest.mark.parametrize("config", [1, 2])
+def test_single_scheme_benchmark_linears_full_size(hq, config):
+    for layer in workloads.config_layers(config):
+        run_linear_single(hq, layer)
+
+
 @pytest.mark.parametrize("layer", workloads.tiny_layers(), ids=lambda l: l.name)
 def test_tiny_layers(hq, layer):
     run_layer(hq, layer)
