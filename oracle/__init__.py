@@ -4,11 +4,13 @@ never by the product package."""
 from .hq_oracle import (  # noqa: F401
     act_hadamard_quant,
     act_hadamard_quant_static,
+    act_width_quant_static,
     block_hadamard,
     build,
     hadamard_raw,
     int_conv2d,
     int_conv2d_static,
+    int_conv2d_width,
     int_gemm,
     int_gemm_single,
     int_linear,

@@ -47,6 +47,16 @@
  *     H_raw the +-1 matrix, block-diagonal over the input channels.  The steps
  *     are taken in that order: the activation codes times H_raw first
  *     (integers up to 8 * block in magnitude), then times the weight codes.
+ *   - Width-axis convolution (the *_width functions): the paper's own
+ *     convolution (Method, "Convolution"): the activation tensor is reshaped to
+ *     rows of one image line each, (B C_in h) x w, and transformed along the
+ *     WIDTH axis, X~ H_c with H_c = BlockDiag(H_k) of size w x w; it is quantised
+ *     with one scale for the tensor; the weights are quantised without any
+ *     transform; and
+ *         Y ~ S S_W 2^(-k/2) Conv( (X~ H_c)_int H_c,raw , W_int ),
+ *     i.e. the integer codes are taken back along the width axis with the +-1
+ *     matrix (integers up to 8 * block in magnitude) and convolved with the
+ *     integer weights, one integer sum over all taps and input channels.
  *
  * All arrays are row-major and owned by the caller.
  */
@@ -321,4 +331,64 @@ int hqo_int_gemm_single(const int8_t *xq, const int8_t *wq, int64_t m, int n, in
     }
     free(h);
     return failed ? -2 : 0;
+}
+
+/* Width-axis convolution, integer stage and dequantisation (Method, "Convolution"):
+ *   u[b, i, :, c] = q[b, i, :, c] * BlockDiag(H_raw)   along the width axis (block | w),
+ *   acc[b, p, q, co] = sum_{r, s, ci} u[b, p*st + r - pad, q*st + s - pad, ci] * wq[co, r, s, ci],
+ *   y = sx * sw[co] * acc / sqrt(block) + bias[co].
+ * xq: [nb, h, w, cin] codes of the width-transformed activations, wq: [cout, r, s, cin] codes
+ * of the un-transformed weights.  acc / y: [nb, ho, wo, cout] or NULL.  Taps outside the image
+ * contribute 0. */
+int hqo_int_conv2d_width(const int8_t *xq, double sx, const int8_t *wq, const double *sw,
+                         const double *bias, int nb, int h, int w, int cin, int cout, int r, int s,
+                         int stride, int pad, int block, int64_t *acc, double *y)
+{
+    if (stride < 1 || pad < 0 || h + 2 * pad < r || w + 2 * pad < s) return -1;
+    if (block < 1 || (block & (block - 1)) || w % block) return -1;
+    const int ho = (h + 2 * pad - r) / stride + 1;
+    const int wo = (w + 2 * pad - s) / stride + 1;
+    double *hm = (double *)malloc(sizeof(double) * (size_t)block * block);
+    int32_t *u = (int32_t *)malloc(sizeof(int32_t) * (size_t)nb * h * w * cin);
+    if (!hm || !u) { free(hm); free(u); return -2; }
+    hqo_hadamard_raw(block, hm);
+    /* the codes times the +-1 matrix along the width axis */
+#pragma omp parallel for schedule(static)
+    for (int64_t line = 0; line < (int64_t)nb * h; ++line)
+        for (int c = 0; c < cin; ++c)
+            for (int b0 = 0; b0 < w; b0 += block)
+                for (int j = 0; j < block; ++j) {
+                    int32_t v = 0;
+                    for (int e = 0; e < block; ++e)
+                        v += (int32_t)xq[((size_t)line * w + b0 + e) * cin + c] * (int32_t)hm[(size_t)e * block + j];
+                    u[((size_t)line * w + b0 + j) * cin + c] = v;
+                }
+    const double norm = 1.0 / sqrt((double)block);
+#pragma omp parallel for schedule(static)
+    for (int64_t pix = 0; pix < (int64_t)nb * ho * wo; ++pix) {
+        const int b = (int)(pix / ((int64_t)ho * wo));
+        const int p = (int)((pix / wo) % ho);
+        const int q = (int)(pix % wo);
+        for (int co = 0; co < cout; ++co) {
+            int64_t a = 0;
+            for (int kr = 0; kr < r; ++kr)
+                for (int ks = 0; ks < s; ++ks) {
+                    const int ih = p * stride + kr - pad;
+                    const int iw = q * stride + ks - pad;
+                    if (ih < 0 || ih >= h || iw < 0 || iw >= w) continue;
+                    const int32_t *ur = u + (((size_t)b * h + ih) * w + iw) * cin;
+                    const int8_t *wr = wq + (((size_t)co * r + kr) * s + ks) * cin;
+                    for (int c = 0; c < cin; ++c) a += (int64_t)ur[c] * (int64_t)wr[c];
+                }
+            if (acc) acc[(size_t)pix * cout + co] = a;
+            if (y) {
+                double v = sx * sw[co] * (double)a * norm;
+                if (bias) v += bias[co];
+                y[(size_t)pix * cout + co] = v;
+            }
+        }
+    }
+    free(hm);
+    free(u);
+    return 0;
 }

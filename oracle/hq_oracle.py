@@ -66,6 +66,9 @@ def _load():
         lib.hqo_int_conv2d_static.restype = i32
         lib.hqo_int_gemm_single.argtypes = [c_i8p, c_i8p, i64, i32, i32, i32, c_i64p]
         lib.hqo_int_gemm_single.restype = i32
+        lib.hqo_int_conv2d_width.argtypes = ([c_i8p, ctypes.c_double, c_i8p, c_dp, c_dp] + [i32] * 10
+                                             + [c_i64p, c_dp])
+        lib.hqo_int_conv2d_width.restype = i32
         lib.hqo_max_threads.argtypes = []
         lib.hqo_max_threads.restype = i32
         _lib = lib
@@ -285,4 +288,42 @@ def int_linear_single(xq, sx, wq, sw, block: int, bias=None):
     y = acc.astype(np.float64) * _f64(sx).reshape(m, 1) * _f64(sw).reshape(1, n) / np.sqrt(float(block))
     if bias is not None:
         y = y + _f64(bias).reshape(1, n)
+    return acc, y
+
+
+# ---- width-axis convolution: the paper's own convolution ---------------------------------------
+
+def act_width_quant_static(x, block: int, bits: int, scale: float):
+    """Activation side of the paper's convolution (Method, "Convolution"): x [N, H, W, C] is
+    transformed along the WIDTH axis (every image line of every channel is one row of X~) and
+    quantised with one scale for the tensor.  Returns (codes [N, H, W, C] int8, t fp64)."""
+    x64 = _f64(x)
+    assert x64.ndim == 4
+    lines = np.ascontiguousarray(np.moveaxis(x64, 2, 3))          # [N, H, C, W]: rows of X~
+    q, t = quantize_static(block_hadamard(lines, block), bits, scale)
+    return (np.ascontiguousarray(np.moveaxis(q, 3, 2)), np.ascontiguousarray(np.moveaxis(t, 3, 2)))
+
+
+def int_conv2d_width(xq, sx: float, wq, sw, block: int, bias=None, stride: int = 1, pad: int = 0,
+                     want_acc: bool = True, want_y: bool = True):
+    """Conv((X~ H_c)_int H_c,raw, W_int), then y = sx * sw[co] * acc / sqrt(block) + bias.
+    xq [N, H, W, Cin] codes of the width-transformed activations, wq [Cout, R, S, Cin] codes of the
+    un-transformed weights.  Returns (acc int64 or None, y fp64 or None), [N, Ho, Wo, Cout]."""
+    xq = np.ascontiguousarray(xq, dtype=np.int8)
+    wq = np.ascontiguousarray(wq, dtype=np.int8)
+    nb, h, w, cin = xq.shape
+    cout, r, s, cin2 = wq.shape
+    assert cin == cin2
+    ho = (h + 2 * pad - r) // stride + 1
+    wo = (w + 2 * pad - s) // stride + 1
+    sw64 = _f64(sw).reshape(cout)
+    b64 = _f64(bias).reshape(cout) if bias is not None else None
+    acc = np.empty((nb, ho, wo, cout), dtype=np.int64) if want_acc else None
+    y = np.empty((nb, ho, wo, cout), dtype=np.float64) if want_y else None
+    rc = _load().hqo_int_conv2d_width(_i8p(xq), float(sx), _i8p(wq), _dp(sw64), _dp(b64), nb, h, w, cin, cout,
+                                      r, s, stride, pad, int(block), _i64p(acc), _dp(y))
+    if rc != 0:
+        raise ValueError("bad geometry or block for the width-axis convolution")
+    if acc is not None:
+        assert np.abs(acc).max(initial=0) < 2**31
     return acc, y

@@ -455,3 +455,92 @@ def test_single_integer_range_and_transform_helps():
         assert np.abs(acc).max() <= 8 * block * 8 * layer.k_in
         err[block] = np.linalg.norm(y - ref) / np.linalg.norm(ref)
     assert err[64] < 0.8 * err[1]
+
+
+# ---- width-axis convolution: the paper's own convolution ---------------------------------------
+
+def width_hadamard(w, block, raw):
+    """BlockDiag of the Sylvester matrix over an axis of length w, from SciPy."""
+    from scipy.linalg import hadamard
+    h = hadamard(block).astype(np.float64)
+    return np.kron(np.eye(w // block), h if raw else h / np.sqrt(block))
+
+
+def test_width_quantiser_transforms_along_the_width_axis():
+    """x [N, H, W, C]: every (image, line, channel) is one row of X~; the transform mixes pixels of
+    a line only, never channels or lines, and the codes are those of the static quantiser."""
+    rng = np.random.default_rng(31)
+    x = rng.standard_normal((2, 3, 16, 5))
+    for block in (1, 4, 16):
+        q, t = oracle.act_width_quant_static(x, block, 4, 0.3)
+        want_t = np.einsum("nhwc,wv->nhvc", x, width_hadamard(16, block, raw=False)) / 0.3
+        assert np.allclose(t, want_t, rtol=1e-12, atol=1e-12)
+        assert np.array_equal(q, np.clip(np.rint(want_t), -8, 7).astype(np.int8))
+    # a one-hot line becomes a flat +-1 pattern along the width, in its own channel only
+    x = np.zeros((1, 1, 8, 3)); x[0, 0, 5, 1] = 8.0
+    q, _ = oracle.act_width_quant_static(x, 8, 4, 8.0 / np.sqrt(8) / 7)
+    assert np.array_equal(np.abs(q[0, 0, :, 1]), np.full(8, 7)) and not q[..., 0].any() and not q[..., 2].any()
+
+
+@pytest.mark.parametrize("ksize,stride,pad,block", [(3, 1, 1, 8), (3, 2, 1, 4), (3, 1, 0, 8), (1, 1, 0, 2), (3, 1, 1, 1)])
+def test_width_conv_vs_brute_force_and_library(ksize, stride, pad, block):
+    """Integer stage against seven nested loops over u = q H_raw (SciPy's matrix), result against
+    conv2d of the dequantised tensors S (q H) and S_W W_int."""
+    rng = np.random.default_rng(40 + ksize + stride + pad + block)
+    nb, h, w, cin, cout = 2, 5, 8, 6, 3
+    xq = rng.integers(-8, 8, (nb, h, w, cin)).astype(np.int8)
+    wq = rng.integers(-8, 8, (cout, ksize, ksize, cin)).astype(np.int8)
+    sw = rng.uniform(0.5, 1.5, cout); bias = rng.standard_normal(cout); sx = 0.21
+    acc, y = oracle.int_conv2d_width(xq, sx, wq, sw, block, bias, stride=stride, pad=pad)
+    u = np.rint(np.einsum("nhwc,wv->nhvc", xq.astype(np.float64), width_hadamard(w, block, raw=True))).astype(np.int64)
+    assert np.abs(u).max() <= 8 * block
+    ho, wo = acc.shape[1], acc.shape[2]
+    brute = np.zeros((nb, ho, wo, cout), dtype=np.int64)
+    for b in range(nb):
+        for p in range(ho):
+            for q in range(wo):
+                for co in range(cout):
+                    for kr in range(ksize):
+                        for ks in range(ksize):
+                            ih, iw = p * stride + kr - pad, q * stride + ks - pad
+                            if 0 <= ih < h and 0 <= iw < w:
+                                for c in range(cin):
+                                    brute[b, p, q, co] += int(u[b, ih, iw, c]) * int(wq[co, kr, ks, c])
+    assert np.array_equal(acc, brute)
+    xhat = sx * np.einsum("nhwc,wv->nhvc", xq.astype(np.float64), width_hadamard(w, block, raw=False))
+    ref = torch.nn.functional.conv2d(torch.from_numpy(xhat).permute(0, 3, 1, 2),
+                                     torch.from_numpy(sw[:, None, None, None] * wq).permute(0, 3, 1, 2),
+                                     torch.from_numpy(bias), stride=stride, padding=pad)
+    assert np.allclose(y, ref.permute(0, 2, 3, 1).numpy(), rtol=1e-12, atol=1e-12)
+
+
+def test_width_conv_block_1_is_the_static_convolution():
+    rng = np.random.default_rng(45)
+    xq = rng.integers(-8, 8, (2, 4, 6, 8)).astype(np.int8)
+    wq = rng.integers(-8, 8, (5, 3, 3, 8)).astype(np.int8)
+    sw = rng.uniform(0.5, 1.5, 5)
+    a1, y1 = oracle.int_conv2d_width(xq, 0.4, wq, sw, 1, None, stride=1, pad=1)
+    a0, y0 = oracle.int_conv2d_static(xq, 0.4, wq, sw, None, stride=1, pad=1)
+    assert np.array_equal(a1, a0) and np.array_equal(y1, y0)
+
+
+def test_width_conv_lossless_case_reduces_to_plain_convolution():
+    """X~ H = s Q exactly and integer-valued weights: nothing is lost, so the scheme must return the
+    fp64 convolution of the original tensors (strided and padded: H never meets the weights)."""
+    rng = np.random.default_rng(46)
+    nb, h, w, cin, cout, block = 2, 6, 16, 4, 3, 16
+    q = rng.integers(-8, 8, (nb, h, w, cin)).astype(np.float64)
+    s = 2.0 ** -3
+    x = np.einsum("nhwc,wv->nhvc", s * q, width_hadamard(w, block, raw=False))     # exact: entries +-1/4
+    qw = rng.integers(-7, 8, (cout, 3, 3, cin)); qw[:, 0, 0, 0] = 7
+    swp = 2.0 ** rng.integers(-6, -1, cout)
+    wgt = swp[:, None, None, None] * qw
+    xq, _ = oracle.act_width_quant_static(x, block, 4, s)
+    assert np.array_equal(xq, q.astype(np.int8))
+    wq, sw, _ = oracle.quantize_weights(wgt.reshape(cout, 9, cin), 1, 4)           # block 1: no transform
+    assert np.array_equal(wq.reshape(cout, 3, 3, cin), qw)
+    for stride, pad in ((1, 1), (2, 1), (1, 0)):
+        _, y = oracle.int_conv2d_width(xq, s, wq.reshape(cout, 3, 3, cin), sw, block, None, stride=stride, pad=pad)
+        ref = torch.nn.functional.conv2d(torch.from_numpy(x).permute(0, 3, 1, 2),
+                                         torch.from_numpy(wgt).permute(0, 3, 1, 2), None, stride=stride, padding=pad)
+        assert np.allclose(y, ref.permute(0, 2, 3, 1).numpy(), rtol=1e-12, atol=1e-12)
