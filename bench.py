@@ -213,6 +213,35 @@ def main():
                               "int_tops_issued": round(3 * layer.ops / i_us / 1e6, 1)})
     torch.cuda.synchronize()
 
+    # ---- the 3x3 layers as the paper's width-axis convolution: activations transformed along the
+    # width axis with one scale, codes taken back with the integer H_raw (three digit planes),
+    # un-transformed quantised weights ----------------------------------------------------------
+    width_layers = []
+    for i, s in enumerate(state):
+        layer, x, wq, sw, xq, sx, y = s
+        if not (layer.kind == "conv" and layer.ksize == 3):
+            continue
+        block = min(64, x.shape[2])
+        w2 = torch.from_numpy(workloads.make_w(layer)).cuda()
+        wq1, sw1 = hq.hq_quantize_weights(w2, 1, layer.w_bits)
+        sx1 = (2.0 * sx.float().median()).reshape(1).contiguous()
+        xu3 = torch.empty((3,) + tuple(xq.shape), dtype=torch.uint8, device="cuda")
+
+        def run_quant_width(_s, x=x, sx1=sx1, xu3=xu3, block=block, layer=layer):
+            hq.hq_act_hadamard_quant_width(x, sx1, block, layer.a_bits, out=xu3)
+
+        def run_conv_width(_s, xu3=xu3, sx1=sx1, wq1=wq1, sw1=sw1, y=y, block=block):
+            hq.hq_int_conv2d_width(xu3, sx1, wq1, sw1, None, block, y_dtype=torch.float16, out=y)
+
+        run_quant_width(s)
+        run_conv_width(s)
+        q_us = batched_us(run_quant_width, s)
+        i_us = batched_us(run_conv_width, s)
+        width_layers.append({"layer": layer.name, "block": block, "quant_us": round(q_us, 2), "int_us": round(i_us, 2),
+                             "int_tops_useful": round(layer.ops / i_us / 1e6, 1),
+                             "int_tops_issued": round(3 * layer.ops / i_us / 1e6, 1)})
+    torch.cuda.synchronize()
+
     conv3 = [i for i, (l, *_r) in enumerate(state) if l.kind == "conv" and l.ksize == 3]
     conv3_ops = sum(state[i][0].ops for i in conv3)
     conv3_us = float(sum(int_us[i] for i in conv3))
@@ -312,6 +341,12 @@ def main():
                     "integer H_raw in three digit planes); useful = 2*M*N*K, issued = three integer passes; "
                     "not part of `value`",
             "layers": single_layers,
+        },
+        "width_axis_mode": {
+            "what": "the 3x3 layers through hq_act_hadamard_quant_width + hq_int_conv2d_width (the paper's own "
+                    "convolution: transform along the width axis, one scale, integer H_raw on the codes, "
+                    "un-transformed weights); useful = 2*M*N*K, issued = three integer passes; not part of `value`",
+            "layers": width_layers,
         },
     }
 

@@ -221,6 +221,49 @@ hq_status hq_int_linear_single(const uint8_t *xq, const float *x_scale, const ui
                                const float *w_scale, const void *bias, int64_t m, int n, int k,
                                int had_block, void *y, hq_dtype y_dtype, void *stream);
 
+/*
+ * ---- Width-axis convolution ----------------------------------------------------
+ *
+ * The paper's own convolution (Method, "Convolution") reshapes the activations to
+ * rows of one image line each, X~ of shape (B C_in h) x w, transforms them along the
+ * WIDTH axis with H_c = BlockDiag(H_k) (w x w), quantises with one scale S for the
+ * tensor, leaves the weights un-transformed, and convolves in integers:
+ *
+ *   Y ~ S S_W 2^(-k/2) Conv( (X~ H_c)_int H_c,raw , W_int ).
+ *
+ * The weight side is hq_quantize_weights with had_block = 1 (no transform).
+ */
+
+/*
+ * q = clamp(rne((X~ H_c) / x_scale[0]), -2^(a_bits-1), 2^(a_bits-1) - 1), then, in exact
+ * integers, u = q * BlockDiag(H_raw) along the width axis (|u| <= 2^(a_bits-1) * had_block),
+ * stored as three signed base-16 digit planes, u = d0 + 16 d1 + 256 d2, digits in [-8, 7].
+ *
+ *   x        [nb, h, w, c] (NHWC) of x_dtype (HQ_F16 | HQ_F32), c even.
+ *   had_block power of two in 1..64 dividing w.
+ *   x_scale  DEVICE pointer to one positive fp32, read when the kernel runs.
+ *   xu3      out, [3, nb, h, w, c / 2] packed digits: plane p is an NHWC tensor of packed nibbles.
+ */
+hq_status hq_act_hadamard_quant_width(const void *x, hq_dtype x_dtype, int nb, int h, int w, int c,
+                                      int had_block, int a_bits, const float *x_scale,
+                                      uint8_t *xu3, void *stream);
+
+/*
+ *   acc[b, p, q, co] = sum_{r, s, ci} u[b, p + r - pad, q + s - pad, ci] * wq[co, r, s, ci]   (int32, exact)
+ *   y[b, p, q, co]   = acc * x_scale[0] * w_scale[co] / sqrt(had_block) + bias[co]
+ *
+ * with u the integers held by the three planes of xu3 (one integer sum per plane, combined
+ * as acc_0 + 16 acc_1 + 256 acc_2).  A tap outside the image contributes 0.
+ *   xu3 [3, nb, h, w, c_in/2], wq [c_out, 3, 3, c_in/2] (codes of the un-transformed weights),
+ *   w_scale [c_out], bias [c_out] of y_dtype or NULL, y [nb, h, w, c_out].
+ * Built: R = S = 3, stride 1, pad 1; c_in a multiple of 64, 9 c_in < 131072.
+ * y_dtype == HQ_I32 writes acc, [nb, h, w, c_out].
+ */
+hq_status hq_int_conv2d_width(const uint8_t *xu3, const float *x_scale, const uint8_t *wq,
+                              const float *w_scale, const void *bias, int nb, int h, int w,
+                              int c_in, int c_out, int r, int s, int stride, int pad,
+                              int had_block, void *y, hq_dtype y_dtype, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,8 @@ _DTYPES = {torch.float16: HQ_F16, torch.float32: HQ_F32, torch.int32: HQ_I32}
 SYMBOLS = ("hq_status_string", "hq_quantize_weights", "hq_act_hadamard_quant",
            "hq_int_linear", "hq_int_conv2d", "hq_act_hadamard_quant_static",
            "hq_int_linear_static", "hq_int_conv2d_static",
-           "hq_quantize_weights_single", "hq_int_linear_single")
+           "hq_quantize_weights_single", "hq_int_linear_single",
+           "hq_act_hadamard_quant_width", "hq_int_conv2d_width")
 
 
 class HqError(RuntimeError):
@@ -54,6 +55,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.hq_int_conv2d_static.argtypes = lib.hq_int_conv2d.argtypes
     lib.hq_quantize_weights_single.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp]
     lib.hq_int_linear_single.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, vp, i32, vp]
+    lib.hq_act_hadamard_quant_width.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]
+    lib.hq_int_conv2d_width.argtypes = [vp] * 5 + [i32] * 10 + [vp, i32, vp]
     for name in SYMBOLS[1:]:
         getattr(lib, name).restype = i32
     _lib = lib
@@ -250,4 +253,43 @@ def hq_int_linear_single(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq3:
     _check("hq_int_linear_single", load_library().hq_int_linear_single(
         _ptr(xq), _ptr(x_scale), _ptr(wq3), _ptr(w_scale), _ptr(bias), m, n, kb * 2, had_block,
         _ptr(y), _DTYPES[y_dtype], _stream()))
+    return y
+
+
+# ---- width-axis convolution: the paper's own convolution ---------------------------------------
+
+def hq_act_hadamard_quant_width(x: torch.Tensor, x_scale: torch.Tensor, had_block: int, a_bits: int = 4,
+                                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """x [N, H, W, C] fp16/fp32, x_scale one fp32 on the device -> xu3 uint8 [3, N, H, W, C/2]
+    (digit planes of the codes taken back along the width axis with the +-1 matrix)."""
+    _dev(x, "x")
+    _scalar(x_scale)
+    if x.dim() != 4:
+        raise ValueError("x must be [N, H, W, C]")
+    nb, h, w, c = x.shape
+    xu3 = out if out is not None else torch.empty((3, nb, h, w, c // 2), dtype=torch.uint8, device=x.device)
+    _check("hq_act_hadamard_quant_width", load_library().hq_act_hadamard_quant_width(
+        _ptr(x), _DTYPES[x.dtype], nb, h, w, c, had_block, a_bits, _ptr(x_scale), _ptr(xu3), _stream()))
+    return xu3
+
+
+def hq_int_conv2d_width(xu3: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torch.Tensor,
+                        w_scale: Optional[torch.Tensor], bias: Optional[torch.Tensor] = None,
+                        had_block: int = 64, y_dtype: torch.dtype = torch.float16,
+                        out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """xu3 [3, N, H, W, Cin/2], wq [Cout, 9, Cin/2] (or [Cout, 3, 3, Cin/2]) -> y [N, H, W, Cout];
+    y_dtype int32 returns the exact integer sums."""
+    _dev(xu3, "xu3"), _dev(wq, "wq")
+    if xu3.dim() != 5 or xu3.shape[0] != 3:
+        raise ValueError("xu3 must be [3, N, H, W, Cin/2]")
+    _, nb, h, w, kb = xu3.shape
+    c_out = wq.shape[0]
+    if wq.numel() != c_out * 9 * kb:
+        raise ValueError("wq does not match xu3 in Cin or is not a 3x3 kernel")
+    if bias is not None and bias.dtype != y_dtype:
+        raise ValueError("bias must have the output dtype")
+    y = out if out is not None else torch.empty((nb, h, w, c_out), dtype=y_dtype, device=xu3.device)
+    _check("hq_int_conv2d_width", load_library().hq_int_conv2d_width(
+        _ptr(xu3), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), nb, h, w, kb * 2, c_out, 3, 3, 1, 1,
+        had_block, _ptr(y), _DTYPES[y_dtype], _stream()))
     return y

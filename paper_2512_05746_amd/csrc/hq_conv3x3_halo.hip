@@ -67,7 +67,7 @@ template <int KIND, int OUT>
 __global__ __launch_bounds__(256, KIND == kConvSum ? 3 : 2) void conv3x3_halo_kernel(HaloArgs a) {
     constexpr bool PER_TAP = KIND == kConvPerTap;
     constexpr bool SUM = KIND == kConvSum;
-    constexpr int TM = 2, TN = 2, NW = 4, KCH = 6, ROWB = KCH * 16, KS = KCH / 2, TAPS = 9;
+    constexpr int TM = 2, TN = 2, NW = 4, KCH = 6, ROWB = KCH * 16, TAPS = 9;
     constexpr int BCO = 64, BP = 256;
     constexpr int A_BYTES = BCO * ROWB;               // weight rows of one tap and slice: six 1 KiB loads
     constexpr int NA = 2;                             // stages of the weight stream

@@ -104,6 +104,30 @@ hq_status int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
     return launch_gemm(a, r * s, y_dtype, st_);
 }
 
+// The paper's width-axis convolution: the activations arrive as three digit planes of the integers
+// (X~ H_c)_int H_c,raw; the kernel walks 27 steps (plane-major), keeps one integer sum per plane
+// over its nine taps (taps outside the image load zeros) and weighs plane p by 16^p.
+hq_status int_conv2d_width(const uint8_t *xu3, const float *x_scale, const uint8_t *wq, const float *w_scale,
+                           const void *bias, int nb, int h, int w, int c_in, int c_out, int r, int s, int stride,
+                           int pad, int had_block, void *y, hq_dtype y_dtype, void *stream) {
+    if (nb <= 0 || h <= 0 || w <= 0 || r <= 0 || s <= 0 || stride <= 0 || pad < 0) {
+        if (!xu3 || !wq || !y) return HQ_ERR_NULL;
+        return HQ_ERR_SHAPE;
+    }
+    const int64_t pixels = static_cast<int64_t>(nb) * h * w;
+    hq_status st = check_common(xu3, x_scale, wq, w_scale, bias, pixels, c_out, c_in, y, y_dtype);
+    if (st != HQ_OK) return st;
+    if (!hq::pow2_upto_128(had_block) || had_block > 64 || w % had_block != 0) return HQ_ERR_SHAPE;
+    if (r != 3 || s != 3 || stride != 1 || pad != 1) return HQ_ERR_UNSUPPORTED;
+    // three planes of activations behind one 32-bit offset; 256 * 64 * (codes per plane sum) below 2^31
+    if (!fits_32bit(3 * pixels, w, c_out, 9, c_in)) return HQ_ERR_UNSUPPORTED;
+    if (static_cast<int64_t>(c_in) * 9 >= 131072) return HQ_ERR_SHAPE;
+    const float norm = static_cast<float>(1.0 / sqrt(static_cast<double>(had_block)));
+    GemmArgs a{xu3, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(pixels), c_out, c_in, h, w, 0, 0, 0, 1,
+               1, norm};
+    return launch_gemm(a, 27, y_dtype, static_cast<hipStream_t>(stream));
+}
+
 }  // namespace
 
 extern "C" hq_status hq_int_linear(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
@@ -138,4 +162,12 @@ extern "C" hq_status hq_int_linear_single(const uint8_t *xq, const float *x_scal
                                           const float *w_scale, const void *bias, int64_t m, int n, int k,
                                           int had_block, void *y, hq_dtype y_dtype, void *stream) {
     return int_linear_single(xq, x_scale, wq3, w_scale, bias, m, n, k, had_block, y, y_dtype, stream);
+}
+
+extern "C" hq_status hq_int_conv2d_width(const uint8_t *xu3, const float *x_scale, const uint8_t *wq,
+                                         const float *w_scale, const void *bias, int nb, int h, int w,
+                                         int c_in, int c_out, int r, int s, int stride, int pad,
+                                         int had_block, void *y, hq_dtype y_dtype, void *stream) {
+    return int_conv2d_width(xu3, x_scale, wq, w_scale, bias, nb, h, w, c_in, c_out, r, s, stride, pad, had_block,
+                            y, y_dtype, stream);
 }

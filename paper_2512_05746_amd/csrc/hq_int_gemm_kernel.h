@@ -62,10 +62,15 @@ constexpr int kOutF16 = 0, kOutF32 = 1, kOutI32 = 2;
 // integer sums are kept per tap (every input pixel has its own scale); a 3x3 convolution with
 // one integer sum over all taps (one scale for the tensor); a linear layer whose weights are
 // three base-16 digit planes [n, 3, k/2] of wider integers (one integer sum per plane, plane p
-// weighted by 16^p when the sums are combined in fp32) - three "taps" that all read the same row.
-constexpr int kLinear = 0, kConvPerTap = 1, kConvSum = 2, kPlanes = 3;
+// weighted by 16^p when the sums are combined in fp32) - three "taps" that all read the same row;
+// a 3x3 convolution whose ACTIVATIONS are three such digit planes [3, pixels, k/2] (one scale for
+// the tensor): 27 steps, plane-major, one integer sum per plane over its nine taps.
+constexpr int kLinear = 0, kConvPerTap = 1, kConvSum = 2, kPlanes = 3, kConvPlanes = 4;
 
-constexpr int taps_of(int kind) { return kind == kLinear ? 1 : (kind == kPlanes ? 3 : 9); }
+// steps of a tile's tap loop
+constexpr int taps_of(int kind) {
+    return kind == kLinear ? 1 : (kind == kPlanes ? 3 : (kind == kConvPlanes ? 27 : 9));
+}
 
 
 // Output channel handled by row i of a 32-row MFMA tile.  Chosen so that the
@@ -260,9 +265,12 @@ __device__ __forceinline__ void store16(float *dst, const float (&v)[16]) {
 template <int TM, int TN, int WAVES_M, int WAVES_N, int KIND, int OUT, int KCH, int NSTAGE, int OCC>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(GemmArgs a) {
     constexpr int TAPS = taps_of(KIND);
-    constexpr bool CONV = KIND == kConvPerTap || KIND == kConvSum;   // taps read shifted pixels
-    constexpr bool PER_TAP = KIND == kConvPerTap || KIND == kPlanes; // per-tap sums, combined in fp32
-    constexpr bool SUM = KIND == kConvSum;          // one sum over all taps; padding taps load zeros
+    constexpr int WTAPS = KIND == kConvPlanes ? 9 : TAPS;             // taps of the weight tensor [n, WTAPS, k/2]
+    constexpr bool CONV = KIND == kConvPerTap || KIND == kConvSum || KIND == kConvPlanes;   // taps read shifted pixels
+    constexpr bool PER_TAP = KIND == kConvPerTap || KIND == kPlanes;  // one integer sum and one scale row per tap
+    constexpr bool SUM = KIND == kConvSum;                            // one integer sum over all taps
+    constexpr bool ZPAD = KIND == kConvSum || KIND == kConvPlanes;    // taps outside the image load zeros
+    constexpr bool FACC = PER_TAP || KIND == kConvPlanes;             // integer sums are folded into fp32 sums
     constexpr int STAPS = PER_TAP ? TAPS : 1;       // rows of the activation-scale table
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int NT = 64 * NW;
@@ -338,7 +346,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
             const uint32_t pix = p0 + tid;
             int mask = 0;
             if (pix < a.pixels) {
-                if constexpr (CONV) mask = tap_mask<TAPS>(pix, a.h, a.w);
+                if constexpr (CONV) mask = tap_mask<9>(pix, a.h, a.w);
                 else mask = (1 << TAPS) - 1;
             }
             s_mask[k & 1][tid] = mask;
@@ -393,8 +401,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     uint32_t ld_b[B_SLOTS];      // activation rows: the same, at the tile's own pixel
     uint32_t ld_bmax[B_SLOTS];   // ... at the last pixel of the tensor
     uint32_t ld_bcur[B_SLOTS];   // ... at the pixel under the tap being fetched
-    int ld_mask[SUM ? B_SLOTS : 1];        // one sum over all taps: the row's tap mask ...
-    uint32_t ld_zero[SUM ? B_SLOTS : 1];   // ... and this lane's piece of the zero row
+    int ld_mask[ZPAD ? B_SLOTS : 1];        // zeros outside the image: the row's tap mask ...
+    uint32_t ld_zero[ZPAD ? B_SLOTS : 1];   // ... and this lane's piece of the zero row
     uint32_t a_tap_off = 0;      // uniform: tap being fetched * kbytes
     uint32_t fk = 0;             // tile (index in this workgroup's list) being fetched
     int ftap = 0, fch = 0;
@@ -407,7 +415,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     };
 #pragma unroll
     for (int j = 0; j < B_SLOTS; ++j) ld_bmax[j] = (a.pixels - 1) * kbytes + slot_byte(j * NW + wave);
-    auto set_fetch_tap = [&](int t) {
+    auto set_fetch_tap = [&](int step) {
+        const int t = step % WTAPS;   // tap of the 3x3 window (digit planes: step = plane * 9 + tap)
         a_tap_off = static_cast<uint32_t>(t) * kbytes;
 #pragma unroll
         for (int j = 0; j < B_SLOTS; ++j) {
@@ -415,6 +424,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
                 const uint32_t shift = static_cast<uint32_t>(((t / 3 - 1) * a.w + (t % 3 - 1)) * kbytes);
                 const uint32_t o = ld_b[j] + shift;
                 ld_bcur[j] = o < ld_bmax[j] ? o : ld_bmax[j];
+                if constexpr (KIND == kConvPlanes) ld_bcur[j] += static_cast<uint32_t>(step / 9) * (a.pixels * kbytes);
             } else {
                 ld_bcur[j] = ld_b[j];
             }
@@ -428,7 +438,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
             const int i = j * NW + wave, row = slot_row(i);
             int co = co0 + (row & ~31) + tile_row_to_channel(row & 31);
             co = co < a.n ? co : a.n - 1;
-            ld_a[j] = static_cast<uint32_t>(co) * TAPS * kbytes + slot_byte(i);
+            ld_a[j] = static_cast<uint32_t>(co) * WTAPS * kbytes + slot_byte(i);
         }
 #pragma unroll
         for (int j = 0; j < B_SLOTS; ++j) {
@@ -436,7 +446,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
             uint32_t pix = p0 + slot_row(i);
             pix = pix < a.pixels ? pix : a.pixels - 1;
             ld_b[j] = pix * kbytes + slot_byte(i);
-            if constexpr (SUM) {   // needs the masks of tile k to be visible
+            if constexpr (ZPAD) {   // needs the masks of tile k to be visible
                 ld_mask[j] = i < B_INSTR ? s_mask[k & 1][slot_row(i)] : 0;
                 ld_zero[j] = slot_byte(i);
             }
@@ -457,8 +467,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
             const int i = j * NW + wave;
             if (i < B_INSTR) {
                 const uint8_t *src = base_b + ld_bcur[j];
-                if constexpr (SUM) {
-                    if (!((ld_mask[j] >> ftap) & 1)) src = g_zero_row + ld_zero[j];
+                if constexpr (ZPAD) {
+                    if (!((ld_mask[j] >> (ftap % WTAPS)) & 1)) src = g_zero_row + ld_zero[j];
                 }
                 load_to_lds16(src, image + BCO * ROWB + i * 1024);
             }
@@ -503,14 +513,25 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
         const uint32_t lds_a = lds_row + wm * TM * 32 * ROWB;
 
         v16i acc[TM][TN];
-        float facc[PER_TAP ? TM : 1][PER_TAP ? TN : 1][16];
-        if constexpr (PER_TAP) {
+        float facc[FACC ? TM : 1][FACC ? TN : 1][16];
+        if constexpr (FACC) {
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) facc[tm][tn][r] = 0.f;
+        }
+        // digit planes of the activations, integer output: the exact sum over the planes
+        constexpr bool ISUM = KIND == kConvPlanes && OUT == kOutI32;
+        int iacc[ISUM ? TM : 1][ISUM ? TN : 1][16];
+        if constexpr (ISUM) {
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) iacc[tm][tn][r] = 0;
         }
 
         // MFMAs of one K step; first: the sums of a tap start from 0
@@ -574,15 +595,42 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
                 const uint32_t sa = lds_a + stage * STAGE_BYTES, sb = lds_b + stage * STAGE_BYTES;
                 Ops op[2];
                 read_packed<TM, TN, ROWB, 0>(op[0], sa, sb);
-                chunk_steps<0, KS, TM, TN, ROWB>(op, sa, sb, SUM ? chunk == 0 : ch == 0, multiply);
+                const bool sum_starts = SUM ? chunk == 0 : (KIND == kConvPlanes ? ch == 0 && tap % 9 == 0 : ch == 0);
+                chunk_steps<0, KS, TM, TN, ROWB>(op, sa, sb, sum_starts, multiply);
             }
 
             if (++ch == chunks_per_tap) {
                 ch = 0;
                 // ---- end of a tap: fold the integer sums into the result (one sum over all taps:
                 // nothing to do before the last tap) ---------------------------------------------
-                if (active && (!SUM || tap == TAPS - 1)) {
-                if constexpr (OUT == kOutI32) {
+                const bool sum_ends = SUM ? tap == TAPS - 1 : (KIND == kConvPlanes ? tap % 9 == 8 : true);
+                if (active && sum_ends) {
+                if constexpr (ISUM) {
+                    // 256 x the plane's sum, weighted by 16^plane; stored after the last plane
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) iacc[tm][tn][r] += (acc[tm][tn][r] >> 8) * (1 << (4 * (tap / 9)));
+                    if (tap == TAPS - 1) {
+                        int *yi = static_cast<int *>(a.y);
+#pragma unroll
+                        for (int tn = 0; tn < TN; ++tn) {
+                            const uint32_t pix = p0 + (wave_n * TN + tn) * 32 + lrow;
+#pragma unroll
+                            for (int tm = 0; tm < TM; ++tm) {
+                                const int cbase = co0 + (wm * TM + tm) * 32 + 16 * lhalf;
+                                if (pix < a.pixels) {
+                                    int *dst = yi + static_cast<int64_t>(pix) * a.n + cbase;
+#pragma unroll
+                                    for (int r = 0; r < 16; ++r)
+                                        if (cbase + r < a.n) dst[r] = iacc[tm][tn][r];
+                                }
+                            }
+                        }
+                    }
+                } else if constexpr (OUT == kOutI32) {
                     int *yi = static_cast<int *>(a.y);
                     constexpr int OUT_TAPS = SUM ? 1 : TAPS;   // sums stored per output pixel
 #pragma unroll
@@ -602,9 +650,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
                             }
                         }
                     }
-                } else if constexpr (PER_TAP) {
+                } else if constexpr (FACC) {
                     float s[TN];
-                    read_tap_scales<TN>(s, lds_sx + (tb * TAPS + tap) * BP * 4);
+                    read_tap_scales<TN>(s, lds_sx + (tb * STAPS + (PER_TAP ? tap : 0)) * BP * 4);
+                    if constexpr (KIND == kConvPlanes) {   // the plane's weight 16^plane
+                        const float weight = static_cast<float>(1 << (4 * (tap / 9)));
+#pragma unroll
+                        for (int tn = 0; tn < TN; ++tn) s[tn] *= weight;
+                    }
 #pragma unroll
                     for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
@@ -649,7 +702,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         float s;
-                        if constexpr (PER_TAP) s = facc[tm][tn][r];
+                        if constexpr (FACC) s = facc[tm][tn][r];
                         else s = s_sx[tb][0][prow] * static_cast<float>(acc[tm][tn][r]);
                         out[r] = s * swv[r] + bv[r];
                     }
@@ -713,6 +766,10 @@ hq_status launch_config(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream
         if (y_dtype == HQ_F16) { HQ_GEMM_CASE(kPlanes, kOutF16) }
         if (y_dtype == HQ_F32) { HQ_GEMM_CASE(kPlanes, kOutF32) }
         if (y_dtype == HQ_I32) { HQ_GEMM_CASE(kPlanes, kOutI32) }
+    } else if (taps == 27) {
+        if (y_dtype == HQ_F16) { HQ_GEMM_CASE(kConvPlanes, kOutF16) }
+        if (y_dtype == HQ_F32) { HQ_GEMM_CASE(kConvPlanes, kOutF32) }
+        if (y_dtype == HQ_I32) { HQ_GEMM_CASE(kConvPlanes, kOutI32) }
     }
 #undef HQ_GEMM_CASE
     return HQ_ERR_DTYPE;

@@ -136,6 +136,28 @@ def test_single_scheme_argument_errors(lib):
     assert lin(P, P, P, P, None, 8, 8, 64, 64, P + 4, 0, None) == ALIGN
 
 
+def test_width_axis_argument_errors(lib):
+    q = lib.hq_act_hadamard_quant_width
+    assert q(P, 0, 1, 4, 8, 64, 8, 4, None, P, None) == NULL
+    assert q(P, 2, 1, 4, 8, 64, 8, 4, P, P, None) == DTYPE
+    assert q(P, 0, 1, 4, 8, 64, 8, 5, P, P, None) == BITS
+    assert q(P, 0, 1, 4, 8, 63, 8, 4, P, P, None) == SHAPE       # odd channel count
+    assert q(P, 0, 1, 4, 12, 64, 8, 4, P, P, None) == SHAPE      # block does not divide the width
+    assert q(P, 0, 1, 4, 128, 64, 128, 4, P, P, None) == SHAPE   # block above 64
+    assert q(P, 0, 1, 4, 8, 64, 8, 4, P + 2, P, None) == ALIGN
+    conv = lib.hq_int_conv2d_width
+    args = lambda **kw: [kw.get(k, d) for k, d in [
+        ("xu3", P), ("sx", P), ("wq", P), ("sw", P), ("bias", None), ("nb", 1), ("h", 4), ("w", 8),
+        ("cin", 64), ("cout", 8), ("r", 3), ("s", 3), ("stride", 1), ("pad", 1), ("block", 8), ("y", P),
+        ("dt", 0), ("stream", None)]]
+    assert conv(*args(xu3=None)) == NULL
+    assert conv(*args(sx=None)) == NULL
+    assert conv(*args(block=16)) == SHAPE
+    assert conv(*args(cin=96)) == SHAPE
+    assert conv(*args(r=1, s=1, pad=0)) == UNSUPPORTED
+    assert conv(*args(stride=2)) == UNSUPPORTED
+
+
 def test_product_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2512_05746_amd")
     for dirpath, _, files in os.walk(pkg):

@@ -233,6 +233,70 @@ def test_single_scheme_benchmark_linears_full_size(hq, config):
         run_linear_single(hq, layer)
 
 
+def run_conv_width(hq, layer, block):
+    """The paper's width-axis convolution on a 3x3 layer: activations transformed along the width
+    axis and quantised with one scale, the codes taken back with the integer H_raw (three digit
+    planes), weights quantised without a transform; the same three layers of checks."""
+    print("layer (width axis)", layer.name, layer.x_shape, "->", layer.n_out, "block", block, flush=True)
+    x, w, bias = workloads.make_x(layer), workloads.make_w(layer), workloads.make_bias(layer)
+    nb, h, wd, cin = x.shape
+    ydt = TORCH_DT[layer.dtype]
+    qmax = 2 ** (layer.a_bits - 1) - 1
+    hb = np.kron(np.eye(wd // block, dtype=np.int64), np.rint(oracle.hadamard_raw(block)).astype(np.int64))
+    along_w = lambda a: np.einsum("nhwc,wv->nhvc", a, hb)
+    # one scale for the tensor, small enough for the clamp to be at work
+    xt = oracle.block_hadamard(np.moveaxis(x.astype(np.float64), 2, 3), block)
+    s = float(np.float32(np.percentile(np.abs(xt), 99.5) / qmax))
+    s_d = torch.tensor([s], dtype=torch.float32, device="cuda")
+    wq4 = lambda c: c.reshape(layer.n_out, 3, 3, cin)
+
+    xq_o, tx = oracle.act_width_quant_static(x, block, layer.a_bits, s)
+    assert (tx > qmax + 0.5).any() and (tx < -qmax - 1.5).any(), "the test scale does not clamp"
+    wq_o, sw_o, tw = oracle.quantize_weights(w, 1, layer.w_bits)
+
+    # (i) quantisers: the planes must decode to q H_raw (along the width) for codes q matching the oracle's
+    xu3_g = hq.hq_act_hadamard_quant_width(dev(x), s_d, block, layer.a_bits)
+    d = unpack_codes(host(xu3_g)).astype(np.int64)                    # [3, N, H, W, C]
+    back = along_w(d[0] + 16 * d[1] + 256 * d[2])                      # = block * q
+    assert (back % block == 0).all(), layer.name + ": planes are not q H_raw for any integer q"
+    xq_gc = (back // block).astype(np.int8)
+    flips = check_codes(layer.name + " xq (width)", xq_gc, xq_o, tx, layer.a_bits)
+    wq_g, sw_g = hq.hq_quantize_weights(dev(w), 1, layer.w_bits)
+    wq_gc = unpack_codes(host(wq_g))
+    check_scales(layer.name + " w_scale", host(sw_g), sw_o)
+    flips += check_codes(layer.name + " wq (un-transformed)", wq_gc, wq_o, tw, layer.w_bits)
+
+    # (ii) integer stage on the oracle's codes
+    acc_o, y_o = oracle.int_conv2d_width(xq_o, s, wq4(wq_o), sw_o, block, bias, stride=1, pad=1)
+    u = along_w(xq_o.astype(np.int64))
+    d0 = ((u + 8) % 16) - 8
+    r1 = (u - d0) // 16
+    d1 = ((r1 + 8) % 16) - 8
+    planes_o = dev(pack_codes(np.stack([d0, d1, (r1 - d1) // 16]).astype(np.int8)))
+    acc_g = host(hq.hq_int_conv2d_width(planes_o, None, dev(pack_codes(wq_o)), None, None, block, y_dtype=torch.int32))
+    assert np.array_equal(acc_g, acc_o), layer.name + " integer sums (width)"
+    del acc_g, acc_o, u, d0, d1, r1, d
+
+    # (iii) whole chain
+    if flips:
+        _, y_o = oracle.int_conv2d_width(xq_gc, s, wq4(wq_gc), sw_o, block, bias, stride=1, pad=1, want_acc=False)
+    bias_d = dev(bias) if bias is not None else None
+    y_g = host(hq.hq_int_conv2d_width(xu3_g, s_d, wq_g, sw_g, bias_d, block, y_dtype=ydt))
+    err = check_y(layer.name + " y (width)", y_g, y_o)
+    print("   ok: tie flips %d, y err %.2e" % (flips, err), flush=True)
+    return flips, err
+
+
+@pytest.mark.parametrize("idx,block", [(3, 1), (4, 4), (6, 1), (7, 16), (7, 2)])
+def test_width_conv_tiny_layers(hq, idx, block):
+    run_conv_width(hq, workloads.tiny_layers()[idx], block)
+
+
+@pytest.mark.parametrize("config,index,block", [(3, 0, 32), (5, 0, 64), (5, 1, 32), (5, 3, 8)])
+def test_width_conv_benchmark_layers_full_size(hq, config, index, block):
+    run_conv_width(hq, workloads.config_layers(config)[index], block)
+
+
 @pytest.mark.parametrize("layer", workloads.tiny_layers(), ids=lambda l: l.name)
 def test_tiny_layers(hq, layer):
     run_layer(hq, layer)
