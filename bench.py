@@ -242,6 +242,33 @@ def main():
                              "int_tops_issued": round(3 * layer.ops / i_us / 1e6, 1)})
     torch.cuda.synchronize()
 
+    # ---- the same sweep with 8-bit codes for both operands (one int8 code per byte) ---------------
+    w8a8_layers = []
+    for i, s in enumerate(state):
+        layer, x, wq, sw, xq, sx, y = s
+        w2 = torch.from_numpy(workloads.make_w(layer)).cuda()
+        wq8, sw8 = hq.hq_quantize_weights(w2, workloads.HAD_BLOCK, 8)
+        xq8 = torch.empty(x.shape, dtype=torch.int8, device="cuda")
+
+        def run_quant8(_s, x=x, xq8=xq8, sx=sx):
+            hq.hq_act_hadamard_quant(x, workloads.HAD_BLOCK, 8, out=(xq8, sx))
+
+        def run_int8(_s, layer=layer, xq8=xq8, sx=sx, wq8=wq8, sw8=sw8, y=y):
+            if layer.kind == "conv":
+                hq.hq_int_conv2d_i8(xq8, sx, wq8, sw8, None, ksize=layer.ksize, y_dtype=torch.float16, out=y)
+            else:
+                hq.hq_int_linear_i8(xq8.reshape(layer.m, -1), sx.reshape(-1), wq8, sw8, None,
+                                    y_dtype=torch.float16, out=y.reshape(layer.m, -1))
+
+        run_quant8(s)
+        run_int8(s)
+        q_us = batched_us(run_quant8, s)
+        i_us = batched_us(run_int8, s)
+        w8a8_layers.append({"layer": layer.name, "int_us": round(i_us, 2),
+                            "int_tops": round(layer.ops / i_us / 1e6, 1), "quant_us": round(q_us, 2)})
+        run_quant(s)   # restore the 4-bit scales for anything that follows
+    torch.cuda.synchronize()
+
     conv3 = [i for i, (l, *_r) in enumerate(state) if l.kind == "conv" and l.ksize == 3]
     conv3_ops = sum(state[i][0].ops for i in conv3)
     conv3_us = float(sum(int_us[i] for i in conv3))
@@ -347,6 +374,14 @@ def main():
                     "convolution: transform along the width axis, one scale, integer H_raw on the codes, "
                     "un-transformed weights); useful = 2*M*N*K, issued = three integer passes; not part of `value`",
             "layers": width_layers,
+        },
+        "w8a8_mode": {
+            "what": "the same sweep with 8-bit codes for both operands (int8 straight into the matrix "
+                    "instruction, no nibble expansion); not part of `value`",
+            "conv3x3_tops_kernel_time": round(conv3_ops / sum(w8a8_layers[i]["int_us"] for i in conv3) / 1e6, 1),
+            "frac_int8_mfma_peak": round(conv3_ops / sum(w8a8_layers[i]["int_us"] for i in conv3) / 1e6
+                                         / INT8_MFMA_PEAK_TOPS, 4),
+            "layers": w8a8_layers,
         },
     }
 

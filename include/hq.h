@@ -66,7 +66,8 @@ const char *hq_status_string(hq_status s);
  *            convolution stored [Cout, R, S, Cin].
  *   had_block power of two in 1..128 dividing k_in; the transform runs along
  *            k_in inside every (n_out, tap) row; 1 means H = I.
- *   w_bits   4 (codes in [-8, 7]) or 3.
+ *   w_bits   4 (codes in [-8, 7]), 3, or 8 (codes in [-128, 127], ONE int8 code per byte:
+ *            wq is then [n_out, taps, k_in] bytes; see the 8-bit section below).
  *   wq       out, [n_out, taps, k_in / 2] packed codes.
  *   w_scale  out, [n_out] fp32: max |transformed row over all taps| / (2^(w_bits-1) - 1),
  *            1.0 for an all-zero channel.
@@ -83,7 +84,8 @@ hq_status hq_quantize_weights(const void *w, hq_dtype w_dtype, int n_out, int ta
  *   x        [m, k] of x_dtype (HQ_F16 | HQ_F32).  NHWC activations are passed
  *            with m = N*H*W and k = C.
  *   had_block power of two in 1..128 dividing k; k must be a multiple of 8.
- *   a_bits   4 (codes in [-8, 7]) or 3 (codes in [-4, 3]).
+ *   a_bits   4 (codes in [-8, 7]), 3 (codes in [-4, 3]), or 8 (codes in [-128, 127], ONE int8
+ *            code per byte: xq is then [m, k] bytes; see the 8-bit section below).
  *   xq       out, [m, k / 2] packed codes.
  *   x_scale  out, [m] fp32: max |transformed token| / (2^(a_bits-1) - 1), 1.0 for an
  *            all-zero token.
@@ -263,6 +265,26 @@ hq_status hq_int_conv2d_width(const uint8_t *xu3, const float *x_scale, const ui
                               const float *w_scale, const void *bias, int nb, int h, int w,
                               int c_in, int c_out, int r, int s, int stride, int pad,
                               int had_block, void *y, hq_dtype y_dtype, void *stream);
+
+/*
+ * ---- 8-bit codes (W8A8) ---------------------------------------------------------
+ *
+ * The same layer at 8 bits for both operands (the paper's higher-precision setting;
+ * Background, "Model Quantization" with N = 8): hq_act_hadamard_quant and
+ * hq_quantize_weights with a_bits = w_bits = 8 write one int8 code per byte (xq [m, k],
+ * wq [n_out, taps, k_in]); the two calls below take such codes.  The codes feed the int8
+ * matrix instruction as they are.  Everything else (scales, per-tap sums of a convolution,
+ * bias, HQ_I32 outputs, built geometries, error behaviour) is as in hq_int_linear /
+ * hq_int_conv2d; k (c_in) a multiple of 64.
+ */
+hq_status hq_int_linear_i8(const int8_t *xq, const float *x_scale, const int8_t *wq,
+                           const float *w_scale, const void *bias, int64_t m, int n, int k,
+                           void *y, hq_dtype y_dtype, void *stream);
+
+hq_status hq_int_conv2d_i8(const int8_t *xq, const float *x_scale, const int8_t *wq,
+                           const float *w_scale, const void *bias, int nb, int h, int w,
+                           int c_in, int c_out, int r, int s, int stride, int pad,
+                           void *y, hq_dtype y_dtype, void *stream);
 
 #ifdef __cplusplus
 }

@@ -5,9 +5,11 @@ from .binding import (  # noqa: F401
     hq_act_hadamard_quant_static,
     hq_act_hadamard_quant_width,
     hq_int_conv2d,
+    hq_int_conv2d_i8,
     hq_int_conv2d_static,
     hq_int_conv2d_width,
     hq_int_linear,
+    hq_int_linear_i8,
     hq_int_linear_single,
     hq_int_linear_static,
     hq_quantize_weights,

@@ -22,7 +22,8 @@ SYMBOLS = ("hq_status_string", "hq_quantize_weights", "hq_act_hadamard_quant",
            "hq_int_linear", "hq_int_conv2d", "hq_act_hadamard_quant_static",
            "hq_int_linear_static", "hq_int_conv2d_static",
            "hq_quantize_weights_single", "hq_int_linear_single",
-           "hq_act_hadamard_quant_width", "hq_int_conv2d_width")
+           "hq_act_hadamard_quant_width", "hq_int_conv2d_width",
+           "hq_int_linear_i8", "hq_int_conv2d_i8")
 
 
 class HqError(RuntimeError):
@@ -57,6 +58,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.hq_int_linear_single.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, vp, i32, vp]
     lib.hq_act_hadamard_quant_width.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]
     lib.hq_int_conv2d_width.argtypes = [vp] * 5 + [i32] * 10 + [vp, i32, vp]
+    lib.hq_int_linear_i8.argtypes = lib.hq_int_linear.argtypes
+    lib.hq_int_conv2d_i8.argtypes = lib.hq_int_conv2d.argtypes
     for name in SYMBOLS[1:]:
         getattr(lib, name).restype = i32
     _lib = lib
@@ -88,10 +91,14 @@ def _dev(t: torch.Tensor, name: str) -> torch.Tensor:
 
 def hq_quantize_weights(w: torch.Tensor, had_block: int = 64, w_bits: int = 4
                         ) -> Tuple[torch.Tensor, torch.Tensor]:
-    """w [n_out, taps, k_in] fp16/fp32 -> (wq uint8 [n_out, taps, k_in/2], w_scale fp32 [n_out])."""
+    """w [n_out, taps, k_in] fp16/fp32 -> (wq uint8 [n_out, taps, k_in/2], w_scale fp32 [n_out]);
+    w_bits = 8: wq int8 [n_out, taps, k_in], one code per byte."""
     _dev(w, "w")
     n_out, taps, k_in = w.shape
-    wq = torch.empty((n_out, taps, k_in // 2), dtype=torch.uint8, device=w.device)
+    if w_bits == 8:
+        wq = torch.empty((n_out, taps, k_in), dtype=torch.int8, device=w.device)
+    else:
+        wq = torch.empty((n_out, taps, k_in // 2), dtype=torch.uint8, device=w.device)
     ws = torch.empty((n_out,), dtype=torch.float32, device=w.device)
     _check("hq_quantize_weights", load_library().hq_quantize_weights(
         _ptr(w), _DTYPES[w.dtype], n_out, taps, k_in, had_block, w_bits, _ptr(wq), _ptr(ws), _stream()))
@@ -101,12 +108,15 @@ def hq_quantize_weights(w: torch.Tensor, had_block: int = 64, w_bits: int = 4
 def hq_act_hadamard_quant(x: torch.Tensor, had_block: int = 64, a_bits: int = 4,
                           out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None
                           ) -> Tuple[torch.Tensor, torch.Tensor]:
-    """x [..., k] fp16/fp32 -> (xq uint8 [..., k/2], x_scale fp32 [...])."""
+    """x [..., k] fp16/fp32 -> (xq uint8 [..., k/2], x_scale fp32 [...]); a_bits = 8: xq int8 [..., k]."""
     _dev(x, "x")
     k = x.shape[-1]
     m = x.numel() // k
     if out is None:
-        xq = torch.empty(x.shape[:-1] + (k // 2,), dtype=torch.uint8, device=x.device)
+        if a_bits == 8:
+            xq = torch.empty(x.shape[:-1] + (k,), dtype=torch.int8, device=x.device)
+        else:
+            xq = torch.empty(x.shape[:-1] + (k // 2,), dtype=torch.uint8, device=x.device)
         xs = torch.empty(x.shape[:-1], dtype=torch.float32, device=x.device)
     else:
         xq, xs = out
@@ -292,4 +302,45 @@ def hq_int_conv2d_width(xu3: torch.Tensor, x_scale: Optional[torch.Tensor], wq: 
     _check("hq_int_conv2d_width", load_library().hq_int_conv2d_width(
         _ptr(xu3), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), nb, h, w, kb * 2, c_out, 3, 3, 1, 1,
         had_block, _ptr(y), _DTYPES[y_dtype], _stream()))
+    return y
+
+
+# ---- 8-bit codes (W8A8): int8 operands, one code per byte ---------------------------------------
+
+def hq_int_linear_i8(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torch.Tensor,
+                     w_scale: Optional[torch.Tensor], bias: Optional[torch.Tensor] = None,
+                     y_dtype: torch.dtype = torch.float16, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """xq int8 [m, k], wq int8 [n, k] (or [n, 1, k]) -> y [m, n]; y_dtype int32 returns the raw sums."""
+    _dev(xq, "xq"), _dev(wq, "wq")
+    m, k = xq.shape
+    n = wq.shape[0]
+    if wq.numel() != n * k:
+        raise ValueError("wq does not match xq in k")
+    if bias is not None and bias.dtype != y_dtype:
+        raise ValueError("bias must have the output dtype")
+    y = out if out is not None else torch.empty((m, n), dtype=y_dtype, device=xq.device)
+    _check("hq_int_linear_i8", load_library().hq_int_linear_i8(
+        _ptr(xq), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), m, n, k, _ptr(y), _DTYPES[y_dtype], _stream()))
+    return y
+
+
+def hq_int_conv2d_i8(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torch.Tensor,
+                     w_scale: Optional[torch.Tensor], bias: Optional[torch.Tensor] = None,
+                     ksize: int = 3, y_dtype: torch.dtype = torch.float16,
+                     out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """xq int8 [N, H, W, Cin], wq int8 [Cout, ksize*ksize, Cin] -> y [N, H, W, Cout] (stride 1, same
+    size); y_dtype int32 returns the per-tap sums [N, H, W, ksize*ksize, Cout]."""
+    _dev(xq, "xq"), _dev(wq, "wq")
+    nb, h, w, c_in = xq.shape
+    c_out = wq.shape[0]
+    taps = ksize * ksize
+    if wq.numel() != c_out * taps * c_in:
+        raise ValueError("wq does not match xq in Cin or the kernel size")
+    if bias is not None and bias.dtype != y_dtype:
+        raise ValueError("bias must have the output dtype")
+    shape = (nb, h, w, taps, c_out) if (y_dtype == torch.int32 and taps > 1) else (nb, h, w, c_out)
+    y = out if out is not None else torch.empty(shape, dtype=y_dtype, device=xq.device)
+    _check("hq_int_conv2d_i8", load_library().hq_int_conv2d_i8(
+        _ptr(xq), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), nb, h, w, c_in, c_out, ksize, ksize, 1,
+        (ksize - 1) // 2, _ptr(y), _DTYPES[y_dtype], _stream()))
     return y

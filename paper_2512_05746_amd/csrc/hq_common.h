@@ -1,4 +1,4 @@
-// Internal helpers shared by the HIP translation units of libhq (host side only).
+// Internal helpers shared by the HIP translation units of libhq.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -28,6 +28,33 @@ inline int compute_units() {
         cached[dev] = n;
     }
     return cached[dev];
+}
+
+// Exact division of n < 2^31 by a run-time constant d >= 2: n / d == umulhi(n, m) >> s.
+// (d == 1 is handled where the quotient is taken.)
+struct Magic31 {
+    uint32_t m, s;
+};
+
+inline Magic31 magic31(uint32_t d) {
+    if (d <= 1) return {0, 0};
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;
+    const uint64_t m = ((1ull << (31 + l)) + d - 1) / d;   // l <= 31: no overflow
+    return {static_cast<uint32_t>(m), l - 1};
+}
+
+__device__ __forceinline__ uint32_t div_magic31(uint32_t n, uint32_t d, uint32_t m, uint32_t s) {
+    return d == 1 ? n : (__umulhi(n, m) >> s);
+}
+
+// Signed base-16 digits of v, least significant first: v = d[0] + 16 d[1] + 256 d[2] with every
+// digit in [-8, 7] (|v| <= 1911).  The format of the digit planes of wide integers.
+__device__ __forceinline__ void digits16(int v, int (&d)[3]) {
+    d[0] = ((v + 8) & 15) - 8;
+    v = (v - d[0]) >> 4;
+    d[1] = ((v + 8) & 15) - 8;
+    d[2] = (v - d[1]) >> 4;
 }
 
 // Maps the sticky launch error (if any) of the calling thread to a status.

@@ -59,10 +59,6 @@ struct HaloArgs {
     int sx_static;
 };
 
-__device__ __forceinline__ uint32_t div_magic31(uint32_t n, uint32_t d, uint32_t m, uint32_t s) {
-    return d == 1 ? n : (__umulhi(n, m) >> s);
-}
-
 template <int KIND, int OUT>
 __global__ __launch_bounds__(256, KIND == kConvSum ? 3 : 2) void conv3x3_halo_kernel(HaloArgs a) {
     constexpr bool PER_TAP = KIND == kConvPerTap;
@@ -191,9 +187,9 @@ __global__ __launch_bounds__(256, KIND == kConvSum ? 3 : 2) void conv3x3_halo_ke
         int my_mask;
         {
             const uint32_t pix = p0 + tid;
-            const uint32_t q = div_magic31(pix, a.w, a.w_magic, a.w_shift);
+            const uint32_t q = hq::div_magic31(pix, a.w, a.w_magic, a.w_shift);
             const int ow = static_cast<int>(pix - q * a.w);
-            const int oh = static_cast<int>(q - div_magic31(q, a.h, a.h_magic, a.h_shift) * a.h);
+            const int oh = static_cast<int>(q - hq::div_magic31(q, a.h, a.h_magic, a.h_shift) * a.h);
             const int cm = (ow > 0 ? 1 : 0) | 2 | (ow + 1 < a.w ? 4 : 0);
             my_mask = (oh > 0 ? cm : 0) | (cm << 3) | (oh + 1 < a.h ? cm << 6 : 0);
             if (pix >= a.pixels) my_mask = 0;
@@ -397,17 +393,6 @@ __global__ __launch_bounds__(256, KIND == kConvSum ? 3 : 2) void conv3x3_halo_ke
     }
 }
 
-struct Magic31 { uint32_t m, s; };
-
-// n / d == umulhi(n, m) >> s for every n < 2^31 (d >= 2; d == 1 is handled in the kernel)
-Magic31 magic31(uint32_t d) {
-    if (d <= 1) return {0, 0};
-    uint32_t l = 0;
-    while ((1ull << l) < d) ++l;
-    const uint64_t m = ((1ull << (31 + l)) + d - 1) / d;   // l <= 31: no overflow
-    return {static_cast<uint32_t>(m), l - 1};
-}
-
 }  // namespace
 
 // True if the layer fits this kernel: channel slices of 192, fp output, image rows short enough
@@ -422,7 +407,7 @@ hq_status hq_conv3x3_halo_launch(const GemmArgs &g, hq_dtype y_dtype, hipStream_
     HaloArgs a{};
     a.xq = g.xq; a.sx = g.sx; a.wq = g.wq; a.sw = g.sw; a.bias = g.bias; a.y = g.y;
     a.pixels = g.pixels; a.n = g.n; a.k = g.k; a.h = g.h; a.w = g.w; a.sx_static = g.sx_static;
-    const Magic31 mw = magic31(static_cast<uint32_t>(g.w)), mh = magic31(static_cast<uint32_t>(g.h));
+    const hq::Magic31 mw = hq::magic31(static_cast<uint32_t>(g.w)), mh = hq::magic31(static_cast<uint32_t>(g.h));
     a.w_magic = mw.m; a.w_shift = mw.s; a.h_magic = mh.m; a.h_shift = mh.s;
     a.n_co_tiles = static_cast<uint32_t>((g.n + 63) / 64);
     const int64_t tiles = ((static_cast<int64_t>(g.pixels) + 255) / 256) * a.n_co_tiles;

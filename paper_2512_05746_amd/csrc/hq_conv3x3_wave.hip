@@ -40,11 +40,6 @@ struct WaveConvArgs {
     int kg_log2;         // waves per tile: 1 << kg_log2 (1, 2 or 4)
 };
 
-// n / d for n < 2^31 (m, s from magic_u31 on the host)
-__device__ __forceinline__ uint32_t div_magic(uint32_t n, uint32_t d, uint32_t m, uint32_t s) {
-    return d == 1 ? n : (__umulhi(n, m) >> s);
-}
-
 template <int OUT, int NSTAGE>
 __global__ __launch_bounds__(256, 1) void conv3x3_wave_kernel(WaveConvArgs a) {
     constexpr int TM = 2, TN = 2, KCH = 6, ROWB = KCH * 16, KS = KCH / 2, TAPS = 9;
@@ -148,9 +143,9 @@ __global__ __launch_bounds__(256, 1) void conv3x3_wave_kernel(WaveConvArgs a) {
         // ---- scales of the nine input pixels of this lane's output pixel (pixel lhalf*32 + lrow)
         {
             const uint32_t pix = p0 + lhalf * 32 + lrow;
-            const uint32_t q = div_magic(pix, a.w, a.w_magic, a.w_shift);
+            const uint32_t q = hq::div_magic31(pix, a.w, a.w_magic, a.w_shift);
             const int ow = static_cast<int>(pix - q * a.w);
-            const int oh = static_cast<int>(q - div_magic(q, a.h, a.h_magic, a.h_shift) * a.h);
+            const int oh = static_cast<int>(q - hq::div_magic31(q, a.h, a.h_magic, a.h_shift) * a.h);
             const int cm = (ow > 0 ? 1 : 0) | 2 | (ow + 1 < a.w ? 4 : 0);
             int mask = (oh > 0 ? cm : 0) | (cm << 3) | (oh + 1 < a.h ? cm << 6 : 0);
             if (pix >= a.pixels) mask = 0;
@@ -297,17 +292,6 @@ __global__ __launch_bounds__(256, 1) void conv3x3_wave_kernel(WaveConvArgs a) {
     }
 }
 
-struct Magic { uint32_t m, s; };
-
-// n / d == umulhi(n, m) >> s for every n < 2^31 (d >= 2; d == 1 is handled by the caller)
-Magic magic_u31(uint32_t d) {
-    if (d <= 1) return {0, 0};
-    uint32_t l = 0;
-    while ((1ull << l) < d) ++l;
-    const uint64_t m = ((1ull << (31 + l)) + d - 1) / d;   // l <= 31: no overflow
-    return {static_cast<uint32_t>(m), l - 1};
-}
-
 }  // namespace
 
 // Waves per tile that minimise rounds * (chunks per wave + fixed cost) on `cus` CUs of four SIMDs.
@@ -328,7 +312,7 @@ hq_status hq_conv3x3_wave_launch(const GemmArgs &g, hq_dtype y_dtype, hipStream_
     WaveConvArgs a{};
     a.xq = g.xq; a.sx = g.sx; a.wq = g.wq; a.sw = g.sw; a.bias = g.bias; a.y = g.y;
     a.pixels = g.pixels; a.n = g.n; a.k = g.k; a.h = g.h; a.w = g.w;
-    const Magic mw = magic_u31(static_cast<uint32_t>(g.w)), mh = magic_u31(static_cast<uint32_t>(g.h));
+    const hq::Magic31 mw = hq::magic31(static_cast<uint32_t>(g.w)), mh = hq::magic31(static_cast<uint32_t>(g.h));
     a.w_magic = mw.m; a.w_shift = mw.s; a.h_magic = mh.m; a.h_shift = mh.s;
     a.n_px_tiles = static_cast<uint32_t>((static_cast<int64_t>(g.pixels) + 63) / 64);
     const int64_t tiles = static_cast<int64_t>(a.n_px_tiles) * ((g.n + 63) / 64);

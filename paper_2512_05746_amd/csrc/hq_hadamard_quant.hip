@@ -115,6 +115,24 @@ __device__ __forceinline__ uint32_t quant_pack8(const float (&v)[8], float inv, 
     return w;
 }
 
+// The same codes one per byte (8-bit codes), element i in byte i.
+__device__ __forceinline__ uint2 quant_bytes8(const float (&v)[8], float inv, float qmin, float qmax) {
+    uint32_t w[2] = {0, 0};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float r = fminf(fmaxf(rintf(v[i] * inv), qmin), qmax);
+        w[i >> 2] |= (static_cast<uint32_t>(static_cast<int>(r)) & 0xFFu) << (8 * (i & 3));
+    }
+    return uint2{w[0], w[1]};
+}
+
+// Stores the eight codes of chunk `chunk`: half a byte each, or one byte each for 8-bit codes.
+__device__ __forceinline__ void store_codes8(uint32_t *xq, int64_t chunk, const float (&v)[8], float inv,
+                                             float qmin, float qmax, bool bytes) {
+    if (bytes) reinterpret_cast<uint2 *>(xq)[chunk] = quant_bytes8(v, inv, qmin, qmax);
+    else xq[chunk] = quant_pack8(v, inv, qmin, qmax);
+}
+
 struct RowQuantArgs {
     int64_t m;          // rows
     int chunks;         // 8-element chunks per row
@@ -124,6 +142,7 @@ struct RowQuantArgs {
     float qmin, qmax;
     float norm;         // 2^{-LOGB/2}
     const float *given;   // static mode: one scale for the whole tensor (device); NULL = per-row abs-max
+    int bytes;            // 8-bit codes: one byte per code instead of half a byte
 };
 
 // Rows short enough that a workgroup keeps several whole rows in registers.
@@ -171,7 +190,7 @@ __global__ __launch_bounds__(kThreads) void rowquant_small(const T *__restrict__
         if (slot < nslots) {
             const float amax = __uint_as_float(s_max[rl[u]]);
             const float inv = a.given ? a.norm / a.given[0] : (amax > 0.f ? a.qmax / amax : 0.f);
-            xq[chunk0 + slot] = quant_pack8(v[u], inv, a.qmin, a.qmax);
+            store_codes8(xq, chunk0 + slot, v[u], inv, a.qmin, a.qmax, a.bytes != 0);
             if (!a.given && slot == rl[u] * a.chunks)
                 scale[row0 + rl[u]] = amax > 0.f ? (amax * a.norm) / a.qmax : 1.0f;
         }
@@ -217,7 +236,7 @@ __global__ __launch_bounds__(kThreads) void rowquant_large(const T *__restrict__
             for (int i = 0; i < 8; ++i) v[i] = 0.f;
         }
         hadamard_raw<LOGB>(v, lane);
-        if (c < a.chunks) xq[chunk0 + c] = quant_pack8(v, inv, a.qmin, a.qmax);
+        if (c < a.chunks) store_codes8(xq, chunk0 + c, v, inv, a.qmin, a.qmax, a.bytes != 0);
     }
     if (tid == 0 && !a.given) scale[blockIdx.x] = amax > 0.f ? (amax * a.norm) / a.qmax : 1.0f;
 }
@@ -542,6 +561,7 @@ hq_status launch_rowquant(const T *x, int64_t m, int row_len, int bits, uint32_t
     while (a.max_group < 16 && a.chunks % (a.max_group * 2) == 0) a.max_group *= 2;
     a.qmax = static_cast<float>((1 << (bits - 1)) - 1);
     a.qmin = -static_cast<float>(1 << (bits - 1));
+    a.bytes = bits == 8 ? 1 : 0;
     a.norm = static_cast<float>(1.0 / sqrt(static_cast<double>(1 << LOGB)));
 
     if (a.chunks <= kThreads * 4) {
@@ -588,7 +608,7 @@ hq_status check_rowquant(const void *x, hq_dtype dt, int64_t m, int k, int64_t r
                          int bits, const void *xq, const void *scale) {
     if (!x || !xq || !scale) return HQ_ERR_NULL;
     if (dt != HQ_F16 && dt != HQ_F32) return HQ_ERR_DTYPE;
-    if (bits != 3 && bits != 4) return HQ_ERR_BITS;
+    if (bits != 3 && bits != 4 && bits != 8) return HQ_ERR_BITS;
     if (m <= 0 || k <= 0 || row_len <= 0 || row_len > 0x7fffffffLL) return HQ_ERR_SHAPE;
     if (!hq::pow2_upto_128(had_block) || k % had_block != 0 || k % 8 != 0) return HQ_ERR_SHAPE;
     if (!hq::aligned16(x) || !hq::aligned16(xq) || (reinterpret_cast<uintptr_t>(scale) & 3u))
@@ -605,7 +625,7 @@ hq_status act_hadamard_quant(const void *x, hq_dtype x_dtype, int64_t m, int k, 
                              uint8_t *xq, float *x_scale, const float *given, void *stream) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint32_t *out = reinterpret_cast<uint32_t *>(xq);
-    if (x_dtype == HQ_F16 && had_block == 64 && k <= 64 * kMaxBlocks)
+    if (x_dtype == HQ_F16 && had_block == 64 && k <= 64 * kMaxBlocks && a_bits != 8)
         return launch_hadamard64(static_cast<const __half *>(x), m, k, a_bits, xq, x_scale, given, s);
     if (x_dtype == HQ_F16)
         return dispatch_block(static_cast<const __half *>(x), m, k, had_block, a_bits, out, x_scale, given, s);

@@ -13,7 +13,7 @@ namespace {
 //   - otherwise 128 x 128 tiles if there is at least one per CU;
 //   - a layer with fewer tiles takes 64 x 64 tiles at four workgroups per CU.
 hq_status launch_gemm(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream_t stream) {
-    if (a.k % 192 != 0) return hq_gemm_launch_128x128(a, taps, y_dtype, stream);
+    if ((a.bits == 8 ? a.k : a.k / 2) % 96 != 0) return hq_gemm_launch_128x128(a, taps, y_dtype, stream);
     const int64_t cus = hq::compute_units();
     const int64_t pix128 = (static_cast<int64_t>(a.pixels) + 127) / 128;
     if (a.n % 64 == 0 && pix128 * (a.n / 64) >= 2 * cus) return hq_gemm_launch_64x128(a, taps, y_dtype, stream);
@@ -47,14 +47,15 @@ hq_status check_common(const uint8_t *xq, const float *x_scale, const uint8_t *w
 
 namespace {
 
+// bits: 4 (packed pairs of codes) or 8 (int8 codes, one per byte)
 hq_status int_linear(const uint8_t *xq, const float *x_scale, const uint8_t *wq, const float *w_scale,
                      const void *bias, int64_t m, int n, int k, void *y, hq_dtype y_dtype, int sx_static,
-                     void *stream) {
+                     int bits, void *stream) {
     hq_status st = check_common(xq, x_scale, wq, w_scale, bias, m, n, k, y, y_dtype);
     if (st != HQ_OK) return st;
-    if (!fits_32bit(m, 1, n, 1, k)) return HQ_ERR_UNSUPPORTED;
+    if (!fits_32bit(m, 1, n, 1, bits == 8 ? 2 * k : k)) return HQ_ERR_UNSUPPORTED;
     GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(m), n, k, 1, 1, 0, 0, 0, 1, sx_static,
-               1.0f};
+               1.0f, bits};
     return launch_gemm(a, 1, y_dtype, static_cast<hipStream_t>(stream));
 }
 
@@ -68,13 +69,13 @@ hq_status int_linear_single(const uint8_t *xq, const float *x_scale, const uint8
     if (!hq::pow2_upto_128(had_block) || k % had_block != 0) return HQ_ERR_SHAPE;
     if (!fits_32bit(m, 1, n, 3, k)) return HQ_ERR_UNSUPPORTED;
     const float norm = static_cast<float>(1.0 / sqrt(static_cast<double>(had_block)));
-    GemmArgs a{xq, x_scale, wq3, w_scale, bias, y, static_cast<uint32_t>(m), n, k, 1, 1, 0, 0, 0, 1, 0, norm};
+    GemmArgs a{xq, x_scale, wq3, w_scale, bias, y, static_cast<uint32_t>(m), n, k, 1, 1, 0, 0, 0, 1, 0, norm, 4};
     return launch_gemm(a, 3, y_dtype, static_cast<hipStream_t>(stream));
 }
 
 hq_status int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq, const float *w_scale,
                      const void *bias, int nb, int h, int w, int c_in, int c_out, int r, int s, int stride,
-                     int pad, void *y, hq_dtype y_dtype, int sx_static, void *stream) {
+                     int pad, void *y, hq_dtype y_dtype, int sx_static, int bits, void *stream) {
     if (nb <= 0 || h <= 0 || w <= 0 || r <= 0 || s <= 0 || stride <= 0 || pad < 0) {
         if (!xq || !wq || !y) return HQ_ERR_NULL;
         return HQ_ERR_SHAPE;
@@ -83,12 +84,13 @@ hq_status int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
     hq_status st = check_common(xq, x_scale, wq, w_scale, bias, pixels, c_out, c_in, y, y_dtype);
     if (st != HQ_OK) return st;
     if (r != s || (r != 1 && r != 3) || stride != 1 || pad != (r - 1) / 2) return HQ_ERR_UNSUPPORTED;
-    if (!fits_32bit(pixels, w, c_out, r * s, c_in)) return HQ_ERR_UNSUPPORTED;
+    if (!fits_32bit(pixels, w, c_out, r * s, bits == 8 ? 2 * c_in : c_in)) return HQ_ERR_UNSUPPORTED;
     // one sum over all taps: 256 * (64 per product) * (codes per sum) must stay below 2^31
     if (sx_static && static_cast<int64_t>(c_in) * r * s >= 131072) return HQ_ERR_SHAPE;
     GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(pixels), c_out, c_in, h, w, 0, 0, 0, 1,
-               sx_static, 1.0f};
+               sx_static, 1.0f, bits};
     hipStream_t st_ = static_cast<hipStream_t>(stream);
+    if (bits == 8) return launch_gemm(a, r * s, y_dtype, st_);   // the 4-bit kernels below expand nibbles
     // A 3x3 layer with about one 64x64 output tile per CU or fewer cannot fill the machine with
     // whole tiles: it takes the kernel that also splits a tile's K range over waves.
     const int64_t tiles64 = ((pixels + 63) / 64) * ((c_out + 63) / 64);
@@ -124,7 +126,7 @@ hq_status int_conv2d_width(const uint8_t *xu3, const float *x_scale, const uint8
     if (static_cast<int64_t>(c_in) * 9 >= 131072) return HQ_ERR_SHAPE;
     const float norm = static_cast<float>(1.0 / sqrt(static_cast<double>(had_block)));
     GemmArgs a{xu3, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(pixels), c_out, c_in, h, w, 0, 0, 0, 1,
-               1, norm};
+               1, norm, 4};
     return launch_gemm(a, 27, y_dtype, static_cast<hipStream_t>(stream));
 }
 
@@ -133,13 +135,13 @@ hq_status int_conv2d_width(const uint8_t *xu3, const float *x_scale, const uint8
 extern "C" hq_status hq_int_linear(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
                                    const float *w_scale, const void *bias, int64_t m, int n, int k,
                                    void *y, hq_dtype y_dtype, void *stream) {
-    return int_linear(xq, x_scale, wq, w_scale, bias, m, n, k, y, y_dtype, 0, stream);
+    return int_linear(xq, x_scale, wq, w_scale, bias, m, n, k, y, y_dtype, 0, 4, stream);
 }
 
 extern "C" hq_status hq_int_linear_static(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
                                           const float *w_scale, const void *bias, int64_t m, int n, int k,
                                           void *y, hq_dtype y_dtype, void *stream) {
-    return int_linear(xq, x_scale, wq, w_scale, bias, m, n, k, y, y_dtype, 1, stream);
+    return int_linear(xq, x_scale, wq, w_scale, bias, m, n, k, y, y_dtype, 1, 4, stream);
 }
 
 extern "C" hq_status hq_int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
@@ -147,7 +149,7 @@ extern "C" hq_status hq_int_conv2d(const uint8_t *xq, const float *x_scale, cons
                                    int c_out, int r, int s, int stride, int pad, void *y, hq_dtype y_dtype,
                                    void *stream) {
     return int_conv2d(xq, x_scale, wq, w_scale, bias, nb, h, w, c_in, c_out, r, s, stride, pad, y, y_dtype, 0,
-                      stream);
+                      4, stream);
 }
 
 extern "C" hq_status hq_int_conv2d_static(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
@@ -155,7 +157,7 @@ extern "C" hq_status hq_int_conv2d_static(const uint8_t *xq, const float *x_scal
                                           int c_in, int c_out, int r, int s, int stride, int pad, void *y,
                                           hq_dtype y_dtype, void *stream) {
     return int_conv2d(xq, x_scale, wq, w_scale, bias, nb, h, w, c_in, c_out, r, s, stride, pad, y, y_dtype, 1,
-                      stream);
+                      4, stream);
 }
 
 extern "C" hq_status hq_int_linear_single(const uint8_t *xq, const float *x_scale, const uint8_t *wq3,
@@ -170,4 +172,19 @@ extern "C" hq_status hq_int_conv2d_width(const uint8_t *xu3, const float *x_scal
                                          int had_block, void *y, hq_dtype y_dtype, void *stream) {
     return int_conv2d_width(xu3, x_scale, wq, w_scale, bias, nb, h, w, c_in, c_out, r, s, stride, pad, had_block,
                             y, y_dtype, stream);
+}
+
+extern "C" hq_status hq_int_linear_i8(const int8_t *xq, const float *x_scale, const int8_t *wq,
+                                      const float *w_scale, const void *bias, int64_t m, int n, int k,
+                                      void *y, hq_dtype y_dtype, void *stream) {
+    return int_linear(reinterpret_cast<const uint8_t *>(xq), x_scale, reinterpret_cast<const uint8_t *>(wq), w_scale,
+                      bias, m, n, k, y, y_dtype, 0, 8, stream);
+}
+
+extern "C" hq_status hq_int_conv2d_i8(const int8_t *xq, const float *x_scale, const int8_t *wq,
+                                      const float *w_scale, const void *bias, int nb, int h, int w, int c_in,
+                                      int c_out, int r, int s, int stride, int pad, void *y, hq_dtype y_dtype,
+                                      void *stream) {
+    return int_conv2d(reinterpret_cast<const uint8_t *>(xq), x_scale, reinterpret_cast<const uint8_t *>(wq), w_scale,
+                      bias, nb, h, w, c_in, c_out, r, s, stride, pad, y, y_dtype, 0, 8, stream);
 }

@@ -50,6 +50,7 @@ struct GemmArgs {
     int sx_static;       // sx is ONE scale for the whole activation tensor (a 3x3 convolution then keeps
                          // one integer sum over all taps)
     float out_scale;     // factor applied with w_scale (1, or 2^(-log2(block)/2) for digit-plane weights)
+    int bits;            // 4: two codes per byte (3-bit codes included); 8: one int8 code per byte
 };
 
 namespace {
@@ -262,8 +263,15 @@ __device__ __forceinline__ void store16(float *dst, const float (&v)[16]) {
 // pixels >= pixels) and taps outside the image read some other in-bounds row
 // instead of zeros: their sums are never stored, and a tap outside the image
 // has scale 0 (int32 output: written as 0).
-template <int TM, int TN, int WAVES_M, int WAVES_N, int KIND, int OUT, int KCH, int NSTAGE, int OCC>
+//
+// XB = 8: the operands are int8 codes, one per byte.  The 16 bytes a lane reads are one MFMA
+// operand as they are (no expansion, one MFMA per read instead of two), the sums carry no factor
+// 256, and a chunk row of KCH * 16 bytes holds KCH * 16 codes.
+template <int TM, int TN, int WAVES_M, int WAVES_N, int KIND, int OUT, int KCH, int NSTAGE, int OCC, int XB = 4>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(GemmArgs a) {
+    static_assert(XB == 4 || XB == 8, "4-bit codes in pairs or int8 codes");
+    constexpr int SHIFT = XB == 8 ? 0 : 8;                    // log2 of the factor the integer sums carry
+    constexpr float UNIT = XB == 8 ? 1.0f : 1.0f / 256.0f;
     constexpr int TAPS = taps_of(KIND);
     constexpr int WTAPS = KIND == kConvPlanes ? 9 : TAPS;             // taps of the weight tensor [n, WTAPS, k/2]
     constexpr bool CONV = KIND == kConvPerTap || KIND == kConvSum || KIND == kConvPlanes;   // taps read shifted pixels
@@ -309,7 +317,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
     const int lrow = lane & 31, lhalf = lane >> 5;
 
-    const int kbytes = a.k >> 1;                 // packed bytes per (row, tap)
+    const int kbytes = XB == 8 ? a.k : a.k >> 1;   // operand bytes per (row, tap)
     const int chunks_per_tap = kbytes / ROWB;    // host guarantees divisibility
     const int total_chunks = TAPS * chunks_per_tap;
     const uint32_t lds_row = lds_address(lds) + lrow * ROWB + (lhalf ^ ((lrow >> 3) & 1)) * 16;
@@ -386,7 +394,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
             for (int j = 0; j < SX_PER_T; ++j) {
                 const int e = tid + j * NT;
                 // the sums carry a factor 256 (both operands are 16 x code); digit plane t weighs 16^t
-                const float unit = KIND == kPlanes ? static_cast<float>(1 << (4 * (e / BP))) / 256.0f : 1.0f / 256.0f;
+                const float unit = KIND == kPlanes ? static_cast<float>(1 << (4 * (e / BP))) * UNIT : UNIT;
                 if (e < STAPS * BP) (&s_sx[k & 1][0][0])[e] = t_sx[j] * unit;
             }
             if (tid < BCO) {
@@ -536,6 +544,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
 
         // MFMAs of one K step; first: the sums of a tap start from 0
         auto multiply = [&](Ops &o, bool first) {
+            if constexpr (XB == 8) {
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) pin(o.a[tm]);
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) pin(o.b[tn]);
+                const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn)
+                        acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(o.a[tm], o.b[tn], first ? zero : acc[tm][tn], 0, 0, 0);
+                return;
+            }
             v4i a0[TM], a1[TM], b0[TN], b1[TN];
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm) { pin(o.a[tm]); expand(o.a[tm], a0[tm], a1[tm]); }
@@ -612,7 +633,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
 #pragma unroll
                         for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-                            for (int r = 0; r < 16; ++r) iacc[tm][tn][r] += (acc[tm][tn][r] >> 8) * (1 << (4 * (tap / 9)));
+                            for (int r = 0; r < 16; ++r) iacc[tm][tn][r] += (acc[tm][tn][r] >> SHIFT) * (1 << (4 * (tap / 9)));
                     if (tap == TAPS - 1) {
                         int *yi = static_cast<int *>(a.y);
 #pragma unroll
@@ -646,7 +667,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
                                 int *dst = yi + (static_cast<int64_t>(pix) * OUT_TAPS + (SUM ? 0 : tap)) * a.n + cbase;
 #pragma unroll
                                 for (int r = 0; r < 16; ++r)
-                                    if (cbase + r < a.n) dst[r] = inside ? (acc[tm][tn][r] >> 8) : 0;
+                                    if (cbase + r < a.n) dst[r] = inside ? (acc[tm][tn][r] >> SHIFT) : 0;
                             }
                         }
                     }
@@ -720,20 +741,20 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     }
 }
 
-template <int TM, int TN, int WAVES_M, int WAVES_N, int KIND, int OUT, int KCH, int NSTAGE, int OCC>
+template <int TM, int TN, int WAVES_M, int WAVES_N, int KIND, int OUT, int KCH, int NSTAGE, int OCC, int XB = 4>
 hq_status launch_tile(GemmArgs a, hipStream_t stream) {
     constexpr int TAPS = taps_of(KIND);
     constexpr int BCO = 32 * TM * WAVES_M, BP = 32 * TN * WAVES_N;
     a.n_co_tiles = (a.n + BCO - 1) / BCO;
     const int64_t p_tiles = (static_cast<int64_t>(a.pixels) + BP - 1) / BP;
     const int64_t tiles = p_tiles * a.n_co_tiles;
-    if (tiles * (a.k / 64) * TAPS > 0x7fffffffLL) return HQ_ERR_SHAPE;   // chunk-stream counters are 32 bit
+    if (tiles * ((a.bits == 8 ? a.k : a.k / 2) / 32) * TAPS > 0x7fffffffLL) return HQ_ERR_SHAPE;   // chunk-stream counters are 32 bit
     a.n_tiles = static_cast<uint32_t>(tiles);
     const int64_t slots = static_cast<int64_t>(hq::compute_units()) * OCC;   // co-resident workgroups
     const unsigned grid = static_cast<unsigned>(tiles < slots ? tiles : slots);
     a.xcds = grid % 8 == 0 ? 1 : 0;
     a.cus = static_cast<uint32_t>(hq::compute_units());
-    hipLaunchKernelGGL((int_gemm_kernel<TM, TN, WAVES_M, WAVES_N, KIND, OUT, KCH, NSTAGE, OCC>),
+    hipLaunchKernelGGL((int_gemm_kernel<TM, TN, WAVES_M, WAVES_N, KIND, OUT, KCH, NSTAGE, OCC, XB>),
                        dim3(grid), dim3(64 * WAVES_M * WAVES_N), 0, stream, a);
     return hq::launch_status();
 }
@@ -744,8 +765,25 @@ hq_status launch_tile(GemmArgs a, hipStream_t stream) {
 // 64-code fallback for channel counts that are not a multiple of 192.
 template <int TM, int TN, int WAVES_M, int WAVES_N, int OCC, bool WITH_64, int NSTAGE_WIDE = 2>
 hq_status launch_config(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream_t stream) {
-    const bool wide = a.k % 192 == 0;
+    const bool wide = (a.bits == 8 ? a.k : a.k / 2) % 96 == 0;   // whole chunks of six 16-byte pieces per row
     if (!wide && !WITH_64) return HQ_ERR_UNSUPPORTED;
+    if (a.bits == 8) {   // int8 codes: linear layers and 3x3 convolutions with per-pixel scales
+#define HQ_GEMM_CASE8(KIND, OUT)                                                                           \
+    if (wide) return launch_tile<TM, TN, WAVES_M, WAVES_N, KIND, OUT, 6, NSTAGE_WIDE, OCC, 8>(a, stream);  \
+    if constexpr (WITH_64) return launch_tile<TM, TN, WAVES_M, WAVES_N, KIND, OUT, 2, 4, OCC, 8>(a, stream); \
+    return HQ_ERR_UNSUPPORTED;
+        if (taps == 1) {
+            if (y_dtype == HQ_F16) { HQ_GEMM_CASE8(kLinear, kOutF16) }
+            if (y_dtype == HQ_F32) { HQ_GEMM_CASE8(kLinear, kOutF32) }
+            if (y_dtype == HQ_I32) { HQ_GEMM_CASE8(kLinear, kOutI32) }
+        } else if (taps == 9 && !a.sx_static) {
+            if (y_dtype == HQ_F16) { HQ_GEMM_CASE8(kConvPerTap, kOutF16) }
+            if (y_dtype == HQ_F32) { HQ_GEMM_CASE8(kConvPerTap, kOutF32) }
+            if (y_dtype == HQ_I32) { HQ_GEMM_CASE8(kConvPerTap, kOutI32) }
+        }
+#undef HQ_GEMM_CASE8
+        return HQ_ERR_UNSUPPORTED;
+    }
 #define HQ_GEMM_CASE(KIND, OUT)                                                                        \
     if (wide) return launch_tile<TM, TN, WAVES_M, WAVES_N, KIND, OUT, 6, NSTAGE_WIDE, OCC>(a, stream);           \
     if constexpr (WITH_64) return launch_tile<TM, TN, WAVES_M, WAVES_N, KIND, OUT, 2, 4, OCC>(a, stream); \

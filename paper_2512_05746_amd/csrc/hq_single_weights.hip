@@ -22,14 +22,6 @@ constexpr int kThreads = 256;
 __device__ __forceinline__ float as_float(__half v) { return __half2float(v); }
 __device__ __forceinline__ float as_float(float v) { return v; }
 
-// signed base-16 digits of v, least significant first; |v| <= 1911 keeps d2 in [-8, 7]
-__device__ __forceinline__ void digits16(int v, int (&d)[3]) {
-    d[0] = ((v + 8) & 15) - 8;
-    v = (v - d[0]) >> 4;
-    d[1] = ((v + 8) & 15) - 8;
-    d[2] = (v - d[1]) >> 4;
-}
-
 template <typename T, int LOGB>
 __global__ __launch_bounds__(kThreads) void single_weights_kernel(const T *__restrict__ w, int k_in, float qmax,
                                                                   uint8_t *__restrict__ wq3,
@@ -72,8 +64,8 @@ __global__ __launch_bounds__(kThreads) void single_weights_kernel(const T *__res
 #pragma unroll
         for (int e = 0; e < U; e += 2) {
             int lo[3], hi[3];
-            digits16(c[e], lo);
-            digits16(c[e + 1], hi);
+            hq::digits16(c[e], lo);
+            hq::digits16(c[e + 1], hi);
 #pragma unroll
             for (int p = 0; p < 3; ++p)
                 out[p * kbytes + ((u0 + e) >> 1)] = static_cast<uint8_t>((lo[p] & 15) | ((hi[p] & 15) << 4));

@@ -46,14 +46,6 @@ __device__ __forceinline__ void butterfly(V (&v)[B]) {
             }
 }
 
-// signed base-16 digit p of v (|v| <= 1911), least significant first
-__device__ __forceinline__ void digits16(int v, int (&d)[3]) {
-    d[0] = ((v + 8) & 15) - 8;
-    v = (v - d[0]) >> 4;
-    d[1] = ((v + 8) & 15) - 8;
-    d[2] = (v - d[1]) >> 4;
-}
-
 template <typename T, int LOGB>
 __global__ __launch_bounds__(kThreads) void width_quant_kernel(const T *__restrict__ x, int w, int c, float qmax,
                                                                const float *__restrict__ given,
@@ -82,8 +74,8 @@ __global__ __launch_bounds__(kThreads) void width_quant_kernel(const T *__restri
 #pragma unroll
         for (int e = 0; e < B; ++e) {
             int lo[3], hi[3];
-            digits16(q0[e], lo);
-            digits16(q1[e], hi);
+            hq::digits16(q0[e], lo);
+            hq::digits16(q1[e], hi);
             uint8_t *dst = xu3 + (static_cast<int64_t>(pix0 + e) * half_c + j);
 #pragma unroll
             for (int p = 0; p < 3; ++p)

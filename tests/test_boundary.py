@@ -43,7 +43,7 @@ def test_act_quant_argument_errors(lib):
     assert f(P, 0, 8, 64, 64, 4, None, P, None) == NULL
     assert f(P, 0, 8, 64, 64, 4, P, None, None) == NULL
     assert f(P, 2, 8, 64, 64, 4, P, P, None) == DTYPE      # int32 is not an input dtype
-    assert f(P, 0, 8, 64, 64, 8, P, P, None) == BITS
+    assert f(P, 0, 8, 64, 64, 6, P, P, None) == BITS
     assert f(P, 0, 8, 64, 64, 2, P, P, None) == BITS
     assert f(P, 0, 0, 64, 64, 4, P, P, None) == SHAPE      # no rows
     assert f(P, 0, 8, 96, 64, 4, P, P, None) == SHAPE      # k not a multiple of the block
@@ -156,6 +156,19 @@ def test_width_axis_argument_errors(lib):
     assert conv(*args(cin=96)) == SHAPE
     assert conv(*args(r=1, s=1, pad=0)) == UNSUPPORTED
     assert conv(*args(stride=2)) == UNSUPPORTED
+
+
+def test_int8_code_argument_errors(lib):
+    lin = lib.hq_int_linear_i8
+    assert lin(None, P, P, P, None, 8, 8, 64, P, 0, None) == NULL
+    assert lin(P, P, P, P, None, 8, 8, 96, P, 0, None) == SHAPE
+    assert lin(P, P, P, P, None, 8, 8, 64, P, 5, None) == DTYPE
+    conv = lib.hq_int_conv2d_i8
+    assert conv(P, P, P, P, None, 1, 4, 4, 64, 8, 3, 3, 2, 1, P, 0, None) == UNSUPPORTED
+    assert conv(P, None, P, P, None, 1, 4, 4, 64, 8, 3, 3, 1, 1, P, 0, None) == NULL
+    # 8-bit codes are a legal width for both quantisers, 5 bits are not
+    assert lib.hq_act_hadamard_quant(None, 0, 8, 64, 64, 8, P, P, None) == NULL
+    assert lib.hq_act_hadamard_quant(P, 0, 8, 64, 64, 5, P, P, None) == BITS
 
 
 def test_product_does_not_import_the_oracle():

@@ -297,6 +297,69 @@ def test_width_conv_benchmark_layers_full_size(hq, config, index, block):
     run_conv_width(hq, workloads.config_layers(config)[index], block)
 
 
+def run_layer_w8a8(hq, layer, block=workloads.HAD_BLOCK):
+    """The layer with 8-bit codes for both operands (one int8 code per byte): the same three layers
+    of checks as run_layer."""
+    print("layer (W8A8)", layer.name, layer.kind, layer.x_shape, "->", layer.n_out, flush=True)
+    x, w, bias = workloads.make_x(layer), workloads.make_w(layer), workloads.make_bias(layer)
+    ydt = TORCH_DT[layer.dtype]
+    xq_o, sx_o, tx = oracle.act_hadamard_quant(x, block, 8)
+    wq_o, sw_o, tw = oracle.quantize_weights(w, block, 8)
+
+    xq_g, sx_g = hq.hq_act_hadamard_quant(dev(x), block, 8)
+    wq_g, sw_g = hq.hq_quantize_weights(dev(w), block, 8)
+    assert xq_g.dtype == torch.int8 and xq_g.shape == x.shape and wq_g.shape == w.shape
+    xq_gc, wq_gc = host(xq_g), host(wq_g)
+    check_scales(layer.name + " x_scale", host(sx_g), sx_o)
+    check_scales(layer.name + " w_scale", host(sw_g), sw_o)
+    flips = check_codes(layer.name + " xq", xq_gc, xq_o, tx, 8)
+    flips += check_codes(layer.name + " wq", wq_gc, wq_o, tw, 8)
+
+    xq_od, wq_od = dev(xq_o), dev(wq_o)
+    bias_d = dev(bias) if bias is not None else None
+    if layer.kind == "linear":
+        acc_o, y_o = oracle.int_linear(xq_o, sx_o, wq_o[:, 0, :], sw_o, bias)
+        acc_g = host(hq.hq_int_linear_i8(xq_od, None, wq_od, None, None, y_dtype=torch.int32))
+        assert np.array_equal(acc_g, acc_o), layer.name + " int32 sums (W8A8)"
+        del acc_g, acc_o
+        if flips:
+            _, y_o = oracle.int_linear(xq_gc, sx_o, wq_gc[:, 0, :], sw_o, bias)
+        y_g = host(hq.hq_int_linear_i8(xq_g, sx_g, wq_g, sw_g, bias_d, y_dtype=ydt))
+    else:
+        ks = layer.ksize
+        wq4 = lambda c: c.reshape(layer.n_out, ks, ks, layer.k_in)
+        acc_o, y_o = oracle.int_conv2d(xq_o, sx_o, wq4(wq_o), sw_o, bias, stride=1, pad=layer.pad)
+        acc_g = host(hq.hq_int_conv2d_i8(xq_od, None, wq_od, None, None, ksize=ks, y_dtype=torch.int32))
+        assert np.array_equal(acc_g.reshape(acc_o.shape), acc_o), layer.name + " per-tap int32 sums (W8A8)"
+        del acc_g, acc_o
+        if flips:
+            _, y_o = oracle.int_conv2d(xq_gc, sx_o, wq4(wq_gc), sw_o, bias, stride=1, pad=layer.pad, want_acc=False)
+        y_g = host(hq.hq_int_conv2d_i8(xq_g, sx_g, wq_g, sw_g, bias_d, ksize=ks, y_dtype=ydt))
+    err = check_y(layer.name + " y (W8A8)", y_g.reshape(y_o.shape), y_o)
+    print("   ok: tie flips %d, y err %.2e" % (flips, err), flush=True)
+    return flips, err
+
+
+@pytest.mark.parametrize("layer", workloads.tiny_layers(), ids=lambda l: l.name)
+def test_w8a8_tiny_layers(hq, layer):
+    run_layer_w8a8(hq, layer)
+
+
+@pytest.mark.parametrize("config", [1, 2, 3, 5])
+def test_w8a8_benchmark_configs_full_size(hq, config):
+    for layer in workloads.config_layers(config):
+        run_layer_w8a8(hq, layer)
+
+
+def test_w8a8_extreme_codes(hq):
+    """All codes at -128 / 127: the largest sums the int8 path can meet stay exact."""
+    m, n, k = 65, 130, 1024
+    xq = np.full((m, k), -128, dtype=np.int8); xq[1::2] = 127
+    wq = np.full((n, k), -128, dtype=np.int8); wq[::3] = 127
+    acc = host(hq.hq_int_linear_i8(dev(xq), None, dev(wq), None, None, y_dtype=torch.int32))
+    assert np.array_equal(acc, oracle.int_gemm(xq, wq))
+
+
 @pytest.mark.parametrize("layer", workloads.tiny_layers(), ids=lambda l: l.name)
 def test_tiny_layers(hq, layer):
     run_layer(hq, layer)
@@ -482,7 +545,7 @@ def test_errors_raise(hq):
     with pytest.raises(hq.HqError):
         hq.hq_act_hadamard_quant(x, 64, 4)
     with pytest.raises(hq.HqError):
-        hq.hq_act_hadamard_quant(x[:, :64].contiguous(), 64, 8)
+        hq.hq_act_hadamard_quant(x[:, :64].contiguous(), 64, 5)
 
 
 def test_hip_graph_replay_matches_eager(hq):

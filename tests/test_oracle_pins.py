@@ -70,7 +70,7 @@ def test_golden_worked_examples():
         assert np.allclose(got, vec(ex["expected"], n), atol=1e-14), ex["cite"]
 
 
-@pytest.mark.parametrize("bits,qmax", [(4, 7), (3, 3)])
+@pytest.mark.parametrize("bits,qmax", [(4, 7), (3, 3), (8, 127)])
 def test_one_hot_codes(bits, qmax):
     """a e_i in one block -> x' = (a/8) Hraw[i, :], so s = |a| / (8 qmax) and every
     code is +-qmax with the sign pattern of row i."""
@@ -84,7 +84,7 @@ def test_one_hot_codes(bits, qmax):
         assert not q[0, :64].any() and not q[0, 128:].any()
 
 
-@pytest.mark.parametrize("bits,qmax", [(4, 7), (3, 3)])
+@pytest.mark.parametrize("bits,qmax", [(4, 7), (3, 3), (8, 127)])
 def test_constant_vector_codes(bits, qmax):
     """c 1_64 -> (8c, 0, ..., 0): one spike, the paper's own counter-example."""
     c = -0.3
@@ -111,7 +111,7 @@ def test_zero_row_scale_is_one():
     assert np.array_equal(s, [1.0, 1.0]) and not q.any()
 
 
-@pytest.mark.parametrize("bits", [3, 4])
+@pytest.mark.parametrize("bits", [3, 4, 8])
 def test_error_bound_half_step(bits):
     """No clipping with an abs-max scale, so |x' - s q| <= s / 2 everywhere."""
     layer = workloads.tiny_layers()[0]
