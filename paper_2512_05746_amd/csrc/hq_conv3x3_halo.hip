@@ -15,9 +15,9 @@
 // tiles, six vector instructions of nibble expansion per MFMA); workgroup tile 64 channels x
 // 256 consecutive pixels (of the flattened [image, row, column] order, so a tile may span
 // image rows and images; what lies outside a pixel's own image is masked per pixel and tap).
-// Two workgroups per CU; persistent, contiguous runs of tiles (the channel tiles of one pixel
-// tile are adjacent, and a workgroup keeps the activation slice when only the channel tile
-// changes).
+// Two workgroups per CU (three for the one-sum kind, which keeps no fp32 sums beside the integer
+// ones); persistent, contiguous runs of tiles (the channel tiles of one pixel tile are adjacent,
+// and a workgroup keeps the activation slice when only the channel tile changes).
 //
 // Loop order.  For each 192-channel slice of the input channels: load the activation slice,
 // then for each of the nine taps: three K steps of 64 codes against that tap's weight rows.

@@ -230,7 +230,8 @@ __device__ __forceinline__ void store16(float *dst, const float (&v)[16]) {
 }
 
 // TM x TN MFMA tiles of 32x32 per wave, WAVES_M x WAVES_N waves per workgroup.
-// TAPS = 1 (linear / 1x1) or 9 (3x3, stride 1, pad 1).
+// The tap loop of a tile has 1 step (linear / 1x1), 9 (3x3, stride 1, pad 1), 3 (weight digit
+// planes) or 27 (activation digit planes of a 3x3 convolution); see the kinds above.
 //
 // Persistent workgroups: the grid is sized to the machine and every workgroup
 // walks a contiguous run of tiles (output-channel tiles of one pixel tile are
@@ -262,7 +263,8 @@ __device__ __forceinline__ void store16(float *dst, const float (&v)[16]) {
 // instructions per load and tap.  So rows that do not exist (channels >= n,
 // pixels >= pixels) and taps outside the image read some other in-bounds row
 // instead of zeros: their sums are never stored, and a tap outside the image
-// has scale 0 (int32 output: written as 0).
+// has scale 0 (int32 output: written as 0).  The kinds with one integer sum over several taps
+// load such rows from a row of zeros instead.
 //
 // XB = 8: the operands are int8 codes, one per byte.  The 16 bytes a lane reads are one MFMA
 // operand as they are (no expansion, one MFMA per read instead of two), the sums carry no factor
