@@ -277,6 +277,14 @@ hq_status hq_int_conv2d_width(const uint8_t *xu3, const float *x_scale, const ui
  * bias, HQ_I32 outputs, built geometries, error behaviour) is as in hq_int_linear /
  * hq_int_conv2d; k (c_in) a multiple of 64.
  */
+/*
+ * Mixed widths (the paper also reports W8A4): the activation path of hq_act_hadamard_quant with
+ * codes of a_bits in {3, 4, 8} written one per byte, xq [m, k], whatever a_bits is; such codes
+ * go with 8-bit weight codes into the two calls below.
+ */
+hq_status hq_act_hadamard_quant_i8(const void *x, hq_dtype x_dtype, int64_t m, int k, int had_block,
+                                   int a_bits, int8_t *xq, float *x_scale, void *stream);
+
 hq_status hq_int_linear_i8(const int8_t *xq, const float *x_scale, const int8_t *wq,
                            const float *w_scale, const void *bias, int64_t m, int n, int k,
                            void *y, hq_dtype y_dtype, void *stream);

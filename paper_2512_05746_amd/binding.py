@@ -23,7 +23,7 @@ SYMBOLS = ("hq_status_string", "hq_quantize_weights", "hq_act_hadamard_quant",
            "hq_int_linear_static", "hq_int_conv2d_static",
            "hq_quantize_weights_single", "hq_int_linear_single",
            "hq_act_hadamard_quant_width", "hq_int_conv2d_width",
-           "hq_int_linear_i8", "hq_int_conv2d_i8")
+           "hq_int_linear_i8", "hq_int_conv2d_i8", "hq_act_hadamard_quant_i8")
 
 
 class HqError(RuntimeError):
@@ -59,6 +59,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.hq_act_hadamard_quant_width.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]
     lib.hq_int_conv2d_width.argtypes = [vp] * 5 + [i32] * 10 + [vp, i32, vp]
     lib.hq_int_linear_i8.argtypes = lib.hq_int_linear.argtypes
+    lib.hq_act_hadamard_quant_i8.argtypes = lib.hq_act_hadamard_quant.argtypes
     lib.hq_int_conv2d_i8.argtypes = lib.hq_int_conv2d.argtypes
     for name in SYMBOLS[1:]:
         getattr(lib, name).restype = i32
@@ -306,6 +307,19 @@ def hq_int_conv2d_width(xu3: torch.Tensor, x_scale: Optional[torch.Tensor], wq: 
 
 
 # ---- 8-bit codes (W8A8): int8 operands, one code per byte ---------------------------------------
+
+def hq_act_hadamard_quant_i8(x: torch.Tensor, had_block: int = 64, a_bits: int = 4
+                             ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """x [..., k] fp16/fp32 -> (xq int8 [..., k] with codes of a_bits bits, x_scale fp32 [...])."""
+    _dev(x, "x")
+    k = x.shape[-1]
+    m = x.numel() // k
+    xq = torch.empty(x.shape, dtype=torch.int8, device=x.device)
+    xs = torch.empty(x.shape[:-1], dtype=torch.float32, device=x.device)
+    _check("hq_act_hadamard_quant_i8", load_library().hq_act_hadamard_quant_i8(
+        _ptr(x), _DTYPES[x.dtype], m, k, had_block, a_bits, _ptr(xq), _ptr(xs), _stream()))
+    return xq, xs
+
 
 def hq_int_linear_i8(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torch.Tensor,
                      w_scale: Optional[torch.Tensor], bias: Optional[torch.Tensor] = None,

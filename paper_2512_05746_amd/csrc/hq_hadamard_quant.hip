@@ -550,7 +550,7 @@ hq_status launch_hadamard64(const __half *x, int64_t m, int k, int bits, uint8_t
 }
 
 template <typename T, int LOGB>
-hq_status launch_rowquant(const T *x, int64_t m, int row_len, int bits, uint32_t *xq, float *scale,
+hq_status launch_rowquant(const T *x, int64_t m, int row_len, int bits, bool bytes, uint32_t *xq, float *scale,
                           const float *given, hipStream_t stream) {
     RowQuantArgs a;
     a.given = given;
@@ -561,7 +561,7 @@ hq_status launch_rowquant(const T *x, int64_t m, int row_len, int bits, uint32_t
     while (a.max_group < 16 && a.chunks % (a.max_group * 2) == 0) a.max_group *= 2;
     a.qmax = static_cast<float>((1 << (bits - 1)) - 1);
     a.qmin = -static_cast<float>(1 << (bits - 1));
-    a.bytes = bits == 8 ? 1 : 0;
+    a.bytes = bytes ? 1 : 0;
     a.norm = static_cast<float>(1.0 / sqrt(static_cast<double>(1 << LOGB)));
 
     if (a.chunks <= kThreads * 4) {
@@ -587,17 +587,18 @@ hq_status launch_rowquant(const T *x, int64_t m, int row_len, int bits, uint32_t
 }
 
 template <typename T>
-hq_status dispatch_block(const T *x, int64_t m, int row_len, int had_block, int bits, uint32_t *xq,
+// bytes: one code per byte (always so for 8-bit codes) instead of two
+hq_status dispatch_block(const T *x, int64_t m, int row_len, int had_block, int bits, bool bytes, uint32_t *xq,
                          float *scale, const float *given, hipStream_t stream) {
     switch (hq::ilog2(had_block)) {
-        case 0: return launch_rowquant<T, 0>(x, m, row_len, bits, xq, scale, given, stream);
-        case 1: return launch_rowquant<T, 1>(x, m, row_len, bits, xq, scale, given, stream);
-        case 2: return launch_rowquant<T, 2>(x, m, row_len, bits, xq, scale, given, stream);
-        case 3: return launch_rowquant<T, 3>(x, m, row_len, bits, xq, scale, given, stream);
-        case 4: return launch_rowquant<T, 4>(x, m, row_len, bits, xq, scale, given, stream);
-        case 5: return launch_rowquant<T, 5>(x, m, row_len, bits, xq, scale, given, stream);
-        case 6: return launch_rowquant<T, 6>(x, m, row_len, bits, xq, scale, given, stream);
-        case 7: return launch_rowquant<T, 7>(x, m, row_len, bits, xq, scale, given, stream);
+        case 0: return launch_rowquant<T, 0>(x, m, row_len, bits, bytes || bits == 8, xq, scale, given, stream);
+        case 1: return launch_rowquant<T, 1>(x, m, row_len, bits, bytes || bits == 8, xq, scale, given, stream);
+        case 2: return launch_rowquant<T, 2>(x, m, row_len, bits, bytes || bits == 8, xq, scale, given, stream);
+        case 3: return launch_rowquant<T, 3>(x, m, row_len, bits, bytes || bits == 8, xq, scale, given, stream);
+        case 4: return launch_rowquant<T, 4>(x, m, row_len, bits, bytes || bits == 8, xq, scale, given, stream);
+        case 5: return launch_rowquant<T, 5>(x, m, row_len, bits, bytes || bits == 8, xq, scale, given, stream);
+        case 6: return launch_rowquant<T, 6>(x, m, row_len, bits, bytes || bits == 8, xq, scale, given, stream);
+        case 7: return launch_rowquant<T, 7>(x, m, row_len, bits, bytes || bits == 8, xq, scale, given, stream);
         default: return HQ_ERR_SHAPE;
     }
 }
@@ -622,14 +623,14 @@ namespace {
 
 // Activation path; given == NULL: per-token abs-max scales written to x_scale, else one static scale.
 hq_status act_hadamard_quant(const void *x, hq_dtype x_dtype, int64_t m, int k, int had_block, int a_bits,
-                             uint8_t *xq, float *x_scale, const float *given, void *stream) {
+                             bool bytes, uint8_t *xq, float *x_scale, const float *given, void *stream) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint32_t *out = reinterpret_cast<uint32_t *>(xq);
-    if (x_dtype == HQ_F16 && had_block == 64 && k <= 64 * kMaxBlocks && a_bits != 8)
+    if (x_dtype == HQ_F16 && had_block == 64 && k <= 64 * kMaxBlocks && a_bits != 8 && !bytes)
         return launch_hadamard64(static_cast<const __half *>(x), m, k, a_bits, xq, x_scale, given, s);
     if (x_dtype == HQ_F16)
-        return dispatch_block(static_cast<const __half *>(x), m, k, had_block, a_bits, out, x_scale, given, s);
-    return dispatch_block(static_cast<const float *>(x), m, k, had_block, a_bits, out, x_scale, given, s);
+        return dispatch_block(static_cast<const __half *>(x), m, k, had_block, a_bits, bytes, out, x_scale, given, s);
+    return dispatch_block(static_cast<const float *>(x), m, k, had_block, a_bits, bytes, out, x_scale, given, s);
 }
 
 }  // namespace
@@ -639,7 +640,15 @@ extern "C" hq_status hq_act_hadamard_quant(const void *x, hq_dtype x_dtype, int6
                                            void *stream) {
     hq_status st = check_rowquant(x, x_dtype, m, k, k, had_block, a_bits, xq, x_scale);
     if (st != HQ_OK) return st;
-    return act_hadamard_quant(x, x_dtype, m, k, had_block, a_bits, xq, x_scale, nullptr, stream);
+    return act_hadamard_quant(x, x_dtype, m, k, had_block, a_bits, false, xq, x_scale, nullptr, stream);
+}
+
+extern "C" hq_status hq_act_hadamard_quant_i8(const void *x, hq_dtype x_dtype, int64_t m, int k, int had_block,
+                                              int a_bits, int8_t *xq, float *x_scale, void *stream) {
+    hq_status st = check_rowquant(x, x_dtype, m, k, k, had_block, a_bits, xq, x_scale);
+    if (st != HQ_OK) return st;
+    return act_hadamard_quant(x, x_dtype, m, k, had_block, a_bits, true, reinterpret_cast<uint8_t *>(xq), x_scale,
+                              nullptr, stream);
 }
 
 extern "C" hq_status hq_act_hadamard_quant_static(const void *x, hq_dtype x_dtype, int64_t m, int k,
@@ -647,7 +656,7 @@ extern "C" hq_status hq_act_hadamard_quant_static(const void *x, hq_dtype x_dtyp
                                                   uint8_t *xq, void *stream) {
     hq_status st = check_rowquant(x, x_dtype, m, k, k, had_block, a_bits, xq, x_scale);
     if (st != HQ_OK) return st;
-    return act_hadamard_quant(x, x_dtype, m, k, had_block, a_bits, xq, nullptr, x_scale, stream);
+    return act_hadamard_quant(x, x_dtype, m, k, had_block, a_bits, false, xq, nullptr, x_scale, stream);
 }
 
 extern "C" hq_status hq_quantize_weights(const void *w, hq_dtype w_dtype, int n_out, int taps, int k_in,
@@ -661,8 +670,8 @@ extern "C" hq_status hq_quantize_weights(const void *w, hq_dtype w_dtype, int n_
     uint32_t *out = reinterpret_cast<uint32_t *>(wq);
     const int len = static_cast<int>(row_len);
     if (w_dtype == HQ_F16)
-        return dispatch_block(static_cast<const __half *>(w), n_out, len, had_block, w_bits, out, w_scale, nullptr, s);
-    return dispatch_block(static_cast<const float *>(w), n_out, len, had_block, w_bits, out, w_scale, nullptr, s);
+        return dispatch_block(static_cast<const __half *>(w), n_out, len, had_block, w_bits, false, out, w_scale, nullptr, s);
+    return dispatch_block(static_cast<const float *>(w), n_out, len, had_block, w_bits, false, out, w_scale, nullptr, s);
 }
 
 extern "C" const char *hq_status_string(hq_status s) {

@@ -166,6 +166,10 @@ def test_int8_code_argument_errors(lib):
     conv = lib.hq_int_conv2d_i8
     assert conv(P, P, P, P, None, 1, 4, 4, 64, 8, 3, 3, 2, 1, P, 0, None) == UNSUPPORTED
     assert conv(P, None, P, P, None, 1, 4, 4, 64, 8, 3, 3, 1, 1, P, 0, None) == NULL
+    q8 = lib.hq_act_hadamard_quant_i8
+    assert q8(P, 0, 8, 64, 64, 4, None, P, None) == NULL
+    assert q8(P, 0, 8, 64, 64, 5, P, P, None) == BITS
+    assert q8(P, 0, 8, 96, 64, 4, P, P, None) == SHAPE
     # 8-bit codes are a legal width for both quantisers, 5 bits are not
     assert lib.hq_act_hadamard_quant(None, 0, 8, 64, 64, 8, P, P, None) == NULL
     assert lib.hq_act_hadamard_quant(P, 0, 8, 64, 64, 5, P, P, None) == BITS

@@ -351,6 +351,31 @@ def test_w8a8_benchmark_configs_full_size(hq, config):
         run_layer_w8a8(hq, layer)
 
 
+@pytest.mark.parametrize("a_bits", [3, 4])
+def test_w8a4_mixed_widths(hq, a_bits):
+    """8-bit weights with 4- or 3-bit activation codes stored one per byte (the paper's W8A4)."""
+    for layer in (workloads.tiny_layers()[0], workloads.tiny_layers()[4], workloads.config_layers(2)[0]):
+        x, w, bias = workloads.make_x(layer), workloads.make_w(layer), workloads.make_bias(layer)
+        xq_o, sx_o, tx = oracle.act_hadamard_quant(x, 64, a_bits)
+        wq_o, sw_o, tw = oracle.quantize_weights(w, 64, 8)
+        xq_g, sx_g = hq.hq_act_hadamard_quant_i8(dev(x), 64, a_bits)
+        wq_g, sw_g = hq.hq_quantize_weights(dev(w), 64, 8)
+        xq_gc, wq_gc = host(xq_g), host(wq_g)
+        check_scales(layer.name + " x_scale", host(sx_g), sx_o)
+        flips = check_codes(layer.name + " xq", xq_gc, xq_o, tx, a_bits)
+        flips += check_codes(layer.name + " wq", wq_gc, wq_o, tw, 8)
+        bias_d = dev(bias) if bias is not None else None
+        if layer.kind == "linear":
+            _, y_o = oracle.int_linear(xq_gc if flips else xq_o, sx_o, (wq_gc if flips else wq_o)[:, 0, :], sw_o, bias)
+            y_g = host(hq.hq_int_linear_i8(xq_g, sx_g, wq_g, sw_g, bias_d, y_dtype=TORCH_DT[layer.dtype]))
+        else:
+            wq4 = lambda c: c.reshape(layer.n_out, 3, 3, layer.k_in)
+            _, y_o = oracle.int_conv2d(xq_gc if flips else xq_o, sx_o, wq4(wq_gc if flips else wq_o), sw_o, bias,
+                                       stride=1, pad=1, want_acc=False)
+            y_g = host(hq.hq_int_conv2d_i8(xq_g, sx_g, wq_g, sw_g, bias_d, ksize=3, y_dtype=TORCH_DT[layer.dtype]))
+        check_y(layer.name + " y (W8A%d)" % a_bits, y_g.reshape(y_o.shape), y_o)
+
+
 def test_w8a8_extreme_codes(hq):
     """All codes at -128 / 127: the largest sums the int8 path can meet stay exact."""
     m, n, k = 65, 130, 1024
