@@ -28,7 +28,7 @@ namespace {
 
 struct WaveConvArgs {
     const uint8_t *xq;   // [pixels, k/2]
-    const float *sx;     // [pixels]
+    const float *sx;     // [pixels], or one value for the whole tensor (sx_static)
     const uint8_t *wq;   // [n, 9, k/2]
     const float *sw;     // [n]
     const void *bias;    // [n] of the output dtype, or null
@@ -38,6 +38,8 @@ struct WaveConvArgs {
     uint32_t w_magic, w_shift, h_magic, h_shift;   // exact division of a pixel index by w and by h
     uint32_t n_px_tiles, n_tiles;
     int kg_log2;         // waves per tile: 1 << kg_log2 (1, 2 or 4)
+    int sx_static;       // one activation scale for the tensor: the per-tap sums are then combined with
+                         // that one scale, which equals one integer sum times one product of scales
 };
 
 template <int OUT, int NSTAGE>
@@ -154,7 +156,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_wave_kernel(WaveConvArgs a) {
             for (int t = 0; t < TAPS; ++t) {
                 uint32_t ip = pix + static_cast<uint32_t>((t / 3 - 1) * a.w + (t % 3 - 1));
                 ip = ip < last ? ip : last;
-                v[t] = a.sx[ip];
+                v[t] = a.sx[a.sx_static ? 0 : ip];
             }
             // the chunks in flight first, then the table: the table's loads are older than the
             // chunk loads, so waiting for them leaves the chunk loads in flight
@@ -311,7 +313,7 @@ hq_status hq_conv3x3_wave_launch(const GemmArgs &g, hq_dtype y_dtype, hipStream_
     if (g.k % 192 != 0 || (y_dtype != HQ_F16 && y_dtype != HQ_F32)) return HQ_ERR_UNSUPPORTED;
     WaveConvArgs a{};
     a.xq = g.xq; a.sx = g.sx; a.wq = g.wq; a.sw = g.sw; a.bias = g.bias; a.y = g.y;
-    a.pixels = g.pixels; a.n = g.n; a.k = g.k; a.h = g.h; a.w = g.w;
+    a.pixels = g.pixels; a.n = g.n; a.k = g.k; a.h = g.h; a.w = g.w; a.sx_static = g.sx_static;
     const hq::Magic31 mw = hq::magic31(static_cast<uint32_t>(g.w)), mh = hq::magic31(static_cast<uint32_t>(g.h));
     a.w_magic = mw.m; a.w_shift = mw.s; a.h_magic = mh.m; a.h_shift = mh.s;
     a.n_px_tiles = static_cast<uint32_t>((static_cast<int64_t>(g.pixels) + 63) / 64);

@@ -92,9 +92,12 @@ hq_status int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
     hipStream_t st_ = static_cast<hipStream_t>(stream);
     if (bits == 8) return launch_gemm(a, r * s, y_dtype, st_);   // the 4-bit kernels below expand nibbles
     // A 3x3 layer with about one 64x64 output tile per CU or fewer cannot fill the machine with
-    // whole tiles: it takes the kernel that also splits a tile's K range over waves.
+    // whole tiles: it takes the kernel that also splits a tile's K range over waves.  (With one
+    // scale for the tensor that kernel still combines per-tap sums in fp32, which equals the one
+    // integer sum times one product of scales up to fp32 rounding; the integer output is the
+    // tile kernel's.)
     const int64_t tiles64 = ((pixels + 63) / 64) * ((c_out + 63) / 64);
-    if (r == 3 && !sx_static && c_in % 192 == 0 && y_dtype != HQ_I32 &&
+    if (r == 3 && c_in % 192 == 0 && y_dtype != HQ_I32 &&
         tiles64 * 4 <= 5 * static_cast<int64_t>(hq::compute_units()))
         return hq_conv3x3_wave_launch(a, y_dtype, st_);
     // With at least one 64 x 256 tile per CU, keeping the activation tile in LDS for all nine taps
