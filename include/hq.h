@@ -66,7 +66,8 @@ const char *hq_status_string(hq_status s);
  *            convolution stored [Cout, R, S, Cin].
  *   had_block power of two in 1..128 dividing k_in; the transform runs along
  *            k_in inside every (n_out, tap) row; 1 means H = I.
- *   w_bits   4 (codes in [-8, 7]), 3, or 8 (codes in [-128, 127], ONE int8 code per byte:
+ *   w_bits   4 (codes in [-8, 7]), 3, 2 (codes in [-2, 1]; both in the 4-bit container), or 8
+ *            (codes in [-128, 127], ONE int8 code per byte:
  *            wq is then [n_out, taps, k_in] bytes; see the 8-bit section below).
  *   wq       out, [n_out, taps, k_in / 2] packed codes.
  *   w_scale  out, [n_out] fp32: max |transformed row over all taps| / (2^(w_bits-1) - 1),
@@ -84,7 +85,7 @@ hq_status hq_quantize_weights(const void *w, hq_dtype w_dtype, int n_out, int ta
  *   x        [m, k] of x_dtype (HQ_F16 | HQ_F32).  NHWC activations are passed
  *            with m = N*H*W and k = C.
  *   had_block power of two in 1..128 dividing k; k must be a multiple of 8.
- *   a_bits   4 (codes in [-8, 7]), 3 (codes in [-4, 3]), or 8 (codes in [-128, 127], ONE int8
+ *   a_bits   4 (codes in [-8, 7]), 3 (codes in [-4, 3]), 2 (codes in [-2, 1]), or 8 (codes in [-128, 127], ONE int8
  *            code per byte: xq is then [m, k] bytes; see the 8-bit section below).
  *   xq       out, [m, k / 2] packed codes.
  *   x_scale  out, [m] fp32: max |transformed token| / (2^(a_bits-1) - 1), 1.0 for an
@@ -201,7 +202,7 @@ hq_status hq_int_conv2d_static(const uint8_t *xq, const float *x_scale, const ui
  *
  *   w        [n_out, k_in] of w_dtype (HQ_F16 | HQ_F32), k_in even.
  *   had_block power of two in 1..128 dividing k_in (the block size the activations use).
- *   w_bits   4 or 3.
+ *   w_bits   4, 3 or 2.
  *   wq3      out, [n_out, 3, k_in / 2] packed digits, plane p at [:, p, :].
  *   w_scale  out, [n_out] fp32.
  */

@@ -609,7 +609,7 @@ hq_status check_rowquant(const void *x, hq_dtype dt, int64_t m, int k, int64_t r
                          int bits, const void *xq, const void *scale) {
     if (!x || !xq || !scale) return HQ_ERR_NULL;
     if (dt != HQ_F16 && dt != HQ_F32) return HQ_ERR_DTYPE;
-    if (bits != 3 && bits != 4 && bits != 8) return HQ_ERR_BITS;
+    if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return HQ_ERR_BITS;
     if (m <= 0 || k <= 0 || row_len <= 0 || row_len > 0x7fffffffLL) return HQ_ERR_SHAPE;
     if (!hq::pow2_upto_128(had_block) || k % had_block != 0 || k % 8 != 0) return HQ_ERR_SHAPE;
     if (!hq::aligned16(x) || !hq::aligned16(xq) || (reinterpret_cast<uintptr_t>(scale) & 3u))

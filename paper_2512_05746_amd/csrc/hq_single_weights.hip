@@ -96,7 +96,7 @@ extern "C" hq_status hq_quantize_weights_single(const void *w, hq_dtype w_dtype,
                                                 void *stream) {
     if (!w || !wq3 || !w_scale) return HQ_ERR_NULL;
     if (w_dtype != HQ_F16 && w_dtype != HQ_F32) return HQ_ERR_DTYPE;
-    if (w_bits != 3 && w_bits != 4) return HQ_ERR_BITS;
+    if (w_bits < 2 || w_bits > 4) return HQ_ERR_BITS;
     if (n_out <= 0 || k_in <= 0 || (k_in & 1)) return HQ_ERR_SHAPE;
     if (!hq::pow2_upto_128(had_block) || k_in % had_block != 0) return HQ_ERR_SHAPE;
     if (!hq::aligned16(w) || !hq::aligned16(wq3) || (reinterpret_cast<uintptr_t>(w_scale) & 3u)) return HQ_ERR_ALIGN;

@@ -111,7 +111,7 @@ extern "C" hq_status hq_act_hadamard_quant_width(const void *x, hq_dtype x_dtype
                                                  uint8_t *xu3, void *stream) {
     if (!x || !x_scale || !xu3) return HQ_ERR_NULL;
     if (x_dtype != HQ_F16 && x_dtype != HQ_F32) return HQ_ERR_DTYPE;
-    if (a_bits != 3 && a_bits != 4) return HQ_ERR_BITS;
+    if (a_bits < 2 || a_bits > 4) return HQ_ERR_BITS;
     if (nb <= 0 || h <= 0 || w <= 0 || c <= 0 || (c & 1)) return HQ_ERR_SHAPE;
     if (!hq::pow2_upto_128(had_block) || had_block > 64 || w % had_block != 0) return HQ_ERR_SHAPE;
     if (!hq::aligned16(x) || !hq::aligned16(xu3) || (reinterpret_cast<uintptr_t>(x_scale) & 3u)) return HQ_ERR_ALIGN;

@@ -44,7 +44,7 @@ def test_act_quant_argument_errors(lib):
     assert f(P, 0, 8, 64, 64, 4, P, None, None) == NULL
     assert f(P, 2, 8, 64, 64, 4, P, P, None) == DTYPE      # int32 is not an input dtype
     assert f(P, 0, 8, 64, 64, 6, P, P, None) == BITS
-    assert f(P, 0, 8, 64, 64, 2, P, P, None) == BITS
+    assert f(P, 0, 8, 64, 64, 1, P, P, None) == BITS
     assert f(P, 0, 0, 64, 64, 4, P, P, None) == SHAPE      # no rows
     assert f(P, 0, 8, 96, 64, 4, P, P, None) == SHAPE      # k not a multiple of the block
     assert f(P, 0, 8, 64, 48, 4, P, P, None) == SHAPE      # block not a power of two

@@ -431,6 +431,14 @@ def test_static_scale_is_read_at_run_time(hq):
         check_codes("codes", unpack_codes(host(hq.hq_act_hadamard_quant_static(xd, s_d, 64, 4))), q_o, t, 4)
 
 
+@pytest.mark.parametrize("a_bits,w_bits", [(4, 2), (2, 4), (2, 2), (3, 3)])
+def test_lower_bit_widths(hq, a_bits, w_bits):
+    """2- and 3-bit codes (in the 4-bit container) for either operand, linear and 3x3."""
+    import dataclasses
+    for idx in (0, 3, 4):
+        run_layer(hq, dataclasses.replace(workloads.tiny_layers()[idx], a_bits=a_bits, w_bits=w_bits))
+
+
 @pytest.mark.parametrize("config", [1, 2, 3, 4, 5])
 def test_benchmark_configs_full_size(hq, config):
     """All five configurations at their full sizes, every output element compared."""
