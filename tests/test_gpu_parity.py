@@ -573,6 +573,58 @@ def test_int_conv_geometry(hq, nb, h, w, cin, cout, ks):
     check_y("y", y_g, y_o, rtol=1e-5)
 
 
+@pytest.mark.parametrize("nb,h,w,cin,cout", [(8, 41, 50, 192, 250), (5, 60, 71, 384, 200), (3, 79, 70, 192, 330)])
+def test_activation_resident_conv_odd_geometry(hq, nb, h, w, cin, cout):
+    """Shapes that take the kernel with the activation tile resident in LDS (at least one 64 x 256
+    tile per CU), with image sizes that are not powers of two, tiles that span image rows and
+    images, a ragged last pixel tile and a ragged last channel tile; per-pixel scales (one or two
+    192-channel slices) and one scale for the tensor (zeros must be loaded outside the image)."""
+    rng = np.random.default_rng(nb * 1000 + h * 100 + w + cin + cout)
+    xq = rng.integers(-8, 8, (nb, h, w, cin)).astype(np.int8)
+    wq = rng.integers(-8, 8, (cout, 3, 3, cin)).astype(np.int8)
+    sx = rng.uniform(0.01, 1.0, (nb, h, w)).astype(np.float32)
+    sw = rng.uniform(0.001, 0.1, cout).astype(np.float32)
+    bias = rng.standard_normal(cout).astype(np.float32)
+    xq_d, wq_d = dev(pack_codes(xq)), dev(pack_codes(wq.reshape(cout, 9, cin)))
+    _, y_o = oracle.int_conv2d(xq, sx, wq, sw, bias, stride=1, pad=1, want_acc=False)
+    y_g = host(hq.hq_int_conv2d(xq_d, dev(sx), wq_d, dev(sw), dev(bias), ksize=3, y_dtype=torch.float32))
+    check_y("y", y_g, y_o, rtol=2e-4)     # sums are folded per (slice, tap) from a biased accumulator
+    s1 = torch.tensor([0.37], dtype=torch.float32, device="cuda")
+    _, y_o = oracle.int_conv2d_static(xq, 0.37, wq, sw, bias, stride=1, pad=1, want_acc=False)
+    y_g = host(hq.hq_int_conv2d_static(xq_d, s1, wq_d, dev(sw), dev(bias), ksize=3, y_dtype=torch.float32))
+    check_y("y (static)", y_g, y_o, rtol=1e-5)
+
+
+def test_random_small_shapes(hq):
+    """A seeded sweep of small ragged shapes through every integer-stage entry point: int32 sums bit
+    for bit on random full-range codes."""
+    rng = np.random.default_rng(20251205)
+    for case in range(24):
+        m, n = int(rng.integers(1, 300)), int(rng.integers(1, 200))
+        k = 64 * int(rng.integers(1, 7))
+        xq = rng.integers(-8, 8, (m, k)).astype(np.int8)
+        wq = rng.integers(-8, 8, (n, k)).astype(np.int8)
+        tag = "case %d: m %d n %d k %d" % (case, m, n, k)
+        acc = host(hq.hq_int_linear(dev(pack_codes(xq)), None, dev(pack_codes(wq)), None, None, y_dtype=torch.int32))
+        assert np.array_equal(acc, oracle.int_gemm(xq, wq)), tag
+        x8 = rng.integers(-128, 128, (m, k)).astype(np.int8)
+        w8 = rng.integers(-128, 128, (n, k)).astype(np.int8)
+        acc = host(hq.hq_int_linear_i8(dev(x8), None, dev(w8), None, None, y_dtype=torch.int32))
+        assert np.array_equal(acc, oracle.int_gemm(x8, w8)), tag + " (int8)"
+        nb, h, w = int(rng.integers(1, 4)), int(rng.integers(1, 14)), int(rng.integers(1, 14))
+        cout = int(rng.integers(1, 100))
+        xc = rng.integers(-8, 8, (nb, h, w, k)).astype(np.int8)
+        wc = rng.integers(-8, 8, (cout, 3, 3, k)).astype(np.int8)
+        tag = "case %d: %dx%dx%d cin %d cout %d" % (case, nb, h, w, k, cout)
+        xc_d, wc_d = dev(pack_codes(xc)), dev(pack_codes(wc.reshape(cout, 9, k)))
+        ones_x, ones_w = np.ones((nb, h, w)), np.ones(cout)
+        acc_t, _ = oracle.int_conv2d(xc, ones_x, wc, ones_w, None, stride=1, pad=1, want_y=False)
+        acc = host(hq.hq_int_conv2d(xc_d, None, wc_d, None, None, ksize=3, y_dtype=torch.int32))
+        assert np.array_equal(acc, acc_t), tag
+        acc = host(hq.hq_int_conv2d_static(xc_d, None, wc_d, None, None, ksize=3, y_dtype=torch.int32))
+        assert np.array_equal(acc, acc_t.sum(axis=3)), tag + " (one sum)"
+
+
 def test_errors_raise(hq):
     x = torch.zeros((4, 96), dtype=torch.float16, device="cuda")
     with pytest.raises(hq.HqError):
