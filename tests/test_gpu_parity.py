@@ -666,3 +666,94 @@ def test_hip_graph_replay_matches_eager(hq):
         assert np.array_equal(host(y).view(np.uint16), want.view(np.uint16)), "replay %d" % i
         run()   # eager work between replays
         torch.cuda.synchronize()
+
+
+def test_hip_graph_replay_of_the_other_schemes(hq):
+    """Static-scale, Single-scheme, width-axis and 8-bit calls captured into one HIP graph; the
+    static scale is changed between replays in device memory and the replay must follow it."""
+    layer = workloads.tiny_layers()[7]                      # 13 x 16 x 16, 192 -> 320, 3x3
+    x = dev(workloads.make_x(layer))
+    w = dev(workloads.make_w(layer))
+    wq, sw = hq.hq_quantize_weights(w, 64, 4)
+    wq1, sw1 = hq.hq_quantize_weights(w, 1, 4)
+    wq8, sw8 = hq.hq_quantize_weights(w, 64, 8)
+    wq3, sw3 = hq.hq_quantize_weights_single(w[:, 4, :].contiguous(), 64, 4)
+    s_d = torch.tensor([0.3], dtype=torch.float32, device="cuda")
+    shape = tuple(x.shape[:-1])
+    xq = torch.empty(shape + (layer.k_in // 2,), dtype=torch.uint8, device="cuda")
+    xd = torch.empty(shape + (layer.k_in // 2,), dtype=torch.uint8, device="cuda")
+    sxd = torch.empty(shape, dtype=torch.float32, device="cuda")
+    xu3 = torch.empty((3,) + shape + (layer.k_in // 2,), dtype=torch.uint8, device="cuda")
+    x8 = torch.empty(shape + (layer.k_in,), dtype=torch.int8, device="cuda")
+    sx8 = torch.empty(shape, dtype=torch.float32, device="cuda")
+    ys = [torch.empty(shape + (layer.n_out,), dtype=torch.float16, device="cuda") for _ in range(4)]
+    m = x.numel() // layer.k_in
+
+    def run():
+        hq.hq_act_hadamard_quant_static(x, s_d, 64, 4, out=xq)
+        hq.hq_int_conv2d_static(xq, s_d, wq, sw, None, ksize=3, y_dtype=torch.float16, out=ys[0])
+        hq.hq_act_hadamard_quant(x, 64, 4, out=(xd, sxd))
+        hq.hq_int_linear_single(xd.reshape(m, -1), sxd.reshape(-1), wq3, sw3, None, 64, y_dtype=torch.float16,
+                                out=ys[1].reshape(m, -1))
+        hq.hq_act_hadamard_quant_width(x, s_d, 16, 4, out=xu3)
+        hq.hq_int_conv2d_width(xu3, s_d, wq1, sw1, None, 16, y_dtype=torch.float16, out=ys[2])
+        hq.hq_act_hadamard_quant(x, 64, 8, out=(x8, sx8))
+        hq.hq_int_conv2d_i8(x8, sx8, wq8, sw8, None, ksize=3, y_dtype=torch.float16, out=ys[3])
+
+    want = {}
+    for s in (0.3, 0.11):
+        s_d.fill_(s)
+        run()
+        want[s] = [host(y).copy() for y in ys]
+    assert not np.array_equal(want[0.3][0], want[0.11][0])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for i, s in enumerate((0.11, 0.3, 0.3, 0.11)):
+        for y in ys:
+            y.zero_()
+        s_d.fill_(s)
+        torch.cuda.synchronize()
+        graph.replay()
+        for j, y in enumerate(ys):
+            assert np.array_equal(host(y).view(np.uint16), want[s][j].view(np.uint16)), "replay %d output %d" % (i, j)
+        run()   # eager work between replays
+        torch.cuda.synchronize()
+
+
+def test_two_streams_at_once(hq):
+    """The library keeps no state: two layers run on two streams at the same time and both results
+    equal those of running them one after the other."""
+    la, lb = workloads.tiny_layers()[4], workloads.tiny_layers()[0]
+    xa, xb = dev(workloads.make_x(la)), dev(workloads.make_x(lb))
+    wa, swa = hq.hq_quantize_weights(dev(workloads.make_w(la)), 64, 4)
+    wb, swb = hq.hq_quantize_weights(dev(workloads.make_w(lb)), 64, 4)
+
+    def layer_a():
+        q, s = hq.hq_act_hadamard_quant(xa, 64, 4)
+        return hq.hq_int_conv2d(q, s, wa, swa, None, ksize=3, y_dtype=torch.float16)
+
+    def layer_b():
+        q, s = hq.hq_act_hadamard_quant(xb, 64, 4)
+        return hq.hq_int_linear(q, s, wb, swb, None, y_dtype=torch.float16)
+
+    ya, yb = host(layer_a()).copy(), host(layer_b()).copy()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    outs = []
+    for _ in range(8):
+        with torch.cuda.stream(s1):
+            oa = layer_a()
+        with torch.cuda.stream(s2):
+            ob = layer_b()
+        outs.append((oa, ob))
+    torch.cuda.synchronize()
+    for oa, ob in outs:
+        assert np.array_equal(host(oa).view(np.uint16), ya.view(np.uint16))
+        assert np.array_equal(host(ob).view(np.uint16), yb.view(np.uint16))
