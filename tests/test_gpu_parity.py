@@ -595,6 +595,110 @@ def test_activation_resident_conv_odd_geometry(hq, nb, h, w, cin, cout):
     check_y("y (static)", y_g, y_o, rtol=1e-5)
 
 
+def _random_bytes(shape, seed):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    return torch.randint(0, 256, shape, dtype=torch.uint8, device="cuda", generator=g)
+
+
+def test_int_linear_at_the_largest_token_count(hq):
+    """The packed operands are addressed with 32-bit byte offsets: the largest token count the
+    linear call accepts for K = 256 (4 GiB of codes) must give the oracle's sums on its first,
+    middle and LAST rows, and one token more must be refused, not wrapped."""
+    k, n = 256, 24
+    m = (2 ** 32 - 1) // (k // 2) - 3
+    print("linear at m =", m, flush=True)
+    xq = _random_bytes((m, k // 2), 1)
+    sx = torch.rand(m, device="cuda") * 0.5 + 0.01
+    rng = np.random.default_rng(5)
+    wq = rng.integers(-8, 8, (n, k)).astype(np.int8)
+    sw = rng.uniform(0.001, 0.1, n).astype(np.float32)
+    bias = rng.standard_normal(n).astype(np.float32)
+    wq_d = dev(pack_codes(wq))
+    rows = np.unique(np.concatenate([np.arange(130), m // 2 + np.arange(-64, 64), np.arange(m - 300, m),
+                                     rng.integers(0, m, 500)]))
+    rows_d = torch.from_numpy(rows).cuda()
+    xq_s = unpack_codes(host(xq[rows_d]))
+    acc_o, y_o = oracle.int_linear(xq_s, host(sx[rows_d]), wq, sw, bias)
+    acc_g = hq.hq_int_linear(xq, None, wq_d, None, None, y_dtype=torch.int32)
+    assert np.array_equal(host(acc_g[rows_d]), acc_o)
+    del acc_g
+    y_g = hq.hq_int_linear(xq, sx, wq_d, dev(sw), dev(bias), y_dtype=torch.float32)
+    check_y("y", host(y_g[rows_d]), y_o, rtol=1e-5)
+    del y_g
+    # one row more: the offsets of the last rows would pass 2^32 (the buffer below is big enough,
+    # and is never read: the call is refused before any launch)
+    xq1 = torch.empty((m + 1, k // 2), dtype=torch.uint8, device="cuda")
+    with pytest.raises(hq.HqError):
+        hq.hq_int_linear(xq1, None, wq_d, None, None, y_dtype=torch.int32)
+
+
+@pytest.mark.parametrize("cin,cout,hw,static", [(64, 8, 128, False), (192, 64, 64, False), (192, 64, 64, True)])
+def test_int_conv_at_the_largest_pixel_count(hq, cin, cout, hw, static):
+    """The same for the 3x3 convolution (tile kernel with 64-code chunks; kernel with the activation
+    tile resident in LDS, per-pixel scales and one scale): the largest batch whose activation
+    offsets, shifted by a tap, stay below 2^32.  Whole images - the first, a middle one, the last
+    two - against the oracle; one image more is refused."""
+    kb = cin // 2
+    nb = ((2 ** 32 - 1) // kb - hw - 2) // (hw * hw)
+    print("conv at", (nb, hw, hw, cin), "->", cout, "static" if static else "dynamic", flush=True)
+    xq = _random_bytes((nb, hw, hw, kb), 2)
+    sx = torch.rand((nb, hw, hw), device="cuda") * 0.5 + 0.01
+    rng = np.random.default_rng(cin + cout)
+    wq = rng.integers(-8, 8, (cout, 3, 3, cin)).astype(np.int8)
+    sw = rng.uniform(0.001, 0.1, cout).astype(np.float32)
+    bias = rng.standard_normal(cout).astype(np.float32)
+    wq_d = dev(pack_codes(wq.reshape(cout, 9, cin)))
+    images = [0, nb // 2, nb - 2, nb - 1]
+    if static:
+        s1 = torch.tensor([0.37], dtype=torch.float32, device="cuda")
+        y_g = hq.hq_int_conv2d_static(xq, s1, wq_d, dev(sw), dev(bias), ksize=3, y_dtype=torch.float32)
+    else:
+        y_g = hq.hq_int_conv2d(xq, sx, wq_d, dev(sw), dev(bias), ksize=3, y_dtype=torch.float32)
+    for i in images:
+        xq_i = unpack_codes(host(xq[i:i + 1]))
+        if static:
+            _, y_o = oracle.int_conv2d_static(xq_i, 0.37, wq, sw, bias, stride=1, pad=1, want_acc=False)
+        else:
+            _, y_o = oracle.int_conv2d(xq_i, host(sx[i:i + 1]), wq, sw, bias, stride=1, pad=1, want_acc=False)
+        check_y("y of image %d" % i, host(y_g[i:i + 1]).reshape(y_o.shape), y_o, rtol=2e-4)
+    del y_g
+    if cout <= 8 and not static:   # per-tap int32 sums (9 x the output volume): the small layer only
+        acc_g = hq.hq_int_conv2d(xq, None, wq_d, None, None, ksize=3, y_dtype=torch.int32)
+        for i in images:
+            acc_o, _ = oracle.int_conv2d(unpack_codes(host(xq[i:i + 1])), host(sx[i:i + 1]), wq, sw, None,
+                                         stride=1, pad=1)
+            assert np.array_equal(host(acc_g[i:i + 1]).reshape(acc_o.shape), acc_o), "image %d" % i
+        del acc_g
+    xq1 = torch.empty((nb + 1, hw, hw, kb), dtype=torch.uint8, device="cuda")   # never read: refused before any launch
+    sx1 = torch.empty((nb + 1, hw, hw), dtype=torch.float32, device="cuda")
+    with pytest.raises(hq.HqError):
+        hq.hq_int_conv2d(xq1, sx1, wq_d, dev(sw), None, ksize=3, y_dtype=torch.float16)
+
+
+def test_act_quant_beyond_4gi_elements(hq):
+    """More than 2^32 elements (8.6 GB of fp16) through the transform-quantise call: sampled
+    tokens, the last ones included, against the oracle."""
+    k = 256
+    m = 2 ** 24 + 5
+    print("act quant at m =", m, flush=True)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3)
+    x = torch.randn((m, k), dtype=torch.float16, device="cuda", generator=g)
+    rng = np.random.default_rng(9)
+    rows = np.unique(np.concatenate([np.arange(70), np.arange(m - 70, m), rng.integers(0, m, 400)]))
+    rows_d = torch.from_numpy(rows).cuda()
+    xq_o, sx_o, t = oracle.act_hadamard_quant(host(x[rows_d]), 64, 4)
+    xq_g, sx_g = hq.hq_act_hadamard_quant(x, 64, 4)
+    check_scales("x_scale", host(sx_g[rows_d]), sx_o)
+    check_codes("xq", unpack_codes(host(xq_g[rows_d])), xq_o, t, 4)
+    del xq_g, sx_g
+    s1 = torch.tensor([0.2], dtype=torch.float32, device="cuda")
+    xq_o, t = oracle.act_hadamard_quant_static(host(x[rows_d]), 64, 4, float(np.float32(0.2)))
+    xq_g = hq.hq_act_hadamard_quant_static(x, s1, 64, 4)
+    check_codes("xq (static)", unpack_codes(host(xq_g[rows_d])), xq_o, t, 4)
+
+
 def test_random_small_shapes(hq):
     """A seeded sweep of small ragged shapes through every integer-stage entry point: int32 sums bit
     for bit on random full-range codes."""
