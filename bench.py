@@ -269,6 +269,24 @@ def main():
         run_quant(s)   # restore the 4-bit scales for anything that follows
     torch.cuda.synchronize()
 
+    # ---- the downsampling convolutions (3x3, stride 2, pad 1) at the sweep's first three sizes -------
+    down_layers = []
+    for s in state:
+        layer, x, wq, sw, xq, sx, y = s
+        if not (layer.kind == "conv" and layer.ksize == 3 and x.shape[1] >= 16):
+            continue
+        ho = (x.shape[1] - 1) // 2 + 1
+        y2 = torch.empty((x.shape[0], ho, ho, layer.n_out), dtype=torch.float16, device="cuda")
+
+        def run_down(_s, xq=xq, sx=sx, wq=wq, sw=sw, y2=y2):
+            hq.hq_int_conv2d(xq, sx, wq, sw, None, ksize=3, stride=2, y_dtype=torch.float16, out=y2)
+
+        run_down(s)
+        i_us = batched_us(run_down, s)
+        down_layers.append({"layer": layer.name + "_stride2", "int_us": round(i_us, 2),
+                            "int_tops": round(layer.ops / 4 / i_us / 1e6, 1)})
+    torch.cuda.synchronize()
+
     conv3 = [i for i, (l, *_r) in enumerate(state) if l.kind == "conv" and l.ksize == 3]
     conv3_ops = sum(state[i][0].ops for i in conv3)
     conv3_us = float(sum(int_us[i] for i in conv3))
@@ -374,6 +392,11 @@ def main():
                     "convolution: transform along the width axis, one scale, integer H_raw on the codes, "
                     "un-transformed weights); useful = 2*M*N*K, issued = three integer passes; not part of `value`",
             "layers": width_layers,
+        },
+        "stride2_downsampling": {
+            "what": "hq_int_conv2d with stride 2 on the 3x3 layers of the sweep down to 16 x 16 (a quarter of "
+                    "the stride-1 operations each); not part of `value`",
+            "layers": down_layers,
         },
         "w8a8_mode": {
             "what": "the same sweep with 8-bit codes for both operands (int8 straight into the matrix "

@@ -125,9 +125,12 @@ hq_status hq_int_linear(const uint8_t *xq, const float *x_scale, const uint8_t *
  *   A tap outside the image contributes 0.
  *   xq [nb, h, w, c_in/2], x_scale [nb, h, w], wq [c_out, R, S, c_in/2],
  *   w_scale [c_out], bias [c_out] of y_dtype or NULL, y [nb, h, w, c_out].
- *   Built: R = S in {1, 3}, stride 1, pad (R-1)/2 (same-size output); anything
- *   else returns HQ_ERR_UNSUPPORTED.  c_in a multiple of 64.
- *   y_dtype == HQ_I32 writes the per-tap accumulators [nb, h, w, R*S, c_out].
+ *   Built: R = S in {1, 3}, stride 1, pad (R-1)/2 (same-size output), and the
+ *   downsampling form R = S = 3, stride 2, pad 1, where output pixel (p, q) reads
+ *   input rows 2p + r - 1 and columns 2q + s - 1 and y is
+ *   [nb, (h-1)/2 + 1, (w-1)/2 + 1, c_out]; anything else returns
+ *   HQ_ERR_UNSUPPORTED.  c_in a multiple of 64.
+ *   y_dtype == HQ_I32 writes the per-tap accumulators [nb, h_out, w_out, R*S, c_out].
  */
 hq_status hq_int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
                         const float *w_scale, const void *bias, int nb, int h, int w,

@@ -145,13 +145,32 @@ def hq_int_linear(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torch.T
     return y
 
 
+def _conv_out(h: int, w: int, ksize: int, stride: int, pad: int):
+    if stride < 1 or pad < 0 or ksize < 1:
+        raise ValueError("bad convolution geometry")
+    return (h + 2 * pad - ksize) // stride + 1, (w + 2 * pad - ksize) // stride + 1
+
+
+def _out(out: Optional[torch.Tensor], shape, dtype: torch.dtype, device) -> torch.Tensor:
+    """A caller's output buffer (must hold exactly the result) or a new one."""
+    if out is None:
+        return torch.empty(shape, dtype=dtype, device=device)
+    n = 1
+    for d in shape:
+        n *= d
+    if not out.is_cuda or out.dtype != dtype or out.numel() != n or not out.is_contiguous():
+        raise ValueError("out must be a contiguous device tensor of %s with %d elements" % (dtype, n))
+    return out
+
+
 def hq_int_conv2d(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torch.Tensor,
                   w_scale: Optional[torch.Tensor], bias: Optional[torch.Tensor] = None,
                   ksize: int = 3, stride: int = 1, pad: Optional[int] = None,
                   y_dtype: torch.dtype = torch.float16, out: Optional[torch.Tensor] = None
                   ) -> torch.Tensor:
-    """xq [nb, h, w, cin/2], wq [cout, ksize*ksize, cin/2] -> y [nb, h, w, cout];
-    y_dtype int32 returns the per-tap sums [nb, h, w, ksize*ksize, cout]."""
+    """xq [nb, h, w, cin/2], wq [cout, ksize*ksize, cin/2] -> y [nb, ho, wo, cout] (same size for
+    stride 1; ksize 3, stride 2, pad 1 halves it, rounding up); y_dtype int32 returns the per-tap
+    sums [nb, ho, wo, ksize*ksize, cout]."""
     _dev(xq, "xq"), _dev(wq, "wq")
     nb, h, w, cb = xq.shape
     cout = wq.shape[0]
@@ -160,12 +179,11 @@ def hq_int_conv2d(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torch.T
     if bias is not None and bias.dtype != y_dtype:
         raise ValueError("bias must have the output dtype")
     pad = (ksize - 1) // 2 if pad is None else pad
-    if out is not None:
-        y = out
-    elif y_dtype == torch.int32:
-        y = torch.empty((nb, h, w, ksize * ksize, cout), dtype=y_dtype, device=xq.device)
+    ho, wo = _conv_out(h, w, ksize, stride, pad)
+    if y_dtype == torch.int32:
+        y = _out(out, (nb, ho, wo, ksize * ksize, cout), y_dtype, xq.device)
     else:
-        y = torch.empty((nb, h, w, cout), dtype=y_dtype, device=xq.device)
+        y = _out(out, (nb, ho, wo, cout), y_dtype, xq.device)
     _check("hq_int_conv2d", load_library().hq_int_conv2d(
         _ptr(xq), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), nb, h, w, cb * 2, cout,
         ksize, ksize, stride, pad, _ptr(y), _DTYPES[y_dtype], _stream()))
@@ -224,7 +242,8 @@ def hq_int_conv2d_static(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: 
     if bias is not None and bias.dtype != y_dtype:
         raise ValueError("bias must have the output dtype")
     pad = (ksize - 1) // 2 if pad is None else pad
-    y = out if out is not None else torch.empty((nb, h, w, cout), dtype=y_dtype, device=xq.device)
+    ho, wo = _conv_out(h, w, ksize, stride, pad)
+    y = _out(out, (nb, ho, wo, cout), y_dtype, xq.device)
     _check("hq_int_conv2d_static", load_library().hq_int_conv2d_static(
         _ptr(xq), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), nb, h, w, cb * 2, cout,
         ksize, ksize, stride, pad, _ptr(y), _DTYPES[y_dtype], _stream()))

@@ -83,13 +83,22 @@ hq_status int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
     const int64_t pixels = static_cast<int64_t>(nb) * h * w;
     hq_status st = check_common(xq, x_scale, wq, w_scale, bias, pixels, c_out, c_in, y, y_dtype);
     if (st != HQ_OK) return st;
-    if (r != s || (r != 1 && r != 3) || stride != 1 || pad != (r - 1) / 2) return HQ_ERR_UNSUPPORTED;
+    const bool down = r == 3 && s == 3 && stride == 2 && pad == 1 && bits == 4;   // the downsampling convolution
+    if (!down && (r != s || (r != 1 && r != 3) || stride != 1 || pad != (r - 1) / 2)) return HQ_ERR_UNSUPPORTED;
     if (!fits_32bit(pixels, w, c_out, r * s, bits == 8 ? 2 * c_in : c_in)) return HQ_ERR_UNSUPPORTED;
     // one sum over all taps: 256 * (64 per product) * (codes per sum) must stay below 2^31
     if (sx_static && static_cast<int64_t>(c_in) * r * s >= 131072) return HQ_ERR_SHAPE;
     GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(pixels), c_out, c_in, h, w, 0, 0, 0, 1,
                sx_static, 1.0f, bits};
     hipStream_t st_ = static_cast<hipStream_t>(stream);
+    if (down) {   // output [nb, (h - 1) / 2 + 1, (w - 1) / 2 + 1, c_out]: the tile kernel's stride-2 form
+        a.stride = 2;
+        a.h_out = (h - 1) / 2 + 1;
+        a.w_out = (w - 1) / 2 + 1;
+        a.in_pixels = static_cast<uint32_t>(pixels);
+        a.pixels = static_cast<uint32_t>(static_cast<int64_t>(nb) * a.h_out * a.w_out);
+        return hq_gemm_launch_64x64(a, 9, y_dtype, st_);
+    }
     if (bits == 8) return launch_gemm(a, r * s, y_dtype, st_);   // the 4-bit kernels below expand nibbles
     // A 3x3 layer with about one 64x64 output tile per CU or fewer cannot fill the machine with
     // whole tiles: it takes the kernel that also splits a tile's K range over waves.  (With one

@@ -51,6 +51,11 @@ struct GemmArgs {
                          // one integer sum over all taps)
     float out_scale;     // factor applied with w_scale (1, or 2^(-log2(block)/2) for digit-plane weights)
     int bits;            // 4: two codes per byte (3-bit codes included); 8: one int8 code per byte
+    // 3x3 convolution with stride 2 (pad 1): `pixels` counts OUTPUT pixels [nb, h_out, w_out], h and w
+    // are the INPUT image size, in_pixels = nb * h * w.  stride 0 or 1: same-size output.
+    int stride;
+    int h_out, w_out;
+    uint32_t in_pixels;
 };
 
 namespace {
@@ -269,9 +274,16 @@ __device__ __forceinline__ void store16(float *dst, const float (&v)[16]) {
 // XB = 8: the operands are int8 codes, one per byte.  The 16 bytes a lane reads are one MFMA
 // operand as they are (no expansion, one MFMA per read instead of two), the sums carry no factor
 // 256, and a chunk row of KCH * 16 bytes holds KCH * 16 codes.
-template <int TM, int TN, int WAVES_M, int WAVES_N, int KIND, int OUT, int KCH, int NSTAGE, int OCC, int XB = 4>
+//
+// S2: 3x3 window with stride 2.  Output pixel (image, oh, ow) sits over input pixel (2 oh, 2 ow):
+// the activation row of a tile row is that input pixel's (a per-tile table of "centres" beside
+// the tap masks), a tap still shifts it by a uniform (dr * w + ds) input pixels, and everything
+// on the output side (tiles, scales of the channels, stores) counts output pixels.
+template <int TM, int TN, int WAVES_M, int WAVES_N, int KIND, int OUT, int KCH, int NSTAGE, int OCC, int XB = 4,
+          bool S2 = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(GemmArgs a) {
     static_assert(XB == 4 || XB == 8, "4-bit codes in pairs or int8 codes");
+    static_assert(!S2 || KIND == kConvPerTap || KIND == kConvSum, "stride 2 is a 3x3 window's");
     constexpr int SHIFT = XB == 8 ? 0 : 8;                    // log2 of the factor the integer sums carry
     constexpr float UNIT = XB == 8 ? 1.0f : 1.0f / 256.0f;
     constexpr int TAPS = taps_of(KIND);
@@ -310,6 +322,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     // two sets of per-tile tables: the set of tile k+1 is built while tile k is multiplied
     __shared__ float s_sx[2][STAPS][BP];   // x_scale / 256 of the input pixel under tap t; 0 outside
     __shared__ int s_mask[2][BP];         // bit t: tap t of this output pixel is inside the image
+    __shared__ uint32_t s_center[2][S2 ? BP : 1];   // stride 2: input pixel under the window's centre
     __shared__ __attribute__((aligned(16))) float s_sw[2][BCO];     // w_scale of the tile's channels
     __shared__ __attribute__((aligned(16))) float s_bias[2][BCO];   // bias (0 if absent)
 
@@ -355,7 +368,22 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
         if (tid < BP) {
             const uint32_t pix = p0 + tid;
             int mask = 0;
-            if (pix < a.pixels) {
+            if constexpr (S2) {
+                uint32_t center = 0;
+                if (pix < a.pixels) {
+                    const uint32_t q = pix / static_cast<uint32_t>(a.w_out);
+                    const int ow = static_cast<int>(pix - q * a.w_out);
+                    const uint32_t img = q / static_cast<uint32_t>(a.h_out);
+                    const int oh = static_cast<int>(q - img * a.h_out);
+#pragma unroll
+                    for (int t = 0; t < 9; ++t) {
+                        const int ih = 2 * oh + t / 3 - 1, iw = 2 * ow + t % 3 - 1;
+                        mask |= (ih >= 0 && ih < a.h && iw >= 0 && iw < a.w) ? (1 << t) : 0;
+                    }
+                    center = (img * a.h + 2 * oh) * a.w + 2 * ow;
+                }
+                s_center[k & 1][tid] = center;
+            } else if (pix < a.pixels) {
                 if constexpr (CONV) mask = tap_mask<9>(pix, a.h, a.w);
                 else mask = (1 << TAPS) - 1;
             }
@@ -376,7 +404,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
                     const int mask = s_mask[k & 1][p];
                     if (PER_TAP ? ((mask >> t) & 1) : (mask != 0)) {
                         const int delta = KIND == kConvPerTap ? (t / 3 - 1) * a.w + (t % 3 - 1) : 0;
-                        t_sx[j] = a.sx[a.sx_static ? 0 : static_cast<int64_t>(p0 + p) + delta];
+                        int64_t at = static_cast<int64_t>(p0 + p);
+                        if constexpr (S2) at = s_center[k & 1][p];
+                        t_sx[j] = a.sx[a.sx_static ? 0 : at + delta];
                     }
                 }
             }
@@ -424,7 +454,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
         return static_cast<uint32_t>(((q % KCH) ^ ((row >> 3) & 1)) * 16);   // swizzle, see above
     };
 #pragma unroll
-    for (int j = 0; j < B_SLOTS; ++j) ld_bmax[j] = (a.pixels - 1) * kbytes + slot_byte(j * NW + wave);
+    for (int j = 0; j < B_SLOTS; ++j)
+        ld_bmax[j] = ((S2 ? a.in_pixels : a.pixels) - 1) * kbytes + slot_byte(j * NW + wave);
     auto set_fetch_tap = [&](int step) {
         const int t = step % WTAPS;   // tap of the 3x3 window (digit planes: step = plane * 9 + tap)
         a_tap_off = static_cast<uint32_t>(t) * kbytes;
@@ -455,6 +486,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
             const int i = j * NW + wave;
             uint32_t pix = p0 + slot_row(i);
             pix = pix < a.pixels ? pix : a.pixels - 1;
+            if constexpr (S2) pix = i < B_INSTR ? s_center[k & 1][slot_row(i)] : 0;   // needs the tables of tile k
             ld_b[j] = pix * kbytes + slot_byte(i);
             if constexpr (ZPAD) {   // needs the masks of tile k to be visible
                 ld_mask[j] = i < B_INSTR ? s_mask[k & 1][slot_row(i)] : 0;
@@ -743,7 +775,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     }
 }
 
-template <int TM, int TN, int WAVES_M, int WAVES_N, int KIND, int OUT, int KCH, int NSTAGE, int OCC, int XB = 4>
+template <int TM, int TN, int WAVES_M, int WAVES_N, int KIND, int OUT, int KCH, int NSTAGE, int OCC, int XB = 4,
+          bool S2 = false>
 hq_status launch_tile(GemmArgs a, hipStream_t stream) {
     constexpr int TAPS = taps_of(KIND);
     constexpr int BCO = 32 * TM * WAVES_M, BP = 32 * TN * WAVES_N;
@@ -756,7 +789,7 @@ hq_status launch_tile(GemmArgs a, hipStream_t stream) {
     const unsigned grid = static_cast<unsigned>(tiles < slots ? tiles : slots);
     a.xcds = grid % 8 == 0 ? 1 : 0;
     a.cus = static_cast<uint32_t>(hq::compute_units());
-    hipLaunchKernelGGL((int_gemm_kernel<TM, TN, WAVES_M, WAVES_N, KIND, OUT, KCH, NSTAGE, OCC, XB>),
+    hipLaunchKernelGGL((int_gemm_kernel<TM, TN, WAVES_M, WAVES_N, KIND, OUT, KCH, NSTAGE, OCC, XB, S2>),
                        dim3(grid), dim3(64 * WAVES_M * WAVES_N), 0, stream, a);
     return hq::launch_status();
 }
@@ -765,9 +798,30 @@ hq_status launch_tile(GemmArgs a, hipStream_t stream) {
 // taps = 9: per-tap sums, or one sum if the activation scale is static; taps = 3: digit planes), the three output
 // types, and K chunks of 192 codes (96 contiguous bytes per row) or, if WITH_64 is set, the
 // 64-code fallback for channel counts that are not a multiple of 192.
-template <int TM, int TN, int WAVES_M, int WAVES_N, int OCC, bool WITH_64, int NSTAGE_WIDE = 2>
+// WITH_S2: this configuration also carries the stride-2 forms of the two 3x3 kinds (4-bit codes).
+template <int TM, int TN, int WAVES_M, int WAVES_N, int OCC, bool WITH_64, int NSTAGE_WIDE = 2, bool WITH_S2 = false>
 hq_status launch_config(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream_t stream) {
     const bool wide = (a.bits == 8 ? a.k : a.k / 2) % 96 == 0;   // whole chunks of six 16-byte pieces per row
+    if (a.stride == 2) {
+        if constexpr (WITH_S2) {
+            if (taps != 9 || a.bits != 4) return HQ_ERR_UNSUPPORTED;
+#define HQ_GEMM_CASE_S2(KIND, OUT)                                                                       \
+    if (wide) return launch_tile<TM, TN, WAVES_M, WAVES_N, KIND, OUT, 6, NSTAGE_WIDE, OCC, 4, true>(a, stream); \
+    return launch_tile<TM, TN, WAVES_M, WAVES_N, KIND, OUT, 2, 4, OCC, 4, true>(a, stream);
+            if (a.sx_static) {
+                if (y_dtype == HQ_F16) { HQ_GEMM_CASE_S2(kConvSum, kOutF16) }
+                if (y_dtype == HQ_F32) { HQ_GEMM_CASE_S2(kConvSum, kOutF32) }
+                if (y_dtype == HQ_I32) { HQ_GEMM_CASE_S2(kConvSum, kOutI32) }
+            } else {
+                if (y_dtype == HQ_F16) { HQ_GEMM_CASE_S2(kConvPerTap, kOutF16) }
+                if (y_dtype == HQ_F32) { HQ_GEMM_CASE_S2(kConvPerTap, kOutF32) }
+                if (y_dtype == HQ_I32) { HQ_GEMM_CASE_S2(kConvPerTap, kOutI32) }
+            }
+#undef HQ_GEMM_CASE_S2
+            return HQ_ERR_DTYPE;
+        }
+        return HQ_ERR_UNSUPPORTED;
+    }
     if (!wide && !WITH_64) return HQ_ERR_UNSUPPORTED;
     if (a.bits == 8) {   // int8 codes: linear layers and 3x3 convolutions with per-pixel scales
 #define HQ_GEMM_CASE8(KIND, OUT)                                                                           \

@@ -88,7 +88,9 @@ def test_conv_argument_errors(lib):
     assert f(*args(xq=None)) == NULL
     assert f(*args(h=0)) == SHAPE
     assert f(*args(cin=96)) == SHAPE
-    assert f(*args(stride=2)) == UNSUPPORTED
+    assert f(*args(stride=3)) == UNSUPPORTED
+    assert f(*args(stride=2, pad=0)) == UNSUPPORTED          # stride 2 is built for 3x3, pad 1 only
+    assert f(*args(stride=2, r=1, s=1, pad=0)) == UNSUPPORTED
     assert f(*args(pad=0)) == UNSUPPORTED
     assert f(*args(r=5, s=5, pad=2)) == UNSUPPORTED
     assert f(*args(r=3, s=1)) == UNSUPPORTED
@@ -112,7 +114,8 @@ def test_static_scale_argument_errors(lib):
         ("cin", 64), ("cout", 8), ("r", 3), ("s", 3), ("stride", 1), ("pad", 1), ("y", P),
         ("dt", 0), ("stream", None)]]
     assert conv(*args(sx=None)) == NULL
-    assert conv(*args(stride=2)) == UNSUPPORTED
+    assert conv(*args(stride=3)) == UNSUPPORTED
+    assert conv(*args(stride=2, pad=0)) == UNSUPPORTED
     assert conv(*args(cin=14592)) == SHAPE      # 9 * 14592 codes in one sum: 256 * acc would overflow
     assert conv(*args(cin=96)) == SHAPE
 

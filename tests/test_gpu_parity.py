@@ -595,6 +595,56 @@ def test_activation_resident_conv_odd_geometry(hq, nb, h, w, cin, cout):
     check_y("y (static)", y_g, y_o, rtol=1e-5)
 
 
+@pytest.mark.parametrize("nb,h,w,cin,cout", [(1, 1, 1, 64, 8), (1, 2, 2, 64, 8), (2, 5, 7, 64, 16), (1, 8, 8, 128, 32),
+                                             (3, 9, 6, 192, 24), (2, 16, 16, 192, 70), (1, 33, 31, 64, 130),
+                                             (5, 12, 20, 384, 64)])
+def test_int_conv_stride_2(hq, nb, h, w, cin, cout):
+    """The downsampling convolution (3x3, stride 2, pad 1): odd and even image sizes (the last
+    window row / column hangs over the edge for even sizes), one-pixel images, tiles spanning
+    images, channel counts with 64- and 192-code chunks; per-tap int32 sums and the sum over all
+    taps bit for bit, fp32 outputs of both scale modes."""
+    rng = np.random.default_rng(nb * 1000 + h * 100 + w * 10 + cin + cout)
+    xq = rng.integers(-8, 8, (nb, h, w, cin)).astype(np.int8)
+    wq = rng.integers(-8, 8, (cout, 3, 3, cin)).astype(np.int8)
+    sx = rng.uniform(0.01, 1.0, (nb, h, w)).astype(np.float32)
+    sw = rng.uniform(0.001, 0.1, cout).astype(np.float32)
+    bias = rng.standard_normal(cout).astype(np.float32)
+    xq_d, wq_d = dev(pack_codes(xq)), dev(pack_codes(wq.reshape(cout, 9, cin)))
+    acc_o, y_o = oracle.int_conv2d(xq, sx, wq, sw, bias, stride=2, pad=1)
+    assert acc_o.shape[1:3] == ((h - 1) // 2 + 1, (w - 1) // 2 + 1)
+    acc_g = host(hq.hq_int_conv2d(xq_d, None, wq_d, None, None, ksize=3, stride=2, y_dtype=torch.int32))
+    assert acc_g.shape == acc_o.shape and np.array_equal(acc_g, acc_o)
+    y_g = host(hq.hq_int_conv2d(xq_d, dev(sx), wq_d, dev(sw), dev(bias), ksize=3, stride=2, y_dtype=torch.float32))
+    check_y("y", y_g, y_o, rtol=1e-5)
+    s1 = torch.tensor([0.37], dtype=torch.float32, device="cuda")
+    acc_o, y_o = oracle.int_conv2d_static(xq, 0.37, wq, sw, bias, stride=2, pad=1)
+    acc_g = host(hq.hq_int_conv2d_static(xq_d, None, wq_d, None, None, ksize=3, stride=2, y_dtype=torch.int32))
+    assert np.array_equal(acc_g, acc_o)
+    y_g = host(hq.hq_int_conv2d_static(xq_d, s1, wq_d, dev(sw), dev(bias), ksize=3, stride=2, y_dtype=torch.float32))
+    check_y("y (static)", y_g, y_o, rtol=1e-5)
+
+
+@pytest.mark.parametrize("hw,c", [(64, 192), (32, 384), (16, 576)])
+def test_stride_2_downsampling_layers_full_size(hq, hw, c):
+    """The three downsampling convolutions of an LDM-4-shaped UNet at batch 16, fp16 output with
+    per-pixel scales, every output against the oracle; per-tap int32 sums on the first two images."""
+    rng = np.random.default_rng(hw + c)
+    nb = 16
+    xq = rng.integers(-8, 8, (nb, hw, hw, c)).astype(np.int8)
+    wq = rng.integers(-8, 8, (c, 3, 3, c)).astype(np.int8)
+    sx = rng.uniform(0.01, 1.0, (nb, hw, hw)).astype(np.float32)
+    sw = rng.uniform(0.001, 0.1, c).astype(np.float32)
+    bias = rng.standard_normal(c).astype(np.float16)
+    xq_d, wq_d = dev(pack_codes(xq)), dev(pack_codes(wq.reshape(c, 9, c)))
+    _, y_o = oracle.int_conv2d(xq, sx, wq, sw, bias, stride=2, pad=1, want_acc=False)
+    y_g = host(hq.hq_int_conv2d(xq_d, dev(sx), wq_d, dev(sw), dev(bias), ksize=3, stride=2, y_dtype=torch.float16))
+    check_y("y", y_g, y_o)
+    acc_o, _ = oracle.int_conv2d(xq[:2], sx[:2], wq, sw, None, stride=2, pad=1, want_y=False)
+    acc_g = host(hq.hq_int_conv2d(xq_d[:2].contiguous(), None, wq_d, None, None, ksize=3, stride=2,
+                                  y_dtype=torch.int32))
+    assert np.array_equal(acc_g, acc_o)
+
+
 def _random_bytes(shape, seed):
     g = torch.Generator(device="cuda")
     g.manual_seed(seed)
