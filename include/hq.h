@@ -26,6 +26,10 @@
  *     2^{-k/2} into the scales in the same way).
  *   - Rounding is round-half-to-even.  Non-finite inputs are undefined.
  *   - The library is stateless and may be called from several host threads.
+ *   - Size limit of the integer stage: the packed operands are addressed with
+ *     32-bit byte offsets.  (rows + image width + 2) * bytes per activation row
+ *     and n * taps * bytes per weight row must stay below 2^32 (4 GiB of codes
+ *     per operand); a larger call returns HQ_ERR_UNSUPPORTED and launches nothing.
  */
 #ifndef HQ_H
 #define HQ_H
@@ -43,7 +47,7 @@ typedef enum {
     HQ_ERR_DTYPE = 3,       /* dtype enum not valid for this argument */
     HQ_ERR_BITS = 4,        /* unsupported bit width */
     HQ_ERR_ALIGN = 5,       /* pointer not 16-byte aligned */
-    HQ_ERR_UNSUPPORTED = 6, /* valid in principle, not built (e.g. stride != 1) */
+    HQ_ERR_UNSUPPORTED = 6, /* valid in principle, not built (e.g. stride 3, a 5x5 window) or beyond the size limit below */
     HQ_ERR_LAUNCH = 7       /* the HIP runtime refused the launch */
 } hq_status;
 
@@ -118,18 +122,17 @@ hq_status hq_int_linear(const uint8_t *xq, const float *x_scale, const uint8_t *
  * integer sum is kept per kernel tap t = (r, s) and the taps are combined in
  * fp32, in the order t = 0 .. R*S-1:
  *
- *   acc_t[b, p, q, co] = sum_ci xq[b, p + r - pad, q + s - pad, ci] * wq[co, r, s, ci]
- *   y[b, p, q, co]     = w_scale[co] * sum_t x_scale[b, p + r - pad, q + s - pad] * acc_t
+ *   acc_t[b, p, q, co] = sum_ci xq[b, stride p + r - pad, stride q + s - pad, ci] * wq[co, r, s, ci]
+ *   y[b, p, q, co]     = w_scale[co] * sum_t x_scale[b, stride p + r - pad, stride q + s - pad] * acc_t
  *                        + bias[co]
  *
  *   A tap outside the image contributes 0.
  *   xq [nb, h, w, c_in/2], x_scale [nb, h, w], wq [c_out, R, S, c_in/2],
- *   w_scale [c_out], bias [c_out] of y_dtype or NULL, y [nb, h, w, c_out].
- *   Built: R = S in {1, 3}, stride 1, pad (R-1)/2 (same-size output), and the
- *   downsampling form R = S = 3, stride 2, pad 1, where output pixel (p, q) reads
- *   input rows 2p + r - 1 and columns 2q + s - 1 and y is
- *   [nb, (h-1)/2 + 1, (w-1)/2 + 1, c_out]; anything else returns
- *   HQ_ERR_UNSUPPORTED.  c_in a multiple of 64.
+ *   w_scale [c_out], bias [c_out] of y_dtype or NULL, y [nb, h_out, w_out, c_out].
+ *   Built: R = S in {1, 3}, stride 1, pad (R-1)/2 (h_out = h, w_out = w), and the
+ *   downsampling form R = S = 3, stride 2, pad 1 (h_out = (h-1)/2 + 1,
+ *   w_out = (w-1)/2 + 1); anything else returns HQ_ERR_UNSUPPORTED.
+ *   c_in a multiple of 64.
  *   y_dtype == HQ_I32 writes the per-tap accumulators [nb, h_out, w_out, R*S, c_out].
  */
 hq_status hq_int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
@@ -174,8 +177,8 @@ hq_status hq_int_linear_static(const uint8_t *xq, const float *x_scale, const ui
  *   y[b, p, q, co]   = acc * x_scale[0] * w_scale[co] + bias[co]
  *
  * A tap outside the image contributes 0.  Shapes and the built geometries are
- * those of hq_int_conv2d; c_in * R * S < 131072.  y_dtype == HQ_I32 writes acc,
- * [nb, h, w, c_out].
+ * those of hq_int_conv2d (p, q and the output size follow the stride in the same
+ * way); c_in * R * S < 131072.  y_dtype == HQ_I32 writes acc, [nb, h_out, w_out, c_out].
  */
 hq_status hq_int_conv2d_static(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
                                const float *w_scale, const void *bias, int nb, int h, int w,
@@ -278,8 +281,9 @@ hq_status hq_int_conv2d_width(const uint8_t *xu3, const float *x_scale, const ui
  * hq_quantize_weights with a_bits = w_bits = 8 write one int8 code per byte (xq [m, k],
  * wq [n_out, taps, k_in]); the two calls below take such codes.  The codes feed the int8
  * matrix instruction as they are.  Everything else (scales, per-tap sums of a convolution,
- * bias, HQ_I32 outputs, built geometries, error behaviour) is as in hq_int_linear /
- * hq_int_conv2d; k (c_in) a multiple of 64.
+ * bias, HQ_I32 outputs, error behaviour) is as in hq_int_linear / hq_int_conv2d; the
+ * convolution is built for stride 1 only (R = S in {1, 3}, pad (R-1)/2); k (c_in) a
+ * multiple of 64.
  */
 /*
  * Mixed widths (the paper also reports W8A4): the activation path of hq_act_hadamard_quant with
