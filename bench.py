@@ -352,7 +352,7 @@ def main():
         "int_stage_tops_kernel_time": round(int_all_tops, 1),
         "frac_int8_mfma_peak_kernel_time": round(int_all_tops / INT8_MFMA_PEAK_TOPS, 4),
         "roofline": {
-            "kernel": "int_gemm_kernel (3x3 implicit-GEMM convolutions of the sweep)",
+            "kernel": "the four 3x3 implicit-GEMM convolution launches of the sweep (conv3x3_halo_kernel, int_gemm_kernel twice, conv3x3_wave_kernel)",
             "bound": "mfma", "achieved": round(achieved, 1), "peak": round(INT8_MFMA_PEAK_TOPS, 1),
             "unit": "TOP/s", "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4),
             "traffic": measured_traffic(),
