@@ -326,6 +326,37 @@ def main():
         return e0.elapsed_time(e1) * 1e3 / reps
 
     hq_us_hbm = time_quant(xs, 8 * nrot)
+    # context: a plain device copy moving the same number of bytes per launch (half read, half written)
+    # through the same rotation of buffers
+    half = q_bytes // 4    # fp16 elements: q_bytes / 2 bytes each way
+    cp_dst = [torch.empty(half, dtype=torch.float16, device="cuda") for _ in range(nrot)]
+
+    def time_copy(reps):
+        def launches():
+            for r in range(reps):
+                j = r % nrot
+                cp_dst[j].copy_(xs[j].view(-1)[:half])
+        launches()
+        torch.cuda.synchronize()
+        g = None
+        if not args.eager:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                launches()
+            g.replay()
+            torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        if g is not None:
+            g.replay()
+        else:
+            launches()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+
+    copy_us = time_copy(8 * nrot)
+    del cp_dst
     hq_us_cached = time_quant(xs[:1], 64)
     # the same kernel on 8 x the batch (two tensors in rotation): the launch and its ramp no longer dominate
     xl = [torch.cat(xs[:8]), torch.cat(xs[8:])]
@@ -367,6 +398,9 @@ def main():
             "us_cache_resident": round(hq_us_cached, 2),
             "gbs_cache_resident": round(q_bytes / hq_us_cached / 1e3, 1),
             "rotating_buffers": nrot, "peak_gbs": HBM_PEAK_GBS,
+            "device_copy_same_bytes": {"what": "torch copy_ of %d bytes (as many read + written as the kernel "
+                                               "moves), same rotation" % (2 * half),
+                                       "us_hbm": round(copy_us, 2), "gbs_hbm": round(4 * half / copy_us / 1e3, 1)},
             "batch_x8": {"bytes_per_launch": 8 * q_bytes, "us_hbm": round(hq_us_large, 2),
                          "gbs_hbm": round(8 * q_bytes / hq_us_large / 1e3, 1),
                          "frac_hbm_peak": round(8 * q_bytes / hq_us_large / 1e3 / HBM_PEAK_GBS, 4)},
