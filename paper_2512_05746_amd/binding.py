@@ -90,6 +90,40 @@ def _dev(t: torch.Tensor, name: str) -> torch.Tensor:
     return t
 
 
+def _conv_out(h: int, w: int, ksize: int, stride: int, pad: int):
+    if stride < 1 or pad < 0 or ksize < 1:
+        raise ValueError("bad convolution geometry")
+    return (h + 2 * pad - ksize) // stride + 1, (w + 2 * pad - ksize) // stride + 1
+
+
+def _out(out: Optional[torch.Tensor], shape, dtype: torch.dtype, device) -> torch.Tensor:
+    """A caller's output buffer (must hold exactly the result) or a new one."""
+    if out is None:
+        return torch.empty(shape, dtype=dtype, device=device)
+    n = 1
+    for d in shape:
+        n *= d
+    if not out.is_cuda or out.dtype != dtype or out.numel() != n or not out.is_contiguous():
+        raise ValueError("out must be a contiguous device tensor of %s with %d elements" % (dtype, n))
+    return out
+
+
+def _vec(t: Optional[torch.Tensor], n: int, dtype: torch.dtype, name: str) -> Optional[torch.Tensor]:
+    """An optional per-row / per-channel device vector: exactly n elements of dtype."""
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous() or t.dtype != dtype or t.numel() != n:
+        raise ValueError("%s must be a contiguous device tensor of %s with %d elements" % (name, dtype, n))
+    return t
+
+
+def _codes(t: torch.Tensor, dtype: torch.dtype, name: str) -> torch.Tensor:
+    _dev(t, name)
+    if t.dtype != dtype:
+        raise ValueError("%s must hold %s codes" % (name, dtype))
+    return t
+
+
 def hq_quantize_weights(w: torch.Tensor, had_block: int = 64, w_bits: int = 4
                         ) -> Tuple[torch.Tensor, torch.Tensor]:
     """w [n_out, taps, k_in] fp16/fp32 -> (wq uint8 [n_out, taps, k_in/2], w_scale fp32 [n_out]);
@@ -120,7 +154,9 @@ def hq_act_hadamard_quant(x: torch.Tensor, had_block: int = 64, a_bits: int = 4,
             xq = torch.empty(x.shape[:-1] + (k // 2,), dtype=torch.uint8, device=x.device)
         xs = torch.empty(x.shape[:-1], dtype=torch.float32, device=x.device)
     else:
-        xq, xs = out
+        xq = _out(out[0], x.shape[:-1] + ((k,) if a_bits == 8 else (k // 2,)),
+                  torch.int8 if a_bits == 8 else torch.uint8, x.device)
+        xs = _out(out[1], x.shape[:-1], torch.float32, x.device)
     _check("hq_act_hadamard_quant", load_library().hq_act_hadamard_quant(
         _ptr(x), _DTYPES[x.dtype], m, k, had_block, a_bits, _ptr(xq), _ptr(xs), _stream()))
     return xq, xs
@@ -131,36 +167,18 @@ def hq_int_linear(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torch.T
                   y_dtype: torch.dtype = torch.float16, out: Optional[torch.Tensor] = None
                   ) -> torch.Tensor:
     """xq [m, k/2], wq [n, k/2] (or [n, 1, k/2]) -> y [m, n]; y_dtype int32 returns the raw sums."""
-    _dev(xq, "xq"), _dev(wq, "wq")
+    _codes(xq, torch.uint8, "xq"), _codes(wq, torch.uint8, "wq")
     m, kb = xq.shape
     n = wq.shape[0]
     if wq.numel() != n * kb:
         raise ValueError("wq does not match xq in k")
-    if bias is not None and bias.dtype != y_dtype:
-        raise ValueError("bias must have the output dtype")
-    y = out if out is not None else torch.empty((m, n), dtype=y_dtype, device=xq.device)
+    _vec(x_scale, m, torch.float32, "x_scale"), _vec(w_scale, n, torch.float32, "w_scale")
+    _vec(bias, n, y_dtype, "bias")
+    y = _out(out, (m, n), y_dtype, xq.device)
     _check("hq_int_linear", load_library().hq_int_linear(
         _ptr(xq), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), m, n, kb * 2,
         _ptr(y), _DTYPES[y_dtype], _stream()))
     return y
-
-
-def _conv_out(h: int, w: int, ksize: int, stride: int, pad: int):
-    if stride < 1 or pad < 0 or ksize < 1:
-        raise ValueError("bad convolution geometry")
-    return (h + 2 * pad - ksize) // stride + 1, (w + 2 * pad - ksize) // stride + 1
-
-
-def _out(out: Optional[torch.Tensor], shape, dtype: torch.dtype, device) -> torch.Tensor:
-    """A caller's output buffer (must hold exactly the result) or a new one."""
-    if out is None:
-        return torch.empty(shape, dtype=dtype, device=device)
-    n = 1
-    for d in shape:
-        n *= d
-    if not out.is_cuda or out.dtype != dtype or out.numel() != n or not out.is_contiguous():
-        raise ValueError("out must be a contiguous device tensor of %s with %d elements" % (dtype, n))
-    return out
 
 
 def hq_int_conv2d(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torch.Tensor,
@@ -171,13 +189,13 @@ def hq_int_conv2d(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torch.T
     """xq [nb, h, w, cin/2], wq [cout, ksize*ksize, cin/2] -> y [nb, ho, wo, cout] (same size for
     stride 1; ksize 3, stride 2, pad 1 halves it, rounding up); y_dtype int32 returns the per-tap
     sums [nb, ho, wo, ksize*ksize, cout]."""
-    _dev(xq, "xq"), _dev(wq, "wq")
+    _codes(xq, torch.uint8, "xq"), _codes(wq, torch.uint8, "wq")
     nb, h, w, cb = xq.shape
     cout = wq.shape[0]
     if wq.numel() != cout * ksize * ksize * cb:
         raise ValueError("wq does not match xq / ksize")
-    if bias is not None and bias.dtype != y_dtype:
-        raise ValueError("bias must have the output dtype")
+    _vec(x_scale, nb * h * w, torch.float32, "x_scale"), _vec(w_scale, cout, torch.float32, "w_scale")
+    _vec(bias, cout, y_dtype, "bias")
     pad = (ksize - 1) // 2 if pad is None else pad
     ho, wo = _conv_out(h, w, ksize, stride, pad)
     if y_dtype == torch.int32:
@@ -202,7 +220,7 @@ def hq_act_hadamard_quant_static(x: torch.Tensor, x_scale: torch.Tensor, had_blo
     _dev(x, "x")
     k = x.shape[-1]
     m = x.numel() // k
-    xq = out if out is not None else torch.empty(x.shape[:-1] + (k // 2,), dtype=torch.uint8, device=x.device)
+    xq = _out(out, x.shape[:-1] + (k // 2,), torch.uint8, x.device)
     _check("hq_act_hadamard_quant_static", load_library().hq_act_hadamard_quant_static(
         _ptr(x), _DTYPES[x.dtype], m, k, had_block, a_bits, _ptr(_scalar(x_scale)), _ptr(xq), _stream()))
     return xq
@@ -213,14 +231,14 @@ def hq_int_linear_static(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: 
                          y_dtype: torch.dtype = torch.float16, out: Optional[torch.Tensor] = None
                          ) -> torch.Tensor:
     """As hq_int_linear with one activation scale (a device tensor holding one float32)."""
-    _dev(xq, "xq"), _dev(wq, "wq")
+    _codes(xq, torch.uint8, "xq"), _codes(wq, torch.uint8, "wq")
     m, kb = xq.shape
     n = wq.shape[0]
     if wq.numel() != n * kb:
         raise ValueError("wq does not match xq in k")
-    if bias is not None and bias.dtype != y_dtype:
-        raise ValueError("bias must have the output dtype")
-    y = out if out is not None else torch.empty((m, n), dtype=y_dtype, device=xq.device)
+    _vec(x_scale, 1, torch.float32, "x_scale"), _vec(w_scale, n, torch.float32, "w_scale")
+    _vec(bias, n, y_dtype, "bias")
+    y = _out(out, (m, n), y_dtype, xq.device)
     _check("hq_int_linear_static", load_library().hq_int_linear_static(
         _ptr(xq), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), m, n, kb * 2,
         _ptr(y), _DTYPES[y_dtype], _stream()))
@@ -234,13 +252,13 @@ def hq_int_conv2d_static(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: 
                          ) -> torch.Tensor:
     """As hq_int_conv2d with one activation scale; y_dtype int32 returns the sums over all
     taps and input channels, [nb, h, w, cout]."""
-    _dev(xq, "xq"), _dev(wq, "wq")
+    _codes(xq, torch.uint8, "xq"), _codes(wq, torch.uint8, "wq")
     nb, h, w, cb = xq.shape
     cout = wq.shape[0]
     if wq.numel() != cout * ksize * ksize * cb:
         raise ValueError("wq does not match xq / ksize")
-    if bias is not None and bias.dtype != y_dtype:
-        raise ValueError("bias must have the output dtype")
+    _vec(x_scale, 1, torch.float32, "x_scale"), _vec(w_scale, cout, torch.float32, "w_scale")
+    _vec(bias, cout, y_dtype, "bias")
     pad = (ksize - 1) // 2 if pad is None else pad
     ho, wo = _conv_out(h, w, ksize, stride, pad)
     y = _out(out, (nb, ho, wo, cout), y_dtype, xq.device)
@@ -271,15 +289,15 @@ def hq_int_linear_single(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq3:
                          had_block: int = 64, y_dtype: torch.dtype = torch.float16,
                          out: Optional[torch.Tensor] = None) -> torch.Tensor:
     """xq [m, k/2], wq3 [n, 3, k/2] -> y [m, n]; y_dtype int32 returns the three sums [m, 3, n]."""
-    _dev(xq, "xq"), _dev(wq3, "wq3")
+    _codes(xq, torch.uint8, "xq"), _codes(wq3, torch.uint8, "wq3")
     m, kb = xq.shape
     n = wq3.shape[0]
     if wq3.numel() != n * 3 * kb:
         raise ValueError("wq3 does not match xq in k")
-    if bias is not None and bias.dtype != y_dtype:
-        raise ValueError("bias must have the output dtype")
+    _vec(x_scale, m, torch.float32, "x_scale"), _vec(w_scale, n, torch.float32, "w_scale")
+    _vec(bias, n, y_dtype, "bias")
     shape = (m, 3, n) if y_dtype == torch.int32 else (m, n)
-    y = out if out is not None else torch.empty(shape, dtype=y_dtype, device=xq.device)
+    y = _out(out, shape, y_dtype, xq.device)
     _check("hq_int_linear_single", load_library().hq_int_linear_single(
         _ptr(xq), _ptr(x_scale), _ptr(wq3), _ptr(w_scale), _ptr(bias), m, n, kb * 2, had_block,
         _ptr(y), _DTYPES[y_dtype], _stream()))
@@ -297,7 +315,7 @@ def hq_act_hadamard_quant_width(x: torch.Tensor, x_scale: torch.Tensor, had_bloc
     if x.dim() != 4:
         raise ValueError("x must be [N, H, W, C]")
     nb, h, w, c = x.shape
-    xu3 = out if out is not None else torch.empty((3, nb, h, w, c // 2), dtype=torch.uint8, device=x.device)
+    xu3 = _out(out, (3, nb, h, w, c // 2), torch.uint8, x.device)
     _check("hq_act_hadamard_quant_width", load_library().hq_act_hadamard_quant_width(
         _ptr(x), _DTYPES[x.dtype], nb, h, w, c, had_block, a_bits, _ptr(x_scale), _ptr(xu3), _stream()))
     return xu3
@@ -309,16 +327,16 @@ def hq_int_conv2d_width(xu3: torch.Tensor, x_scale: Optional[torch.Tensor], wq: 
                         out: Optional[torch.Tensor] = None) -> torch.Tensor:
     """xu3 [3, N, H, W, Cin/2], wq [Cout, 9, Cin/2] (or [Cout, 3, 3, Cin/2]) -> y [N, H, W, Cout];
     y_dtype int32 returns the exact integer sums."""
-    _dev(xu3, "xu3"), _dev(wq, "wq")
+    _codes(xu3, torch.uint8, "xu3"), _codes(wq, torch.uint8, "wq")
     if xu3.dim() != 5 or xu3.shape[0] != 3:
         raise ValueError("xu3 must be [3, N, H, W, Cin/2]")
     _, nb, h, w, kb = xu3.shape
     c_out = wq.shape[0]
     if wq.numel() != c_out * 9 * kb:
         raise ValueError("wq does not match xu3 in Cin or is not a 3x3 kernel")
-    if bias is not None and bias.dtype != y_dtype:
-        raise ValueError("bias must have the output dtype")
-    y = out if out is not None else torch.empty((nb, h, w, c_out), dtype=y_dtype, device=xu3.device)
+    _vec(x_scale, 1, torch.float32, "x_scale"), _vec(w_scale, c_out, torch.float32, "w_scale")
+    _vec(bias, c_out, y_dtype, "bias")
+    y = _out(out, (nb, h, w, c_out), y_dtype, xu3.device)
     _check("hq_int_conv2d_width", load_library().hq_int_conv2d_width(
         _ptr(xu3), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), nb, h, w, kb * 2, c_out, 3, 3, 1, 1,
         had_block, _ptr(y), _DTYPES[y_dtype], _stream()))
@@ -344,14 +362,14 @@ def hq_int_linear_i8(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torc
                      w_scale: Optional[torch.Tensor], bias: Optional[torch.Tensor] = None,
                      y_dtype: torch.dtype = torch.float16, out: Optional[torch.Tensor] = None) -> torch.Tensor:
     """xq int8 [m, k], wq int8 [n, k] (or [n, 1, k]) -> y [m, n]; y_dtype int32 returns the raw sums."""
-    _dev(xq, "xq"), _dev(wq, "wq")
+    _codes(xq, torch.int8, "xq"), _codes(wq, torch.int8, "wq")
     m, k = xq.shape
     n = wq.shape[0]
     if wq.numel() != n * k:
         raise ValueError("wq does not match xq in k")
-    if bias is not None and bias.dtype != y_dtype:
-        raise ValueError("bias must have the output dtype")
-    y = out if out is not None else torch.empty((m, n), dtype=y_dtype, device=xq.device)
+    _vec(x_scale, m, torch.float32, "x_scale"), _vec(w_scale, n, torch.float32, "w_scale")
+    _vec(bias, n, y_dtype, "bias")
+    y = _out(out, (m, n), y_dtype, xq.device)
     _check("hq_int_linear_i8", load_library().hq_int_linear_i8(
         _ptr(xq), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), m, n, k, _ptr(y), _DTYPES[y_dtype], _stream()))
     return y
@@ -363,16 +381,16 @@ def hq_int_conv2d_i8(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torc
                      out: Optional[torch.Tensor] = None) -> torch.Tensor:
     """xq int8 [N, H, W, Cin], wq int8 [Cout, ksize*ksize, Cin] -> y [N, H, W, Cout] (stride 1, same
     size); y_dtype int32 returns the per-tap sums [N, H, W, ksize*ksize, Cout]."""
-    _dev(xq, "xq"), _dev(wq, "wq")
+    _codes(xq, torch.int8, "xq"), _codes(wq, torch.int8, "wq")
     nb, h, w, c_in = xq.shape
     c_out = wq.shape[0]
     taps = ksize * ksize
     if wq.numel() != c_out * taps * c_in:
         raise ValueError("wq does not match xq in Cin or the kernel size")
-    if bias is not None and bias.dtype != y_dtype:
-        raise ValueError("bias must have the output dtype")
+    _vec(x_scale, nb * h * w, torch.float32, "x_scale"), _vec(w_scale, c_out, torch.float32, "w_scale")
+    _vec(bias, c_out, y_dtype, "bias")
     shape = (nb, h, w, taps, c_out) if (y_dtype == torch.int32 and taps > 1) else (nb, h, w, c_out)
-    y = out if out is not None else torch.empty(shape, dtype=y_dtype, device=xq.device)
+    y = _out(out, shape, y_dtype, xq.device)
     _check("hq_int_conv2d_i8", load_library().hq_int_conv2d_i8(
         _ptr(xq), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), nb, h, w, c_in, c_out, ksize, ksize, 1,
         (ksize - 1) // 2, _ptr(y), _DTYPES[y_dtype], _stream()))

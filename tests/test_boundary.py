@@ -185,3 +185,18 @@ def test_product_does_not_import_the_oracle():
             if fn.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, fn)).read()
                 assert "oracle" not in text, os.path.join(dirpath, fn)
+
+
+def test_binding_rejects_host_tensors_before_any_call():
+    """The Python face takes device tensors only; a host tensor is refused by the binding itself,
+    before the library is asked anything (so this needs no GPU)."""
+    import torch
+    import paper_2512_05746_amd as hq
+    codes = torch.zeros((4, 32), dtype=torch.uint8)
+    with pytest.raises(ValueError):
+        hq.hq_int_linear(codes, None, codes, None, None, y_dtype=torch.int32)
+    with pytest.raises(ValueError):
+        hq.hq_act_hadamard_quant(torch.zeros((4, 64), dtype=torch.float16), 64, 4)
+    with pytest.raises(ValueError):
+        hq.hq_int_conv2d(torch.zeros((1, 2, 2, 32), dtype=torch.uint8), None, torch.zeros((8, 9, 32), dtype=torch.uint8),
+                         None, None, ksize=3, y_dtype=torch.int32)

@@ -787,6 +787,39 @@ def test_errors_raise(hq):
         hq.hq_act_hadamard_quant(x[:, :64].contiguous(), 64, 5)
 
 
+def test_binding_refuses_buffers_of_the_wrong_size(hq):
+    """Output buffers, scales and bias handed to the binding must have exactly the size the call
+    writes or reads, and codes the dtype of their format; anything else is refused before the
+    library is called."""
+    xq = torch.zeros((8, 32), dtype=torch.uint8, device="cuda")
+    wq = torch.zeros((16, 32), dtype=torch.uint8, device="cuda")
+    sx = torch.ones(8, device="cuda")
+    sw = torch.ones(16, device="cuda")
+    ok = hq.hq_int_linear(xq, sx, wq, sw, None, y_dtype=torch.float16)
+    assert ok.shape == (8, 16)
+    bad = [
+        lambda: hq.hq_int_linear(xq, sx, wq, sw, None, y_dtype=torch.float16, out=torch.empty((8, 15), dtype=torch.float16, device="cuda")),
+        lambda: hq.hq_int_linear(xq, sx, wq, sw, None, y_dtype=torch.float16, out=torch.empty((8, 16), dtype=torch.float32, device="cuda")),
+        lambda: hq.hq_int_linear(xq, sx[:7], wq, sw, None, y_dtype=torch.float16),
+        lambda: hq.hq_int_linear(xq, sx, wq, sw[:15], None, y_dtype=torch.float16),
+        lambda: hq.hq_int_linear(xq, sx, wq, sw, torch.zeros(15, dtype=torch.float16, device="cuda"), y_dtype=torch.float16),
+        lambda: hq.hq_int_linear(xq, sx, wq, sw, torch.zeros(16, dtype=torch.float32, device="cuda"), y_dtype=torch.float16),
+        lambda: hq.hq_int_linear(xq.view(torch.int8), sx, wq, sw, None, y_dtype=torch.float16),
+        lambda: hq.hq_int_linear_i8(xq, sx, wq, sw, None, y_dtype=torch.float16),
+        lambda: hq.hq_int_linear_static(xq, sx, wq, sw, None, y_dtype=torch.float16),      # the scale must be ONE value
+        lambda: hq.hq_int_conv2d(xq.view(1, 2, 4, 32), sx, wq.new_zeros((16, 9, 32)), sw, None, ksize=3,
+                                 out=torch.empty((1, 2, 4, 15), dtype=torch.float16, device="cuda")),
+        lambda: hq.hq_act_hadamard_quant(torch.zeros((8, 64), dtype=torch.float16, device="cuda"), 64, 4,
+                                         out=(xq, torch.empty(7, device="cuda"))),
+        lambda: hq.hq_act_hadamard_quant_static(torch.zeros((8, 64), dtype=torch.float16, device="cuda"),
+                                                torch.ones(1, device="cuda"), 64, 4, out=xq[:7]),
+    ]
+    for i, call in enumerate(bad):
+        with pytest.raises(ValueError):
+            call()
+            pytest.fail("case %d was accepted" % i)
+
+
 def test_hip_graph_replay_matches_eager(hq):
     """The whole layer captured into a HIP graph: every replay (with eager work and
     synchronisations in between) must reproduce the eager result bit for bit."""
