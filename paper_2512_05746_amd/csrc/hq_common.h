@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "hq.h"
 
 namespace hq {
@@ -19,15 +21,15 @@ inline int ilog2(int v) {
 
 // Compute units of the current device (queried once per device; 256 on MI355X).
 inline int compute_units() {
-    static int cached[64] = {0};
+    static std::atomic<int> cached[64];   // zero-initialised; host threads may race to fill an entry with the same value
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cached[dev] = n;
+        cached[dev].store(n, std::memory_order_relaxed);
     }
-    return cached[dev];
+    return n;
 }
 
 // Exact division of n < 2^31 by a run-time constant d >= 2: n / d == umulhi(n, m) >> s.
