@@ -26,6 +26,9 @@
  *     2^{-k/2} into the scales in the same way).
  *   - Rounding is round-half-to-even.  Non-finite inputs are undefined.
  *   - The library is stateless and may be called from several host threads.
+ *   - HQ_ERR_LAUNCH reports a launch the HIP runtime refused.  The runtime's per-thread
+ *     "last error" is sampled before a call launches anything: an error that the caller's own
+ *     earlier HIP calls left pending there is neither reported as the library's nor cleared.
  *   - Size limit of the integer stage: the packed operands are addressed with
  *     32-bit byte offsets.  (rows + image width + 2) * bytes per activation row
  *     and n * taps * bytes per weight row must stay below 2^32 (4 GiB of codes
@@ -139,6 +142,17 @@ hq_status hq_int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *
                         const float *w_scale, const void *bias, int nb, int h, int w,
                         int c_in, int c_out, int r, int s, int stride, int pad,
                         void *y, hq_dtype y_dtype, void *stream);
+
+/*
+ * Diagnostic: the kernel family that hq_int_conv2d (static_scale = 0) or hq_int_conv2d_static
+ * (static_scale = 1) runs for a convolution of this geometry on the current device, for 4-bit
+ * (bits = 4) or 8-bit (bits = 8, hq_int_conv2d_i8) codes.  The choice depends on the geometry
+ * only, never on y_dtype: the HQ_I32 outputs (raw integer sums) come from the same kernel as the
+ * floating-point outputs.  Host logic only; returns a static string: "tile", "tile (stride 2)",
+ * "wave-split", "activation-resident", or "unsupported".
+ */
+const char *hq_int_conv2d_kernel_name(int nb, int h, int w, int c_in, int c_out, int r, int s,
+                                      int stride, int pad, int static_scale, int bits);
 
 /*
  * ---- Static activation scale -------------------------------------------------

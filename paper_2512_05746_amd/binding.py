@@ -24,6 +24,8 @@ SYMBOLS = ("hq_status_string", "hq_quantize_weights", "hq_act_hadamard_quant",
            "hq_quantize_weights_single", "hq_int_linear_single",
            "hq_act_hadamard_quant_width", "hq_int_conv2d_width",
            "hq_int_linear_i8", "hq_int_conv2d_i8", "hq_act_hadamard_quant_i8")
+# entry points that do not return a status
+INFO_SYMBOLS = ("hq_int_conv2d_kernel_name",)
 
 
 class HqError(RuntimeError):
@@ -36,13 +38,15 @@ _lib = None
 
 
 def load_library(path: Optional[str] = None) -> ctypes.CDLL:
-    """Loads libhq.so, building it first only if no built library exists."""
+    """Loads libhq.so.  The in-tree library is built first if it is missing or older than one of
+    its sources (a child-process compile; nothing here touches the GPU before that)."""
     global _lib
     if _lib is not None and path is None:
         return _lib
-    path = path or _build.LIB
-    if not os.path.exists(path):
-        _build.build_lib()
+    if path is None:
+        path = _build.LIB
+        if _build.is_stale():
+            _build.build_lib()
     lib = ctypes.CDLL(path)
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
     lib.hq_status_string.argtypes = [i32]
@@ -63,8 +67,18 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.hq_int_conv2d_i8.argtypes = lib.hq_int_conv2d.argtypes
     for name in SYMBOLS[1:]:
         getattr(lib, name).restype = i32
+    lib.hq_int_conv2d_kernel_name.argtypes = [i32] * 11
+    lib.hq_int_conv2d_kernel_name.restype = ctypes.c_char_p
     _lib = lib
     return lib
+
+
+def hq_int_conv2d_kernel_name(nb: int, h: int, w: int, c_in: int, c_out: int, ksize: int = 3, stride: int = 1,
+                              pad: Optional[int] = None, static_scale: bool = False, bits: int = 4) -> str:
+    """Name of the kernel family the convolution calls run for this geometry (host logic only)."""
+    pad = (ksize - 1) // 2 if pad is None else pad
+    return load_library().hq_int_conv2d_kernel_name(nb, h, w, c_in, c_out, ksize, ksize, stride, pad,
+                                                    1 if static_scale else 0, bits).decode()
 
 
 def status_string(code: int) -> str:

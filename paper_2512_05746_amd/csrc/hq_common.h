@@ -59,9 +59,21 @@ __device__ __forceinline__ void digits16(int v, int (&d)[3]) {
     d[2] = (v - d[1]) >> 4;
 }
 
-// Maps the sticky launch error (if any) of the calling thread to a status.
-inline hq_status launch_status() {
-    return hipGetLastError() == hipSuccess ? HQ_OK : HQ_ERR_LAUNCH;
-}
+// Status of the launches made while an object of this class lives.  Kernel launches report
+// failures through the calling thread's "last error", which an earlier call of the caller may
+// already have set: the state is sampled BEFORE the launches, and an error that was pending then
+// is neither reported as the library's nor cleared (it stays for the caller to find).  Only when
+// the state was clean is a new error taken (and cleared) as the launch's own.
+class LaunchCheck {
+public:
+    LaunchCheck() : prior_(hipPeekAtLastError()) {}
+    hq_status status() const {
+        if (prior_ != hipSuccess) return hipPeekAtLastError() == prior_ ? HQ_OK : HQ_ERR_LAUNCH;
+        return hipGetLastError() == hipSuccess ? HQ_OK : HQ_ERR_LAUNCH;
+    }
+
+private:
+    hipError_t prior_;
+};
 
 }  // namespace hq

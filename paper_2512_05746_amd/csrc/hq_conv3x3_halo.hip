@@ -165,11 +165,14 @@ __global__ __launch_bounds__(256, KIND == kConvSum ? 3 : 2) void conv3x3_halo_ke
     const uint32_t lds_bias = lds_address(s_bias) + lhalf * 64;
 
     // integer accumulators start from the bits of 1.5 * 2^23 when their sums are folded per tap
+    // (integer output: from 0, the sums themselves are stored)
+    constexpr bool INT_OUT = OUT == kOutI32;
+    constexpr bool FOLD = PER_TAP && !INT_OUT;
     constexpr int kBiasBits = 0x4B400000;
     constexpr float kBias = 12582912.0f;
     v16i acc_start;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc_start[r] = PER_TAP ? kBiasBits : 0;
+    for (int r = 0; r < 16; ++r) acc_start[r] = FOLD ? kBiasBits : 0;
     if constexpr (PER_TAP) asm volatile("" : "+v"(acc_start));   // kept in registers, not rebuilt per tap
 
     if (my_tiles > 0) {   // loads of the first tile (the zero row above is not touched by them)
@@ -194,7 +197,9 @@ __global__ __launch_bounds__(256, KIND == kConvSum ? 3 : 2) void conv3x3_halo_ke
             my_mask = (oh > 0 ? cm : 0) | (cm << 3) | (oh + 1 < a.h ? cm << 6 : 0);
             if (pix >= a.pixels) my_mask = 0;
             s_mask[tid] = my_mask;
-            if constexpr (PER_TAP) {
+            if constexpr (INT_OUT) {
+                // no scales are read (the pointers may be null)
+            } else if constexpr (PER_TAP) {
                 float v[TAPS];
 #pragma unroll
                 for (int t = 0; t < TAPS; ++t) {
@@ -213,16 +218,18 @@ __global__ __launch_bounds__(256, KIND == kConvSum ? 3 : 2) void conv3x3_halo_ke
             } else {
                 s_sx[0][tid] = my_mask ? a.sx[0] * (1.0f / 256.0f) : 0.f;
             }
-            if (tid < BCO) {
-                const bool ok = co0 + tid < a.n;
-                const Out *bias = static_cast<const Out *>(a.bias);
-                s_sw[tid] = ok ? a.sw[co0 + tid] : 0.f;
-                s_bias[tid] = ok && bias ? to_float(bias[co0 + tid]) : 0.f;
+            if constexpr (!INT_OUT) {
+                if (tid < BCO) {
+                    const bool ok = co0 + tid < a.n;
+                    const Out *bias = static_cast<const Out *>(a.bias);
+                    s_sw[tid] = ok ? a.sw[co0 + tid] : 0.f;
+                    s_bias[tid] = ok && bias ? to_float(bias[co0 + tid]) : 0.f;
+                }
             }
         }
 
         v16i acc[TM][TN];
-        float facc[PER_TAP ? TM : 1][PER_TAP ? TN : 1][16];
+        float facc[FOLD ? TM : 1][FOLD ? TN : 1][16];
         auto multiply = [&](Ops &o, bool first) {
             v4i a0[TM], a1[TM], b0[TN], b1[TN];
 #pragma unroll
@@ -249,7 +256,7 @@ __global__ __launch_bounds__(256, KIND == kConvSum ? 3 : 2) void conv3x3_halo_ke
                     acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[tm], b1[tn], acc[tm][tn], 0, 0, 0);
         };
 
-        int pix_mask[TN];   // masks of this lane's pixels, local index wave * 64 + tn * 32 + lrow (one sum only)
+        int pix_mask[TN];   // masks of this lane's pixels, local index wave * 64 + tn * 32 + lrow (one sum, integer output)
 
         for (int slice = 0; slice < slices; ++slice) {
             if (slice > 0) {
@@ -260,11 +267,11 @@ __global__ __launch_bounds__(256, KIND == kConvSum ? 3 : 2) void conv3x3_halo_ke
             wait_vmem<0>();
             __syncthreads();   // slice, first weights and tables visible
             if (slice == 0) {
-                if constexpr (SUM) {
+                if constexpr (SUM || INT_OUT) {
 #pragma unroll
                     for (int tn = 0; tn < TN; ++tn) pix_mask[tn] = s_mask[wave * 64 + tn * 32 + lrow];
                 }
-                if constexpr (PER_TAP) {
+                if constexpr (FOLD) {
 #pragma unroll
                     for (int tn = 0; tn < TN; ++tn) {
                         const float f0 = s_start[wave * 64 + tn * 32 + lrow];
@@ -312,7 +319,28 @@ __global__ __launch_bounds__(256, KIND == kConvSum ? 3 : 2) void conv3x3_halo_ke
                 wait_lds<0>();
                 multiply(op[0], false);
 
-                if constexpr (PER_TAP) {
+                if constexpr (PER_TAP && INT_OUT) {
+                    // the sums of this (slice, tap), exactly: stored by the first slice, added by the others
+                    // (the same lane owns an element in every slice); a tap outside the image is written as 0
+                    int *yi = static_cast<int *>(a.y);
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn) {
+                        const uint32_t pix = p0 + wave * 64 + tn * 32 + lrow;
+                        if (pix >= a.pixels) continue;
+                        const bool inside = (pix_mask[tn] >> tap) & 1;
+#pragma unroll
+                        for (int tm = 0; tm < TM; ++tm) {
+                            const int cbase = co0 + tm * 32 + 16 * lhalf;
+                            int *dst = yi + (static_cast<int64_t>(pix) * TAPS + tap) * a.n + cbase;
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                if (cbase + r >= a.n) continue;
+                                const int v = inside ? (acc[tm][tn][r] >> 8) : 0;
+                                dst[r] = slice == 0 ? v : dst[r] + v;
+                            }
+                        }
+                    }
+                } else if constexpr (PER_TAP) {
                     float s[TN];
                     read_tap_scales<TN>(s, lds_sx + tap * (BP * 4));
 #pragma unroll
@@ -348,6 +376,24 @@ __global__ __launch_bounds__(256, KIND == kConvSum ? 3 : 2) void conv3x3_halo_ke
         }
 
         // ---- dequantising epilogue (LDS reads by hand: loads of the next tile are in flight) ------
+        if constexpr (INT_OUT) {
+            if constexpr (SUM) {   // the one sum over all taps and slices
+                int *yi = static_cast<int *>(a.y);
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) {
+                    const uint32_t pix = p0 + wave * 64 + tn * 32 + lrow;
+                    if (pix >= a.pixels) continue;
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm) {
+                        const int cbase = co0 + tm * 32 + 16 * lhalf;
+                        int *dst = yi + static_cast<int64_t>(pix) * a.n + cbase;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            if (cbase + r < a.n) dst[r] = acc[tm][tn][r] >> 8;
+                    }
+                }
+            }
+        } else {
         Out *y = static_cast<Out *>(a.y);
         const bool vec_ok = (a.n & 15) == 0;
         float sxv[TN];
@@ -375,7 +421,7 @@ __global__ __launch_bounds__(256, KIND == kConvSum ? 3 : 2) void conv3x3_halo_ke
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     float v;
-                    if constexpr (PER_TAP) v = facc[tm][tn][r];
+                    if constexpr (FOLD) v = facc[tm][tn][r];
                     else v = sxv[tn] * static_cast<float>(acc[tm][tn][r]);
                     out[r] = __builtin_fmaf(v, __int_as_float(swq[r >> 2][r & 3]), __int_as_float(bq[r >> 2][r & 3]));
                 }
@@ -389,20 +435,22 @@ __global__ __launch_bounds__(256, KIND == kConvSum ? 3 : 2) void conv3x3_halo_ke
                 }
             }
         }
+        }
         __syncthreads();   // the tables are free for the next tile
     }
 }
 
 }  // namespace
 
-// True if the layer fits this kernel: channel slices of 192, fp output, image rows short enough
-// for 256 pixels plus the halo to fit the LDS buffer.
+// True if the layer fits this kernel: channel slices of 192, image rows short enough for 256
+// pixels plus the halo to fit the LDS buffer.
 bool hq_conv3x3_halo_fits(const GemmArgs &g, hq_dtype y_dtype) {
-    return g.k % 192 == 0 && (y_dtype == HQ_F16 || y_dtype == HQ_F32) && 256 + 2 * (g.w + 1) <= kHaloRows &&
-           g.pixels >= static_cast<uint32_t>(kHaloRows);
+    return g.k % 192 == 0 && (y_dtype == HQ_F16 || y_dtype == HQ_F32 || y_dtype == HQ_I32) &&
+           256 + 2 * (g.w + 1) <= kHaloRows && g.pixels >= static_cast<uint32_t>(kHaloRows);
 }
 
 hq_status hq_conv3x3_halo_launch(const GemmArgs &g, hq_dtype y_dtype, hipStream_t stream) {
+    const hq::LaunchCheck check;   // samples the thread's error state before anything is launched
     if (!hq_conv3x3_halo_fits(g, y_dtype)) return HQ_ERR_UNSUPPORTED;
     HaloArgs a{};
     a.xq = g.xq; a.sx = g.sx; a.wq = g.wq; a.sw = g.sw; a.bias = g.bias; a.y = g.y;
@@ -421,13 +469,17 @@ hq_status hq_conv3x3_halo_launch(const GemmArgs &g, hq_dtype y_dtype, hipStream_
     if (g.sx_static) {
         if (y_dtype == HQ_F16)
             hipLaunchKernelGGL((conv3x3_halo_kernel<kConvSum, kOutF16>), dim3(grid), block, 0, stream, a);
-        else
+        else if (y_dtype == HQ_F32)
             hipLaunchKernelGGL((conv3x3_halo_kernel<kConvSum, kOutF32>), dim3(grid), block, 0, stream, a);
+        else
+            hipLaunchKernelGGL((conv3x3_halo_kernel<kConvSum, kOutI32>), dim3(grid), block, 0, stream, a);
     } else {
         if (y_dtype == HQ_F16)
             hipLaunchKernelGGL((conv3x3_halo_kernel<kConvPerTap, kOutF16>), dim3(grid), block, 0, stream, a);
-        else
+        else if (y_dtype == HQ_F32)
             hipLaunchKernelGGL((conv3x3_halo_kernel<kConvPerTap, kOutF32>), dim3(grid), block, 0, stream, a);
+        else
+            hipLaunchKernelGGL((conv3x3_halo_kernel<kConvPerTap, kOutI32>), dim3(grid), block, 0, stream, a);
     }
-    return hq::launch_status();
+    return check.status();
 }

@@ -133,13 +133,19 @@ __global__ __launch_bounds__(256, 1) void conv3x3_wave_kernel(WaveConvArgs a) {
         if (++fch == cpt) { fch = 0; ++ftap; }
     };
 
-    float facc[TM][TN][16];
+    constexpr bool INT_OUT = OUT == kOutI32;
+    float facc[INT_OUT ? 1 : TM][INT_OUT ? 1 : TN][16];
+    if constexpr (!INT_OUT) {
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
+        for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
+            for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) facc[tm][tn][r] = 0.f;
+                for (int r = 0; r < 16; ++r) facc[tm][tn][r] = 0.f;
+    }
+    int my_mask[TN];   // integer output: tap masks of this lane's two pixels (pixel tn * 32 + lrow)
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) my_mask[tn] = 0;
 
     if (c0 < c1) {
         // ---- scales of the nine input pixels of this lane's output pixel (pixel lhalf*32 + lrow)
@@ -156,7 +162,11 @@ __global__ __launch_bounds__(256, 1) void conv3x3_wave_kernel(WaveConvArgs a) {
             for (int t = 0; t < TAPS; ++t) {
                 uint32_t ip = pix + static_cast<uint32_t>((t / 3 - 1) * a.w + (t % 3 - 1));
                 ip = ip < last ? ip : last;
-                v[t] = a.sx[a.sx_static ? 0 : ip];
+                v[t] = INT_OUT ? 0.f : a.sx[a.sx_static ? 0 : ip];   // integer output: no scales (null allowed)
+            }
+            if constexpr (INT_OUT) {   // lane (lhalf, lrow) computed the mask of pixel lhalf * 32 + lrow
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) my_mask[tn] = __shfl(mask, tn * 32 + lrow, 64);
             }
             // the chunks in flight first, then the table: the table's loads are older than the
             // chunk loads, so waiting for them leaves the chunk loads in flight
@@ -211,21 +221,46 @@ __global__ __launch_bounds__(256, 1) void conv3x3_wave_kernel(WaveConvArgs a) {
 
             const bool tap_ends = ch + 1 == cpt;
             if (tap_ends || c + 1 == c1) {
-                float s[TN];
-                read_tap_scales<TN>(s, lds_sx + tap * (TN * 32 * 4));
+                if constexpr (INT_OUT) {
+                    // This wave's share of the tap's sum, added to the zero-filled output: integer
+                    // additions are exact, so the order in which the waves of a tile arrive does not
+                    // matter.  Per-tap sums [pixel, tap, n]; one sum over all taps [pixel, n] when the
+                    // tensor has one scale (then taps outside the image must not count either).
+                    int *yi = static_cast<int *>(a.y);
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
+                    for (int tn = 0; tn < TN; ++tn) {
+                        const uint32_t pix = p0 + tn * 32 + lrow;
+                        if (pix >= a.pixels || !((my_mask[tn] >> tap) & 1)) continue;
 #pragma unroll
-                    for (int tm = 0; tm < TM; ++tm)
+                        for (int tm = 0; tm < TM; ++tm) {
+                            const int cbase = co0 + tm * 32 + 16 * lhalf;
+                            int *dst = yi + (a.sx_static ? static_cast<int64_t>(pix)
+                                                         : static_cast<int64_t>(pix) * TAPS + tap) * a.n + cbase;
 #pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            facc[tm][tn][r] += s[tn] * static_cast<float>(acc[tm][tn][r]);
+                            for (int r = 0; r < 16; ++r)
+                                if (cbase + r < a.n) atomicAdd(dst + r, acc[tm][tn][r] >> 8);
+                        }
+                    }
+                } else {
+                    float s[TN];
+                    read_tap_scales<TN>(s, lds_sx + tap * (TN * 32 * 4));
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r)
+                                facc[tm][tn][r] += s[tn] * static_cast<float>(acc[tm][tn][r]);
+                }
             }
             if (tap_ends) { ch = 0; ++tap; } else { ++ch; }
             stage = stage + 1 == NSTAGE ? 0 : stage + 1;
         }
     }
 
+    if constexpr (INT_OUT) {
+        return;   // everything was added to the output above
+    } else {
     // ---- the KG partial results of a tile meet in LDS; each wave finishes its share -----------
     // partial of a wave: [sub-tile tm*2+tn][r/4][lane] float4 in its own (now idle) stages
     Out *y = static_cast<Out *>(a.y);
@@ -292,6 +327,14 @@ __global__ __launch_bounds__(256, 1) void conv3x3_wave_kernel(WaveConvArgs a) {
         }
         finish(sub >> 1, sub & 1, v);
     }
+    }
+}
+
+// Zero fill of the integer output (its sums are accumulated with integer atomics).
+__global__ void fill_zero_kernel(int4 *dst, uint64_t n16, int *tail, int n_tail) {
+    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n16) dst[i] = int4{0, 0, 0, 0};
+    if (i < static_cast<uint64_t>(n_tail)) tail[i] = 0;
 }
 
 }  // namespace
@@ -310,7 +353,8 @@ int hq_conv3x3_wave_split(int64_t tiles, int chunks, int cus) {
 }
 
 hq_status hq_conv3x3_wave_launch(const GemmArgs &g, hq_dtype y_dtype, hipStream_t stream) {
-    if (g.k % 192 != 0 || (y_dtype != HQ_F16 && y_dtype != HQ_F32)) return HQ_ERR_UNSUPPORTED;
+    const hq::LaunchCheck check;   // samples the thread's error state before anything is launched
+    if (g.k % 192 != 0 || (y_dtype != HQ_F16 && y_dtype != HQ_F32 && y_dtype != HQ_I32)) return HQ_ERR_UNSUPPORTED;
     WaveConvArgs a{};
     a.xq = g.xq; a.sx = g.sx; a.wq = g.wq; a.sw = g.sw; a.bias = g.bias; a.y = g.y;
     a.pixels = g.pixels; a.n = g.n; a.k = g.k; a.h = g.h; a.w = g.w; a.sx_static = g.sx_static;
@@ -322,9 +366,20 @@ hq_status hq_conv3x3_wave_launch(const GemmArgs &g, hq_dtype y_dtype, hipStream_
     a.n_tiles = static_cast<uint32_t>(tiles);
     a.kg_log2 = hq_conv3x3_wave_split(tiles, 9 * (g.k / 192), hq::compute_units());
     const unsigned grid = static_cast<unsigned>(((tiles << a.kg_log2) + 3) / 4);
-    if (y_dtype == HQ_F16)
+    if (y_dtype == HQ_I32) {
+        // integer output [pixels, 9, n] (per-tap sums) or [pixels, n] (one scale: one sum): zero it, then
+        // every wave adds its share of a tap's sum
+        const uint64_t ints = static_cast<uint64_t>(g.pixels) * (g.sx_static ? 1 : 9) * g.n;
+        const uint64_t n16 = ints / 4;
+        const int n_tail = static_cast<int>(ints % 4);
+        const uint64_t blocks = (n16 + 255) / 256;
+        if (blocks > 0x7fffffffULL) return HQ_ERR_SHAPE;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(static_cast<unsigned>(blocks ? blocks : 1)), dim3(256), 0, stream,
+                           static_cast<int4 *>(g.y), n16, static_cast<int *>(g.y) + n16 * 4, n_tail);
+        hipLaunchKernelGGL((conv3x3_wave_kernel<kOutI32, 3>), dim3(grid), dim3(256), 0, stream, a);
+    } else if (y_dtype == HQ_F16)
         hipLaunchKernelGGL((conv3x3_wave_kernel<kOutF16, 3>), dim3(grid), dim3(256), 0, stream, a);
     else
         hipLaunchKernelGGL((conv3x3_wave_kernel<kOutF32, 3>), dim3(grid), dim3(256), 0, stream, a);
-    return hq::launch_status();
+    return check.status();
 }

@@ -500,6 +500,7 @@ __global__ __launch_bounds__(64 * kMaxBlocks) void hadamard64_quant_split_f16(co
 
 hq_status launch_hadamard64_split(const __half *x, int64_t m, int k, int bits, uint8_t *xq, float *scale,
                             const float *given, hipStream_t stream) {
+    const hq::LaunchCheck check;   // samples the thread's error state before anything is launched
     const float qmax = static_cast<float>((1 << (bits - 1)) - 1);
     const int nblk = k / 64;
     const int64_t groups = (m + 15) / 16;
@@ -513,7 +514,7 @@ hq_status launch_hadamard64_split(const __half *x, int64_t m, int k, int bits, u
     else
         hipLaunchKernelGGL(hadamard64_quant_split_f16<false>, dim3(static_cast<unsigned>(grid)), dim3(64 * nblk), 0,
                            stream, x, m, k, qmax, xq, scale, given);
-    return hq::launch_status();
+    return check.status();
 }
 
 template <int NBLK>
@@ -529,6 +530,7 @@ void launch_hadamard64_blocks(const __half *x, int64_t m, float qmax, uint8_t *x
 
 hq_status launch_hadamard64(const __half *x, int64_t m, int k, int bits, uint8_t *xq, float *scale,
                             const float *given, hipStream_t stream) {
+    const hq::LaunchCheck check;   // samples the thread's error state before anything is launched
     // one wave per 16 tokens needs about two waves per SIMD to hide the latency of its loads
     if ((m + 15) / 16 < 8 * static_cast<int64_t>(hq::compute_units()))
         return launch_hadamard64_split(x, m, k, bits, xq, scale, given, stream);
@@ -546,12 +548,13 @@ hq_status launch_hadamard64(const __half *x, int64_t m, int k, int bits, uint8_t
 #undef HQ_BLOCKS_CASE
         default: return HQ_ERR_SHAPE;
     }
-    return hq::launch_status();
+    return check.status();
 }
 
 template <typename T, int LOGB>
 hq_status launch_rowquant(const T *x, int64_t m, int row_len, int bits, bool bytes, uint32_t *xq, float *scale,
                           const float *given, hipStream_t stream) {
+    const hq::LaunchCheck check;   // samples the thread's error state before anything is launched
     RowQuantArgs a;
     a.given = given;
     a.m = m;
@@ -583,7 +586,7 @@ hq_status launch_rowquant(const T *x, int64_t m, int row_len, int bits, bool byt
         hipLaunchKernelGGL((rowquant_large<T, LOGB>), dim3(static_cast<unsigned>(m)), dim3(kThreads), 0,
                            stream, x, a, xq, scale);
     }
-    return hq::launch_status();
+    return check.status();
 }
 
 template <typename T>

@@ -43,6 +43,31 @@ hq_status check_common(const uint8_t *xq, const float *x_scale, const uint8_t *w
     return HQ_OK;
 }
 
+// Which kernel serves a stride-1 convolution.  The choice depends on the shape only, never on the
+// output type: the integer output (the raw sums) comes from the same kernel as the fp output.
+enum ConvKernel { kConvKernelTile = 0, kConvKernelWave = 1, kConvKernelHalo = 2 };
+
+ConvKernel choose_conv_kernel(int64_t pixels, int w, int c_in, int c_out, int r, int sx_static, int bits) {
+    if (bits == 8 || r != 3) return kConvKernelTile;   // the other two kernels expand nibbles, 3x3 only
+    // A 3x3 layer with about one 64x64 output tile per CU or fewer cannot fill the machine with
+    // whole tiles: it takes the kernel that also splits a tile's K range over waves.  (With one
+    // scale for the tensor that kernel still combines per-tap sums in fp32, which equals the one
+    // integer sum times one product of scales up to fp32 rounding.)
+    const int64_t cus = hq::compute_units();
+    const int64_t tiles64 = ((pixels + 63) / 64) * ((c_out + 63) / 64);
+    if (c_in % 192 == 0 && tiles64 * 4 <= 5 * cus) return kConvKernelWave;
+    // With at least one 64 x 256 tile per CU, keeping the activation tile in LDS for all nine taps
+    // beats re-fetching it per tap when the per-tap flush does not double (one 192-channel slice)
+    // or there is no flush at all (static scale).
+    const int64_t tiles256 = ((pixels + 255) / 256) * ((c_out + 63) / 64);
+    GemmArgs probe{};
+    probe.k = c_in;
+    probe.w = w;
+    probe.pixels = static_cast<uint32_t>(pixels);
+    if ((sx_static || c_in == 192) && tiles256 >= cus && hq_conv3x3_halo_fits(probe, HQ_F16)) return kConvKernelHalo;
+    return kConvKernelTile;
+}
+
 }  // namespace
 
 namespace {
@@ -99,22 +124,11 @@ hq_status int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
         a.pixels = static_cast<uint32_t>(static_cast<int64_t>(nb) * a.h_out * a.w_out);
         return hq_gemm_launch_64x64(a, 9, y_dtype, st_);
     }
-    if (bits == 8) return launch_gemm(a, r * s, y_dtype, st_);   // the 4-bit kernels below expand nibbles
-    // A 3x3 layer with about one 64x64 output tile per CU or fewer cannot fill the machine with
-    // whole tiles: it takes the kernel that also splits a tile's K range over waves.  (With one
-    // scale for the tensor that kernel still combines per-tap sums in fp32, which equals the one
-    // integer sum times one product of scales up to fp32 rounding; the integer output is the
-    // tile kernel's.)
-    const int64_t tiles64 = ((pixels + 63) / 64) * ((c_out + 63) / 64);
-    if (r == 3 && c_in % 192 == 0 && y_dtype != HQ_I32 &&
-        tiles64 * 4 <= 5 * static_cast<int64_t>(hq::compute_units()))
-        return hq_conv3x3_wave_launch(a, y_dtype, st_);
-    // With at least one 64 x 256 tile per CU, keeping the activation tile in LDS for all nine taps
-    // beats re-fetching it per tap when the per-tap flush does not double (one 192-channel slice)
-    // or there is no flush at all (static scale).
-    const int64_t tiles256 = ((pixels + 255) / 256) * ((c_out + 63) / 64);
-    if (r == 3 && (sx_static || c_in == 192) && tiles256 >= hq::compute_units() && hq_conv3x3_halo_fits(a, y_dtype))
-        return hq_conv3x3_halo_launch(a, y_dtype, st_);
+    switch (choose_conv_kernel(pixels, w, c_in, c_out, r, sx_static, bits)) {
+        case kConvKernelWave: return hq_conv3x3_wave_launch(a, y_dtype, st_);
+        case kConvKernelHalo: return hq_conv3x3_halo_launch(a, y_dtype, st_);
+        default: break;
+    }
     return launch_gemm(a, r * s, y_dtype, st_);
 }
 
@@ -199,4 +213,16 @@ extern "C" hq_status hq_int_conv2d_i8(const int8_t *xq, const float *x_scale, co
                                       void *stream) {
     return int_conv2d(reinterpret_cast<const uint8_t *>(xq), x_scale, reinterpret_cast<const uint8_t *>(wq), w_scale,
                       bias, nb, h, w, c_in, c_out, r, s, stride, pad, y, y_dtype, 0, 8, stream);
+}
+
+extern "C" const char *hq_int_conv2d_kernel_name(int nb, int h, int w, int c_in, int c_out, int r, int s, int stride,
+                                                 int pad, int static_scale, int bits) {
+    if (nb <= 0 || h <= 0 || w <= 0 || c_in <= 0 || c_out <= 0 || (bits != 4 && bits != 8)) return "unsupported";
+    if (r == 3 && s == 3 && stride == 2 && pad == 1 && bits == 4) return "tile (stride 2)";
+    if (r != s || (r != 1 && r != 3) || stride != 1 || pad != (r - 1) / 2) return "unsupported";
+    switch (choose_conv_kernel(static_cast<int64_t>(nb) * h * w, w, c_in, c_out, r, static_scale, bits)) {
+        case kConvKernelWave: return "wave-split";
+        case kConvKernelHalo: return "activation-resident";
+        default: return "tile";
+    }
 }

@@ -778,6 +778,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
 template <int TM, int TN, int WAVES_M, int WAVES_N, int KIND, int OUT, int KCH, int NSTAGE, int OCC, int XB = 4,
           bool S2 = false>
 hq_status launch_tile(GemmArgs a, hipStream_t stream) {
+    const hq::LaunchCheck check;   // samples the thread's error state before anything is launched
     constexpr int TAPS = taps_of(KIND);
     constexpr int BCO = 32 * TM * WAVES_M, BP = 32 * TN * WAVES_N;
     a.n_co_tiles = (a.n + BCO - 1) / BCO;
@@ -791,7 +792,7 @@ hq_status launch_tile(GemmArgs a, hipStream_t stream) {
     a.cus = static_cast<uint32_t>(hq::compute_units());
     hipLaunchKernelGGL((int_gemm_kernel<TM, TN, WAVES_M, WAVES_N, KIND, OUT, KCH, NSTAGE, OCC, XB, S2>),
                        dim3(grid), dim3(64 * WAVES_M * WAVES_N), 0, stream, a);
-    return hq::launch_status();
+    return check.status();
 }
 
 // All instantiations of one tile configuration: the four kernel kinds (taps = 1: linear;

@@ -76,6 +76,7 @@ __global__ __launch_bounds__(kThreads) void single_weights_kernel(const T *__res
 template <typename T>
 hq_status launch_single_weights(const T *w, int n_out, int k_in, int had_block, int bits, uint8_t *wq3,
                                 float *w_scale, hipStream_t stream) {
+    const hq::LaunchCheck check;   // samples the thread's error state before anything is launched
     const float qmax = static_cast<float>((1 << (bits - 1)) - 1);
     const dim3 grid(static_cast<unsigned>(n_out)), block(kThreads);
     switch (hq::ilog2(had_block)) {
@@ -86,7 +87,7 @@ hq_status launch_single_weights(const T *w, int n_out, int k_in, int had_block, 
 #undef HQ_SINGLE_CASE
         default: return HQ_ERR_SHAPE;
     }
-    return hq::launch_status();
+    return check.status();
 }
 
 }  // namespace

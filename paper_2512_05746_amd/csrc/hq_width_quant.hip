@@ -87,6 +87,7 @@ __global__ __launch_bounds__(kThreads) void width_quant_kernel(const T *__restri
 template <typename T>
 hq_status launch_width_quant(const T *x, int64_t lines, int w, int c, int had_block, int bits, const float *given,
                              uint8_t *xu3, hipStream_t stream) {
+    const hq::LaunchCheck check;   // samples the thread's error state before anything is launched
     const float qmax = static_cast<float>((1 << (bits - 1)) - 1);
     const int64_t grid = lines * (w / had_block);
     const int64_t plane = lines * w * (c / 2);
@@ -101,7 +102,7 @@ hq_status launch_width_quant(const T *x, int64_t lines, int w, int c, int had_bl
 #undef HQ_WIDTH_CASE
         default: return HQ_ERR_SHAPE;
     }
-    return hq::launch_status();
+    return check.status();
 }
 
 }  // namespace

@@ -26,9 +26,24 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert set(names) == set(hq.binding.SYMBOLS)
+    assert set(names) == set(hq.binding.SYMBOLS) | set(hq.binding.INFO_SYMBOLS)
     for name in names:
         assert getattr(lib, name) is not None
+
+
+def test_conv_kernel_choice_is_a_function_of_the_geometry(lib):
+    """The kernel family is reported per geometry (no output type among the arguments): the three
+    3x3 families are each reachable, and geometries that are not built say so."""
+    name = hq.hq_int_conv2d_kernel_name
+    assert name(16, 64, 64, 192, 192) == "activation-resident"
+    assert name(16, 8, 8, 960, 960) == "wave-split"
+    assert name(16, 32, 32, 384, 384) in ("tile", "activation-resident")
+    assert name(16, 32, 32, 384, 384, static_scale=True) == "activation-resident"
+    assert name(2, 9, 9, 64, 8) == "tile"
+    assert name(2, 9, 9, 64, 8, ksize=1) == "tile"
+    assert name(2, 9, 9, 64, 8, stride=2) == "tile (stride 2)"
+    assert name(2, 9, 9, 64, 8, ksize=5) == "unsupported"
+    assert name(16, 64, 64, 192, 192, bits=8) == "tile"
 
 
 def test_status_strings(lib):

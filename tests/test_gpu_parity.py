@@ -74,6 +74,8 @@ def run_layer(hq, layer, block=workloads.HAD_BLOCK):
     else:
         ks = layer.ksize
         wq4 = lambda c: c.reshape(layer.n_out, ks, ks, layer.k_in)
+        # the integer output comes from the same kernel as the fp output (the choice has no dtype argument)
+        print("   kernel:", hq.hq_int_conv2d_kernel_name(*layer.x_shape, layer.n_out, ksize=ks), flush=True)
         acc_o, y_o = oracle.int_conv2d(xq_o, sx_o, wq4(wq_o), sw_o, bias, stride=1, pad=layer.pad)
         acc_g = host(hq.hq_int_conv2d(xq_od, None, wq_od, None, None, ksize=ks, y_dtype=torch.int32))
         assert np.array_equal(acc_g, acc_o), layer.name + " per-tap int32 sums"
@@ -102,7 +104,7 @@ def run_layer_static(hq, layer, block=workloads.HAD_BLOCK):
 
     xq_o, tx = oracle.act_hadamard_quant_static(x, block, layer.a_bits, s)
     assert (tx > qmax + 0.5).any() and (tx < -qmax - 1.5).any(), "the test scale does not clamp"
-    wq_o, sw_o, _ = oracle.quantize_weights(w, block, layer.w_bits)
+    wq_o, sw_o, tw = oracle.quantize_weights(w, block, layer.w_bits)
 
     # (i) the activation quantiser (the weight path is that of the dynamic mode)
     xq_g = hq.hq_act_hadamard_quant_static(dev(x), s_d, block, layer.a_bits)
@@ -111,25 +113,30 @@ def run_layer_static(hq, layer, block=workloads.HAD_BLOCK):
     assert xq_gc.min() == -qmax - 1 and xq_gc.max() == qmax
     wq_g, sw_g = hq.hq_quantize_weights(dev(w), block, layer.w_bits)
     wq_gc = unpack_codes(host(wq_g))
+    check_scales(layer.name + " w_scale", host(sw_g), sw_o)
+    flips += check_codes(layer.name + " wq", wq_gc, wq_o, tw, layer.w_bits)
 
-    # (ii) integer stage on the oracle's codes, (iii) whole chain
+    # (ii) integer stage on the oracle's codes, (iii) whole chain against the oracle's own result
+    # (its codes and scales; the GPU's codes only where (i) found legitimate flips at ties)
     xq_od, wq_od = dev(pack_codes(xq_o)), dev(pack_codes(wq_o))
     bias_d = dev(bias) if bias is not None else None
-    sw_gh = host(sw_g).astype(np.float64)
+    xq_r, wq_r = (xq_gc, wq_gc) if flips else (xq_o, wq_o)
     if layer.kind == "linear":
         acc_o, _ = oracle.int_linear_static(xq_o, s, wq_o[:, 0, :], sw_o, bias)
         acc_g = host(hq.hq_int_linear_static(xq_od, None, wq_od, None, None, y_dtype=torch.int32))
         assert np.array_equal(acc_g, acc_o), layer.name + " int32 sums (static)"
-        _, y_o = oracle.int_linear_static(xq_gc, s, wq_gc[:, 0, :], sw_gh, bias)
+        _, y_o = oracle.int_linear_static(xq_r, s, wq_r[:, 0, :], sw_o, bias)
         y_g = host(hq.hq_int_linear_static(xq_g, s_d, wq_g, sw_g, bias_d, y_dtype=ydt))
     else:
         ks = layer.ksize
         wq4 = lambda c: c.reshape(layer.n_out, ks, ks, layer.k_in)
+        print("   kernel:", hq.hq_int_conv2d_kernel_name(*layer.x_shape, layer.n_out, ksize=ks, static_scale=True),
+              flush=True)
         acc_o, _ = oracle.int_conv2d_static(xq_o, s, wq4(wq_o), sw_o, bias, stride=1, pad=layer.pad,
                                             want_y=False)
         acc_g = host(hq.hq_int_conv2d_static(xq_od, None, wq_od, None, None, ksize=ks, y_dtype=torch.int32))
         assert np.array_equal(acc_g, acc_o), layer.name + " int32 sums over all taps (static)"
-        _, y_o = oracle.int_conv2d_static(xq_gc, s, wq4(wq_gc), sw_gh, bias, stride=1, pad=layer.pad,
+        _, y_o = oracle.int_conv2d_static(xq_r, s, wq4(wq_r), sw_o, bias, stride=1, pad=layer.pad,
                                           want_acc=False)
         y_g = host(hq.hq_int_conv2d_static(xq_g, s_d, wq_g, sw_g, bias_d, ksize=ks, y_dtype=ydt))
     err = check_y(layer.name + " y (static)", y_g.reshape(y_o.shape), y_o)
@@ -345,7 +352,7 @@ def test_w8a8_tiny_layers(hq, layer):
     run_layer_w8a8(hq, layer)
 
 
-@pytest.mark.parametrize("config", [1, 2, 3, 5])
+@pytest.mark.parametrize("config", [1, 2, 3, 4, 5])
 def test_w8a8_benchmark_configs_full_size(hq, config):
     for layer in workloads.config_layers(config):
         run_layer_w8a8(hq, layer)
@@ -395,7 +402,7 @@ def test_tiny_layers_static_scale(hq, layer):
     run_layer_static(hq, layer)
 
 
-@pytest.mark.parametrize("config", [1, 3, 4, 5])
+@pytest.mark.parametrize("config", [1, 2, 3, 4, 5])
 def test_benchmark_configs_full_size_static_scale(hq, config):
     for layer in workloads.config_layers(config):
         run_layer_static(hq, layer)
@@ -586,9 +593,49 @@ def test_activation_resident_conv_odd_geometry(hq, nb, h, w, cin, cout):
     sw = rng.uniform(0.001, 0.1, cout).astype(np.float32)
     bias = rng.standard_normal(cout).astype(np.float32)
     xq_d, wq_d = dev(pack_codes(xq)), dev(pack_codes(wq.reshape(cout, 9, cin)))
-    _, y_o = oracle.int_conv2d(xq, sx, wq, sw, bias, stride=1, pad=1, want_acc=False)
+    assert hq.hq_int_conv2d_kernel_name(nb, h, w, cin, cout, static_scale=True) == "activation-resident"
+    if cin == 192:
+        assert hq.hq_int_conv2d_kernel_name(nb, h, w, cin, cout) == "activation-resident"
+    acc_o, y_o = oracle.int_conv2d(xq, sx, wq, sw, bias, stride=1, pad=1)
+    acc_g = host(hq.hq_int_conv2d(xq_d, None, wq_d, None, None, ksize=3, y_dtype=torch.int32))
+    assert np.array_equal(acc_g, acc_o), "per-tap int32 sums"
+    del acc_g
     y_g = host(hq.hq_int_conv2d(xq_d, dev(sx), wq_d, dev(sw), dev(bias), ksize=3, y_dtype=torch.float32))
     check_y("y", y_g, y_o, rtol=2e-4)     # sums are folded per (slice, tap) from a biased accumulator
+    s1 = torch.tensor([0.37], dtype=torch.float32, device="cuda")
+    _, y_o = oracle.int_conv2d_static(xq, 0.37, wq, sw, bias, stride=1, pad=1, want_acc=False)
+    acc_g = host(hq.hq_int_conv2d_static(xq_d, None, wq_d, None, None, ksize=3, y_dtype=torch.int32))
+    assert np.array_equal(acc_g, acc_o.sum(axis=3)), "int32 sums over all taps"
+    del acc_g, acc_o
+    y_g = host(hq.hq_int_conv2d_static(xq_d, s1, wq_d, dev(sw), dev(bias), ksize=3, y_dtype=torch.float32))
+    check_y("y (static)", y_g, y_o, rtol=1e-5)
+
+
+@pytest.mark.parametrize("nb,h,w,cin,cout", [(1, 16, 16, 192, 100), (3, 9, 6, 384, 24), (5, 7, 9, 576, 130),
+                                             (2, 8, 8, 960, 960), (1, 1, 1, 192, 8), (4, 16, 16, 192, 320)])
+def test_wave_split_conv_odd_geometry(hq, nb, h, w, cin, cout):
+    """Shapes that take the kernel which splits a tile's K range over the waves of a workgroup
+    (few 64 x 64 tiles): 1, 2 and 4 waves per tile, ragged pixel and channel tiles, tiles spanning
+    images.  Per-tap int32 sums and the one sum over all taps bit for bit (every wave adds its
+    share with integer atomics), fp32 outputs of both scale modes to 1e-5."""
+    rng = np.random.default_rng(nb * 1000 + h * 100 + w + cin + cout)
+    xq = rng.integers(-8, 8, (nb, h, w, cin)).astype(np.int8)
+    wq = rng.integers(-8, 8, (cout, 3, 3, cin)).astype(np.int8)
+    xq[0, 0, 0, :], wq[0, :, :, :] = -8, -8
+    sx = rng.uniform(0.01, 1.0, (nb, h, w)).astype(np.float32)
+    sw = rng.uniform(0.001, 0.1, cout).astype(np.float32)
+    bias = rng.standard_normal(cout).astype(np.float32)
+    xq_d, wq_d = dev(pack_codes(xq)), dev(pack_codes(wq.reshape(cout, 9, cin)))
+    assert hq.hq_int_conv2d_kernel_name(nb, h, w, cin, cout) == "wave-split"
+    assert hq.hq_int_conv2d_kernel_name(nb, h, w, cin, cout, static_scale=True) == "wave-split"
+    acc_o, y_o = oracle.int_conv2d(xq, sx, wq, sw, bias, stride=1, pad=1)
+    for rep in range(2):     # twice: the output buffer is zeroed by the call itself
+        acc_g = host(hq.hq_int_conv2d(xq_d, None, wq_d, None, None, ksize=3, y_dtype=torch.int32))
+        assert np.array_equal(acc_g, acc_o), "per-tap int32 sums, call %d" % rep
+    acc_g = host(hq.hq_int_conv2d_static(xq_d, None, wq_d, None, None, ksize=3, y_dtype=torch.int32))
+    assert np.array_equal(acc_g, acc_o.sum(axis=3)), "int32 sums over all taps"
+    y_g = host(hq.hq_int_conv2d(xq_d, dev(sx), wq_d, dev(sw), dev(bias), ksize=3, y_dtype=torch.float32))
+    check_y("y", y_g, y_o, rtol=1e-5)
     s1 = torch.tensor([0.37], dtype=torch.float32, device="cuda")
     _, y_o = oracle.int_conv2d_static(xq, 0.37, wq, sw, bias, stride=1, pad=1, want_acc=False)
     y_g = host(hq.hq_int_conv2d_static(xq_d, s1, wq_d, dev(sw), dev(bias), ksize=3, y_dtype=torch.float32))
