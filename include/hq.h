@@ -149,7 +149,8 @@ hq_status hq_int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *
  * (bits = 4) or 8-bit (bits = 8, hq_int_conv2d_i8) codes.  The choice depends on the geometry
  * only, never on y_dtype: the HQ_I32 outputs (raw integer sums) come from the same kernel as the
  * floating-point outputs.  Host logic only; returns a static string: "tile", "tile (stride 2)",
- * "wave-split", "activation-resident", or "unsupported".
+ * "wave-split", "activation-resident", "activation-resident-int8 (P pixels)" with P = 256, 128 or 64
+ * (the pixel tile of a workgroup), or "unsupported".
  */
 const char *hq_int_conv2d_kernel_name(int nb, int h, int w, int c_in, int c_out, int r, int s,
                                       int stride, int pad, int static_scale, int bits);

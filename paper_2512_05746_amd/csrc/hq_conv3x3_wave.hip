@@ -352,6 +352,17 @@ int hq_conv3x3_wave_split(int64_t tiles, int chunks, int cus) {
     return best;
 }
 
+// Zero fill of `ints` int32 values at a 16-byte aligned address (a kernel, so that it can be captured).
+hq_status hq_fill_zero_launch(void *dst, uint64_t ints, hipStream_t stream) {
+    const uint64_t n16 = ints / 4;
+    const int n_tail = static_cast<int>(ints % 4);
+    const uint64_t blocks = (n16 + 255) / 256;
+    if (blocks > 0x7fffffffULL) return HQ_ERR_SHAPE;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(static_cast<unsigned>(blocks ? blocks : 1)), dim3(256), 0, stream,
+                       static_cast<int4 *>(dst), n16, static_cast<int *>(dst) + n16 * 4, n_tail);
+    return HQ_OK;
+}
+
 hq_status hq_conv3x3_wave_launch(const GemmArgs &g, hq_dtype y_dtype, hipStream_t stream) {
     const hq::LaunchCheck check;   // samples the thread's error state before anything is launched
     if (g.k % 192 != 0 || (y_dtype != HQ_F16 && y_dtype != HQ_F32 && y_dtype != HQ_I32)) return HQ_ERR_UNSUPPORTED;
@@ -369,13 +380,9 @@ hq_status hq_conv3x3_wave_launch(const GemmArgs &g, hq_dtype y_dtype, hipStream_
     if (y_dtype == HQ_I32) {
         // integer output [pixels, 9, n] (per-tap sums) or [pixels, n] (one scale: one sum): zero it, then
         // every wave adds its share of a tap's sum
-        const uint64_t ints = static_cast<uint64_t>(g.pixels) * (g.sx_static ? 1 : 9) * g.n;
-        const uint64_t n16 = ints / 4;
-        const int n_tail = static_cast<int>(ints % 4);
-        const uint64_t blocks = (n16 + 255) / 256;
-        if (blocks > 0x7fffffffULL) return HQ_ERR_SHAPE;
-        hipLaunchKernelGGL(fill_zero_kernel, dim3(static_cast<unsigned>(blocks ? blocks : 1)), dim3(256), 0, stream,
-                           static_cast<int4 *>(g.y), n16, static_cast<int *>(g.y) + n16 * 4, n_tail);
+        const hq_status st = hq_fill_zero_launch(g.y, static_cast<uint64_t>(g.pixels) * (g.sx_static ? 1 : 9) * g.n,
+                                                 stream);
+        if (st != HQ_OK) return st;
         hipLaunchKernelGGL((conv3x3_wave_kernel<kOutI32, 3>), dim3(grid), dim3(256), 0, stream, a);
     } else if (y_dtype == HQ_F16)
         hipLaunchKernelGGL((conv3x3_wave_kernel<kOutF16, 3>), dim3(grid), dim3(256), 0, stream, a);

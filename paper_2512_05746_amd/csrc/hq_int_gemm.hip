@@ -45,10 +45,13 @@ hq_status check_common(const uint8_t *xq, const float *x_scale, const uint8_t *w
 
 // Which kernel serves a stride-1 convolution.  The choice depends on the shape only, never on the
 // output type: the integer output (the raw sums) comes from the same kernel as the fp output.
-enum ConvKernel { kConvKernelTile = 0, kConvKernelWave = 1, kConvKernelHalo = 2 };
+enum ConvKernel { kConvKernelTile = 0, kConvKernelWave = 1, kConvKernelHalo = 2, kConvKernelRes = 3 };
 
 ConvKernel choose_conv_kernel(int64_t pixels, int w, int c_in, int c_out, int r, int sx_static, int bits) {
-    if (bits == 8 || r != 3) return kConvKernelTile;   // the other two kernels expand nibbles, 3x3 only
+    if (bits == 8 || r != 3) return kConvKernelTile;   // the other kernels expand nibbles, 3x3 only
+    // Per-pixel scales, 192-channel slices, an activation tile that fits the LDS as int8 and at least
+    // half a tile per CU: the eight-wave kernel with the expanded activation tile resident.
+    if (!sx_static && hq_conv3x3_res_fits(pixels, w, c_in, c_out)) return kConvKernelRes;
     // A 3x3 layer with about one 64x64 output tile per CU or fewer cannot fill the machine with
     // whole tiles: it takes the kernel that also splits a tile's K range over waves.  (With one
     // scale for the tensor that kernel still combines per-tap sums in fp32, which equals the one
@@ -127,6 +130,7 @@ hq_status int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
     switch (choose_conv_kernel(pixels, w, c_in, c_out, r, sx_static, bits)) {
         case kConvKernelWave: return hq_conv3x3_wave_launch(a, y_dtype, st_);
         case kConvKernelHalo: return hq_conv3x3_halo_launch(a, y_dtype, st_);
+        case kConvKernelRes: return hq_conv3x3_res_launch(a, y_dtype, st_);
         default: break;
     }
     return launch_gemm(a, r * s, y_dtype, st_);
@@ -223,6 +227,12 @@ extern "C" const char *hq_int_conv2d_kernel_name(int nb, int h, int w, int c_in,
     switch (choose_conv_kernel(static_cast<int64_t>(nb) * h * w, w, c_in, c_out, r, static_scale, bits)) {
         case kConvKernelWave: return "wave-split";
         case kConvKernelHalo: return "activation-resident";
+        case kConvKernelRes:
+            switch (hq_conv3x3_res_tile_pixels(static_cast<int64_t>(nb) * h * w, w, c_in, c_out)) {
+                case 256: return "activation-resident-int8 (256 pixels)";
+                case 128: return "activation-resident-int8 (128 pixels)";
+                default: return "activation-resident-int8 (64 pixels)";
+            }
         default: return "tile";
     }
 }

@@ -878,6 +878,11 @@ hq_status hq_gemm_launch_64x128(const GemmArgs &a, int taps, hq_dtype y_dtype, h
 hq_status hq_gemm_launch_64x64(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream_t stream);
 // 3x3 convolution, one wave per 64x64 tile and K share (hq_conv3x3_wave.hip)
 hq_status hq_conv3x3_wave_launch(const GemmArgs &a, hq_dtype y_dtype, hipStream_t stream);
+hq_status hq_fill_zero_launch(void *dst, uint64_t ints, hipStream_t stream);
+// 3x3 convolution, per-pixel scales: eight waves per CU, int8 activation tile resident in LDS (hq_conv3x3_res.hip)
+bool hq_conv3x3_res_fits(int64_t pixels, int w, int c_in, int c_out);
+int hq_conv3x3_res_tile_pixels(int64_t pixels, int w, int c_in, int c_out);
+hq_status hq_conv3x3_res_launch(const GemmArgs &a, hq_dtype y_dtype, hipStream_t stream);
 // 3x3 convolution with the activation tile resident in LDS (hq_conv3x3_halo.hip)
 bool hq_conv3x3_halo_fits(const GemmArgs &a, hq_dtype y_dtype);
 hq_status hq_conv3x3_halo_launch(const GemmArgs &a, hq_dtype y_dtype, hipStream_t stream);

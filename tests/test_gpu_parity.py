@@ -594,8 +594,6 @@ def test_activation_resident_conv_odd_geometry(hq, nb, h, w, cin, cout):
     bias = rng.standard_normal(cout).astype(np.float32)
     xq_d, wq_d = dev(pack_codes(xq)), dev(pack_codes(wq.reshape(cout, 9, cin)))
     assert hq.hq_int_conv2d_kernel_name(nb, h, w, cin, cout, static_scale=True) == "activation-resident"
-    if cin == 192:
-        assert hq.hq_int_conv2d_kernel_name(nb, h, w, cin, cout) == "activation-resident"
     acc_o, y_o = oracle.int_conv2d(xq, sx, wq, sw, bias, stride=1, pad=1)
     acc_g = host(hq.hq_int_conv2d(xq_d, None, wq_d, None, None, ksize=3, y_dtype=torch.int32))
     assert np.array_equal(acc_g, acc_o), "per-tap int32 sums"
@@ -609,6 +607,40 @@ def test_activation_resident_conv_odd_geometry(hq, nb, h, w, cin, cout):
     del acc_g, acc_o
     y_g = host(hq.hq_int_conv2d_static(xq_d, s1, wq_d, dev(sw), dev(bias), ksize=3, y_dtype=torch.float32))
     check_y("y (static)", y_g, y_o, rtol=1e-5)
+
+
+@pytest.mark.parametrize("nb,h,w,cin,cout,px", [(8, 41, 50, 192, 250, 256), (3, 79, 70, 192, 330, 256),
+                                                (3, 40, 40, 192, 500, 64), (20, 30, 33, 384, 150, 128),
+                                                (17, 32, 20, 384, 390, 128), (33, 16, 16, 192, 200, 128),
+                                                (19, 15, 15, 576, 300, 64), (8, 32, 32, 384, 384, 64)])
+def test_int8_resident_conv_odd_geometry(hq, nb, h, w, cin, cout, px):
+    """Shapes that take the eight-wave kernel with the int8 activation tile resident in LDS, for
+    each of its three pixel-tile sizes (K ranges split over 1+2, 2+4 and 4+8 waves, partial sums
+    exchanged through LDS), one to three 192-channel slices, image sizes that are not powers of
+    two, tiles that span image rows and images, ragged last pixel and channel tiles.  Per-tap int32
+    sums bit for bit (twice: the call zeroes its output), fp32 output to 2e-4 (sums are folded per
+    slice and tap from a biased accumulator)."""
+    rng = np.random.default_rng(nb * 1000 + h * 100 + w + cin + cout)
+    xq = rng.integers(-8, 8, (nb, h, w, cin)).astype(np.int8)
+    wq = rng.integers(-8, 8, (cout, 3, 3, cin)).astype(np.int8)
+    xq[0, 0, 0, :], wq[0, :, :, :] = -8, -8
+    sx = rng.uniform(0.01, 1.0, (nb, h, w)).astype(np.float32)
+    sw = rng.uniform(0.001, 0.1, cout).astype(np.float32)
+    bias = rng.standard_normal(cout).astype(np.float32)
+    xq_d, wq_d = dev(pack_codes(xq)), dev(pack_codes(wq.reshape(cout, 9, cin)))
+    assert hq.hq_int_conv2d_kernel_name(nb, h, w, cin, cout) == "activation-resident-int8 (%d pixels)" % px
+    acc_o, y_o = oracle.int_conv2d(xq, sx, wq, sw, bias, stride=1, pad=1)
+    for rep in range(2):
+        acc_g = host(hq.hq_int_conv2d(xq_d, None, wq_d, None, None, ksize=3, y_dtype=torch.int32))
+        assert np.array_equal(acc_g, acc_o), "per-tap int32 sums, call %d" % rep
+        del acc_g
+    del acc_o
+    y_g = host(hq.hq_int_conv2d(xq_d, dev(sx), wq_d, dev(sw), dev(bias), ksize=3, y_dtype=torch.float32))
+    check_y("y", y_g, y_o, rtol=2e-4)
+    y_h = host(hq.hq_int_conv2d(xq_d, dev(sx), wq_d, dev(sw), dev(bias.astype(np.float16)), ksize=3,
+                                y_dtype=torch.float16))
+    _, y_o = oracle.int_conv2d(xq, sx, wq, sw, bias.astype(np.float16), stride=1, pad=1, want_acc=False)
+    check_y("y (fp16)", y_h, y_o, rtol=1e-3)
 
 
 @pytest.mark.parametrize("nb,h,w,cin,cout", [(1, 16, 16, 192, 100), (3, 9, 6, 384, 24), (5, 7, 9, 576, 130),
