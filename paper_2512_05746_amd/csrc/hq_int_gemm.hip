@@ -59,9 +59,10 @@ ConvKernel choose_conv_kernel(int64_t pixels, int w, int c_in, int c_out, int r,
     const int64_t cus = hq::compute_units();
     const int64_t tiles64 = ((pixels + 63) / 64) * ((c_out + 63) / 64);
     if (c_in % 192 == 0 && tiles64 * 4 <= 5 * cus) return kConvKernelWave;
-    // With at least one 64 x 256 tile per CU, keeping the activation tile in LDS for all nine taps
-    // beats re-fetching it per tap when the per-tap flush does not double (one 192-channel slice)
-    // or there is no flush at all (static scale).
+    // One scale for the tensor and at least one 64 x 256 tile per CU: no per-tap fold at all, the
+    // kernel that keeps the packed activation tile in LDS for all nine taps, three workgroups per CU.
+    // (It also serves per-pixel scales with one 192-channel slice where the int8-resident kernel
+    // above does not fit, e.g. very wide images.)
     const int64_t tiles256 = ((pixels + 255) / 256) * ((c_out + 63) / 64);
     GemmArgs probe{};
     probe.k = c_in;
@@ -230,6 +231,7 @@ extern "C" const char *hq_int_conv2d_kernel_name(int nb, int h, int w, int c_in,
         case kConvKernelRes:
             switch (hq_conv3x3_res_tile_pixels(static_cast<int64_t>(nb) * h * w, w, c_in, c_out)) {
                 case 256: return "activation-resident-int8 (256 pixels)";
+                case 129: return "activation-resident-int8 (128 pixels, 4 waves)";
                 case 128: return "activation-resident-int8 (128 pixels)";
                 default: return "activation-resident-int8 (64 pixels)";
             }

@@ -609,14 +609,15 @@ def test_activation_resident_conv_odd_geometry(hq, nb, h, w, cin, cout):
     check_y("y (static)", y_g, y_o, rtol=1e-5)
 
 
-@pytest.mark.parametrize("nb,h,w,cin,cout,px", [(8, 41, 50, 192, 250, 256), (3, 79, 70, 192, 330, 256),
+@pytest.mark.parametrize("nb,h,w,cin,cout,px", [(8, 41, 50, 192, 250, "128 pixels, 4 waves"), (3, 79, 70, 192, 330, 256),
+                                                (9, 60, 61, 192, 100, "128 pixels, 4 waves"),
                                                 (3, 40, 40, 192, 500, 64), (20, 30, 33, 384, 150, 128),
                                                 (17, 32, 20, 384, 390, 128), (33, 16, 16, 192, 200, 128),
                                                 (19, 15, 15, 576, 300, 64), (8, 32, 32, 384, 384, 64)])
 def test_int8_resident_conv_odd_geometry(hq, nb, h, w, cin, cout, px):
-    """Shapes that take the eight-wave kernel with the int8 activation tile resident in LDS, for
-    each of its three pixel-tile sizes (K ranges split over 1+2, 2+4 and 4+8 waves, partial sums
-    exchanged through LDS), one to three 192-channel slices, image sizes that are not powers of
+    """Shapes that take the kernel with the int8 activation tile resident in LDS, for each of its
+    three pixel-tile sizes with eight waves (K ranges split over 1+2, 2+4 and 4+8 waves, partial sums
+    exchanged through LDS) and for its four-wave form, one to three 192-channel slices, image sizes that are not powers of
     two, tiles that span image rows and images, ragged last pixel and channel tiles.  Per-tap int32
     sums bit for bit (twice: the call zeroes its output), fp32 output to 2e-4 (sums are folded per
     slice and tap from a biased accumulator)."""
@@ -628,7 +629,8 @@ def test_int8_resident_conv_odd_geometry(hq, nb, h, w, cin, cout, px):
     sw = rng.uniform(0.001, 0.1, cout).astype(np.float32)
     bias = rng.standard_normal(cout).astype(np.float32)
     xq_d, wq_d = dev(pack_codes(xq)), dev(pack_codes(wq.reshape(cout, 9, cin)))
-    assert hq.hq_int_conv2d_kernel_name(nb, h, w, cin, cout) == "activation-resident-int8 (%d pixels)" % px
+    want = "activation-resident-int8 (%s)" % (px if isinstance(px, str) else "%d pixels" % px)
+    assert hq.hq_int_conv2d_kernel_name(nb, h, w, cin, cout) == want
     acc_o, y_o = oracle.int_conv2d(xq, sx, wq, sw, bias, stride=1, pad=1)
     for rep in range(2):
         acc_g = host(hq.hq_int_conv2d(xq_d, None, wq_d, None, None, ksize=3, y_dtype=torch.int32))
