@@ -10,12 +10,15 @@ resident in HBM before timing starts.
 
 Prints ONE JSON line.  `value` is the aggregate integer throughput of the sweep
 (2*M*N*K_total operations per layer, summed, divided by the wall time of a
-step).  `roofline` is for the dominant kernel (the 3x3 implicit-GEMM
-convolutions) from HIP-event durations taken around runs of identical launches
-in a second, instrumented pass over the same kernels and buffers.  `hadamard_quant` reports the standalone
-transform+quantise kernel on the largest activation, rotating through enough
-buffers to defeat the 256 MB last-level cache.  `cpu_baseline` is the CPU oracle
-on a bounded sample of the same workload.
+step).  Consecutive steps alternate between two complete sets of activation,
+code, scale and output buffers, so that the data a step touches (two sets:
+about 440 MB) does not fit the 256 MB last-level cache.  `roofline` is for the
+dominant kernel (the 3x3 implicit-GEMM convolutions) from HIP-event durations
+taken around runs of identical launches in a second, instrumented pass, in which
+every kernel rotates through as many buffer sets as it takes to exceed 288 MB.
+`hadamard_quant` reports the standalone transform+quantise kernel on the largest
+activation with the same kind of rotation.  `cpu_baseline` is the CPU oracle on
+one whole step of the same workload (about two seconds on the host's cores).
 """
 import argparse
 import json
@@ -58,17 +61,25 @@ def main():
     layers = workloads.config_layers(CONFIG)
 
     # ---- resident inputs, offline weight preparation, preallocated outputs -----------------
-    state = []
+    # Two complete buffer sets (the second a copy of the first): consecutive timed steps alternate
+    # between them, so a step never finds its data in the 256 MB last-level cache.
+    def new_buffers(layer, x):
+        xq = torch.empty(x.shape[:-1] + (layer.k_in // 2,), dtype=torch.uint8, device="cuda")
+        sx = torch.empty(x.shape[:-1], dtype=torch.float32, device="cuda")
+        y = torch.empty(x.shape[:-1] + (layer.n_out,), dtype=torch.float16, device="cuda")
+        return xq, sx, y
+
+    state, state_b = [], []
     for layer in layers:
         x = torch.from_numpy(workloads.make_x(layer)).cuda()
         w = torch.from_numpy(workloads.make_w(layer)).cuda()
         wq, sw = hq.hq_quantize_weights(w, workloads.HAD_BLOCK, layer.w_bits)
         del w
-        xq = torch.empty(x.shape[:-1] + (layer.k_in // 2,), dtype=torch.uint8, device="cuda")
-        sx = torch.empty(x.shape[:-1], dtype=torch.float32, device="cuda")
-        y = torch.empty(x.shape[:-1] + (layer.n_out,), dtype=torch.float16, device="cuda")
-        state.append((layer, x, wq, sw, xq, sx, y))
+        state.append((layer, x, wq, sw) + new_buffers(layer, x))
+        xb2 = x.clone()
+        state_b.append((layer, xb2, wq, sw) + new_buffers(layer, xb2))
     torch.cuda.synchronize()
+    set_bytes = sum(sum(t.numel() * t.element_size() for t in s[1:]) for s in state)
 
     def run_quant(s):
         layer, x, wq, sw, xq, sx, y = s
@@ -81,8 +92,8 @@ def main():
         else:
             hq.hq_int_linear(xq, sx, wq, sw, None, y_dtype=torch.float16, out=y)
 
-    def step():
-        for s in state:
+    def step(which=None):
+        for s in (state if which is None else which):
             run_quant(s)
             run_int(s)
 
@@ -92,24 +103,34 @@ def main():
     # memset nodes: the kernels clear nothing) and the timed region replays it, so the step
     # time is the device's, not the Python launch loop's.  --eager times the plain loop.
     graph = None
+    sets = (state, state_b)
     if not args.eager:
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
-            step()
+            for st in sets:
+                step(st)
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            step()
-    run_step = graph.replay if graph is not None else step
+        graph = []
+        for st in sets:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                step(st)
+            graph.append(g)
 
-    for _ in range(args.warmup):
-        run_step()
+    def run_step(i):
+        if graph is not None:
+            graph[i % 2].replay()
+        else:
+            step(sets[i % 2])
+
+    for i in range(args.warmup):
+        run_step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run_step()
+    for i in range(args.steps):
+        run_step(i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall / args.steps * 1e3
@@ -124,19 +145,23 @@ def main():
     reps = max(args.steps, 20)
 
     def batched_us(fn, s):
+        """Mean duration of fn over `reps` back-to-back launches; s is one buffer set or a list of
+        sets the launches rotate through."""
+        rot = s if isinstance(s, list) else [s]
+        n = max(reps, len(rot))
         if args.eager:
-            fn(s)
+            fn(rot[0])
             e0, e1 = ev(), ev()
             e0.record()
-            for _ in range(reps):
-                fn(s)
+            for r in range(n):
+                fn(rot[r % len(rot)])
             e1.record()
             torch.cuda.synchronize()
-            return e0.elapsed_time(e1) * 1e3 / reps
+            return e0.elapsed_time(e1) * 1e3 / n
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
-            for _ in range(reps):
-                fn(s)
+            for r in range(n):
+                fn(rot[r % len(rot)])
         g.replay()
         torch.cuda.synchronize()
         e0, e1 = ev(), ev()
@@ -144,13 +169,30 @@ def main():
         g.replay()
         e1.record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / reps
+        return e0.elapsed_time(e1) * 1e3 / n
 
+    # Every layer's two kernels are timed while rotating through as many copies of the layer's
+    # buffers as it takes to exceed the last-level cache (288 MB of activations, codes, scales and
+    # outputs), so the durations are those of a kernel that finds nothing of its own in cache.
+    ROTATE_BYTES = 288 << 20
     quant_us = np.zeros(len(state))
     int_us = np.zeros(len(state))
+    rot_sets = []
     for i, s in enumerate(state):
-        quant_us[i] = batched_us(run_quant, s)
-        int_us[i] = batched_us(run_int, s)
+        layer, x, wq, sw = s[:4]
+        one = sum(t.numel() * t.element_size() for t in (x,) + tuple(s[4:]))
+        n_sets = max(2, -(-ROTATE_BYTES // one))
+        rot = [s, state_b[i]]
+        while len(rot) < n_sets:
+            x2 = x.clone()
+            rot.append((layer, x2, wq, sw) + new_buffers(layer, x2))
+        for r in rot:
+            run_quant(r)
+        quant_us[i] = batched_us(run_quant, rot)
+        int_us[i] = batched_us(run_int, rot)
+        rot_sets.append(len(rot))
+        del rot
+    torch.cuda.synchronize()
 
     per_layer = []
     for i, (layer, *_r) in enumerate(state):
@@ -158,14 +200,24 @@ def main():
         in_bytes = layer.m * layer.k_in // 2 + layer.m * 4
         w_bytes = layer.n_out * layer.taps * layer.k_in // 2
         q_bytes = layer.m * layer.k_in * 2 + layer.m * layer.k_in // 2 + layer.m * 4
+        int_tops = layer.ops / int_us[i] / 1e6
+        int_gbs = (out_bytes + in_bytes + w_bytes) / int_us[i] / 1e3
+        # the roof that binds the integer stage of this layer: the matrix cores when its arithmetic
+        # intensity is above the machine balance (peak op/s over peak bytes/s), else the output write
+        mfma_bound = layer.ops / (out_bytes + in_bytes + w_bytes) > INT8_MFMA_PEAK_TOPS * 1e3 / HBM_PEAK_GBS
         per_layer.append({
             "layer": layer.name, "gop": round(layer.ops / 1e9, 3),
             "int_us": round(float(int_us[i]), 2),
-            "int_tops": round(layer.ops / int_us[i] / 1e6, 1),
-            "int_frac_mfma_peak": round(layer.ops / int_us[i] / 1e6 / INT8_MFMA_PEAK_TOPS, 4),
-            "int_gbs": round((out_bytes + in_bytes + w_bytes) / int_us[i] / 1e3, 1),
+            "int_tops": round(int_tops, 1),
+            "int_frac_mfma_peak": round(int_tops / INT8_MFMA_PEAK_TOPS, 4),
+            "int_gbs": round(int_gbs, 1),
+            "int_binding_roof": "mfma" if mfma_bound else "hbm",
+            "int_frac_of_binding_roof": round(int_tops / INT8_MFMA_PEAK_TOPS if mfma_bound
+                                              else int_gbs / HBM_PEAK_GBS, 4),
             "quant_us": round(float(quant_us[i]), 2),
             "quant_gbs": round(q_bytes / quant_us[i] / 1e3, 1),
+            "quant_frac_hbm_peak": round(q_bytes / quant_us[i] / 1e3 / HBM_PEAK_GBS, 4),
+            "rotating_buffer_sets": rot_sets[i],
         })
     # ---- the same layers with ONE static activation scale (the paper's learned per-timestep
     # scale): no abs-max pass, and a 3x3 convolution keeps one integer sum over all taps ------
@@ -374,6 +426,9 @@ def main():
                         "block-64 Hadamard; 9 layers, act-quant + integer conv/linear each",
             "total_gop": round(total_ops / 1e9, 2), "launches_per_step": 2 * len(state),
             "launch": "hipgraph replay" if graph is not None else "eager",
+            "buffer_sets": 2, "working_set_mb": round(2 * set_bytes / 1e6, 1),
+            "memory": "consecutive steps alternate between two buffer sets (working set above the 256 MB "
+                      "last-level cache); per-layer and roofline durations rotate each kernel over 288 MB of buffers",
         },
         "frac_int8_mfma_peak_wall": round(value / INT8_MFMA_PEAK_TOPS, 4),
         "int8_mfma_peak_tops": {"nominal_2.4GHz": round(INT8_MFMA_PEAK_TOPS, 1),
@@ -383,11 +438,14 @@ def main():
         "int_stage_tops_kernel_time": round(int_all_tops, 1),
         "frac_int8_mfma_peak_kernel_time": round(int_all_tops / INT8_MFMA_PEAK_TOPS, 4),
         "roofline": {
-            "kernel": "the four 3x3 implicit-GEMM convolution launches of the sweep (conv3x3_halo_kernel, int_gemm_kernel twice, conv3x3_wave_kernel)",
+            "kernel": "the four 3x3 implicit-GEMM convolution launches of the sweep: " + ", ".join(
+                hq.hq_int_conv2d_kernel_name(*state[i][1].shape, state[i][0].n_out) for i in conv3),
             "bound": "mfma", "achieved": round(achieved, 1), "peak": round(INT8_MFMA_PEAK_TOPS, 1),
             "unit": "TOP/s", "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4),
             "traffic": measured_traffic(),
-            "traffic_unit": "HBM bytes per launch, mean over the four 3x3 launches (rocprofv3 FETCH_SIZE/WRITE_SIZE)",
+            "traffic_unit": "HBM bytes per launch, mean over the four 3x3 launches; read from the committed "
+                            "rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this command "
+                            "(profiles/bench_config5_hbm_traffic.txt), not measured in this run",
             "ops_per_launch": round(conv3_ops / len(conv3)), "us_per_launch": round(conv3_us / len(conv3), 2),
         },
         "hadamard_quant": {
