@@ -111,7 +111,8 @@ hq_status hq_act_hadamard_quant(const void *x, hq_dtype x_dtype, int64_t m, int 
  *   y[i, j]   = acc[i, j] * x_scale[i] * w_scale[j] + bias[j]   (fp32, cast to y_dtype)
  *
  *   xq [m, k/2], x_scale [m], wq [n, k/2], w_scale [n]; bias [n] of y_dtype or
- *   NULL; k a multiple of 64, k < 131072; y [m, n].
+ *   NULL; k a multiple of 8 (multiples of 64 take the fast kernels; any other multiple of 8, e.g.
+ *   the few channels of a layer that keeps H = I, takes a small general kernel), k < 131072; y [m, n].
  *   y_dtype == HQ_I32 writes acc itself (bias and scales ignored; they may be NULL).
  */
 hq_status hq_int_linear(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
@@ -135,7 +136,7 @@ hq_status hq_int_linear(const uint8_t *xq, const float *x_scale, const uint8_t *
  *   Built: R = S in {1, 3}, stride 1, pad (R-1)/2 (h_out = h, w_out = w), and the
  *   downsampling form R = S = 3, stride 2, pad 1 (h_out = (h-1)/2 + 1,
  *   w_out = (w-1)/2 + 1); anything else returns HQ_ERR_UNSUPPORTED.
- *   c_in a multiple of 64.
+ *   c_in a multiple of 8 at stride 1 (multiples of 64 take the fast kernels), a multiple of 64 at stride 2.
  *   y_dtype == HQ_I32 writes the per-tap accumulators [nb, h_out, w_out, R*S, c_out].
  */
 hq_status hq_int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
@@ -150,7 +151,8 @@ hq_status hq_int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *
  * only, never on y_dtype: the HQ_I32 outputs (raw integer sums) come from the same kernel as the
  * floating-point outputs.  Host logic only; returns a static string: "tile", "tile (stride 2)",
  * "wave-split", "activation-resident", "activation-resident-int8 (P pixels)" with P = 256, 128 or 64
- * (the pixel tile of a workgroup), or "unsupported".
+ * (the pixel tile of a workgroup; "128 pixels, 4 waves" for the four-wave form), "small-channel-count"
+ * (c_in not a multiple of 64), or "unsupported".
  */
 const char *hq_int_conv2d_kernel_name(int nb, int h, int w, int c_in, int c_out, int r, int s,
                                       int stride, int pad, int static_scale, int bits);

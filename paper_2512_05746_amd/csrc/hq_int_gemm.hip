@@ -30,12 +30,15 @@ bool fits_32bit(int64_t pixels, int w, int n, int taps, int k) {
            static_cast<int64_t>(n) * taps * (k / 2) <= lim;
 }
 
+// k_unit: what k must be a multiple of (64 for the kernels that fetch whole 64-code chunks; 8 where the
+// kernel for other channel counts can take over)
 hq_status check_common(const uint8_t *xq, const float *x_scale, const uint8_t *wq, const float *w_scale,
-                       const void *bias, int64_t pixels, int n, int k, const void *y, hq_dtype y_dtype) {
+                       const void *bias, int64_t pixels, int n, int k, const void *y, hq_dtype y_dtype,
+                       int k_unit = 64) {
     if (y_dtype != HQ_F16 && y_dtype != HQ_F32 && y_dtype != HQ_I32) return HQ_ERR_DTYPE;
     if (!xq || !wq || !y) return HQ_ERR_NULL;
     if (y_dtype != HQ_I32 && (!x_scale || !w_scale)) return HQ_ERR_NULL;
-    if (pixels <= 0 || n <= 0 || k <= 0 || (k & 63) != 0 || k >= 131072) return HQ_ERR_SHAPE;
+    if (pixels <= 0 || n <= 0 || k <= 0 || k % k_unit != 0 || k >= 131072) return HQ_ERR_SHAPE;
     if (!hq::aligned16(xq) || !hq::aligned16(wq) || !hq::aligned16(y)) return HQ_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(x_scale) & 3u) || (reinterpret_cast<uintptr_t>(w_scale) & 3u) ||
         (reinterpret_cast<uintptr_t>(bias) & 1u))
@@ -80,11 +83,12 @@ namespace {
 hq_status int_linear(const uint8_t *xq, const float *x_scale, const uint8_t *wq, const float *w_scale,
                      const void *bias, int64_t m, int n, int k, void *y, hq_dtype y_dtype, int sx_static,
                      int bits, void *stream) {
-    hq_status st = check_common(xq, x_scale, wq, w_scale, bias, m, n, k, y, y_dtype);
+    hq_status st = check_common(xq, x_scale, wq, w_scale, bias, m, n, k, y, y_dtype, bits == 4 ? 8 : 64);
     if (st != HQ_OK) return st;
     if (!fits_32bit(m, 1, n, 1, bits == 8 ? 2 * k : k)) return HQ_ERR_UNSUPPORTED;
     GemmArgs a{xq, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(m), n, k, 1, 1, 0, 0, 0, 1, sx_static,
                1.0f, bits};
+    if (k % 64 != 0) return hq_gemm_launch_anyk(a, 1, y_dtype, static_cast<hipStream_t>(stream));
     return launch_gemm(a, 1, y_dtype, static_cast<hipStream_t>(stream));
 }
 
@@ -110,7 +114,8 @@ hq_status int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
         return HQ_ERR_SHAPE;
     }
     const int64_t pixels = static_cast<int64_t>(nb) * h * w;
-    hq_status st = check_common(xq, x_scale, wq, w_scale, bias, pixels, c_out, c_in, y, y_dtype);
+    hq_status st = check_common(xq, x_scale, wq, w_scale, bias, pixels, c_out, c_in, y, y_dtype,
+                                bits == 4 && stride == 1 ? 8 : 64);
     if (st != HQ_OK) return st;
     const bool down = r == 3 && s == 3 && stride == 2 && pad == 1 && bits == 4;   // the downsampling convolution
     if (!down && (r != s || (r != 1 && r != 3) || stride != 1 || pad != (r - 1) / 2)) return HQ_ERR_UNSUPPORTED;
@@ -128,6 +133,7 @@ hq_status int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
         a.pixels = static_cast<uint32_t>(static_cast<int64_t>(nb) * a.h_out * a.w_out);
         return hq_gemm_launch_64x64(a, 9, y_dtype, st_);
     }
+    if (c_in % 64 != 0) return hq_gemm_launch_anyk(a, r * s, y_dtype, st_);
     switch (choose_conv_kernel(pixels, w, c_in, c_out, r, sx_static, bits)) {
         case kConvKernelWave: return hq_conv3x3_wave_launch(a, y_dtype, st_);
         case kConvKernelHalo: return hq_conv3x3_halo_launch(a, y_dtype, st_);
@@ -225,6 +231,8 @@ extern "C" const char *hq_int_conv2d_kernel_name(int nb, int h, int w, int c_in,
     if (nb <= 0 || h <= 0 || w <= 0 || c_in <= 0 || c_out <= 0 || (bits != 4 && bits != 8)) return "unsupported";
     if (r == 3 && s == 3 && stride == 2 && pad == 1 && bits == 4) return "tile (stride 2)";
     if (r != s || (r != 1 && r != 3) || stride != 1 || pad != (r - 1) / 2) return "unsupported";
+    if (c_in % 8 != 0 || (bits == 8 && c_in % 64 != 0)) return "unsupported";
+    if (c_in % 64 != 0) return "small-channel-count";
     switch (choose_conv_kernel(static_cast<int64_t>(nb) * h * w, w, c_in, c_out, r, static_scale, bits)) {
         case kConvKernelWave: return "wave-split";
         case kConvKernelHalo: return "activation-resident";

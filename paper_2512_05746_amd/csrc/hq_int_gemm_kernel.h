@@ -878,6 +878,8 @@ hq_status hq_gemm_launch_64x128(const GemmArgs &a, int taps, hq_dtype y_dtype, h
 hq_status hq_gemm_launch_64x64(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream_t stream);
 // 3x3 convolution, one wave per 64x64 tile and K share (hq_conv3x3_wave.hip)
 hq_status hq_conv3x3_wave_launch(const GemmArgs &a, hq_dtype y_dtype, hipStream_t stream);
+// linear / 1x1 / 3x3 (stride 1) for channel counts that are a multiple of 8 but not of 64 (hq_int_gemm_anyk.hip)
+hq_status hq_gemm_launch_anyk(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream_t stream);
 hq_status hq_fill_zero_launch(void *dst, uint64_t ints, hipStream_t stream);
 // 3x3 convolution, per-pixel scales: eight waves per CU, int8 activation tile resident in LDS (hq_conv3x3_res.hip)
 bool hq_conv3x3_res_fits(int64_t pixels, int w, int c_in, int c_out);

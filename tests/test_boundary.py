@@ -47,6 +47,10 @@ def test_conv_kernel_choice_is_a_function_of_the_geometry(lib):
     assert name(2, 9, 9, 64, 8, stride=2) == "tile (stride 2)"
     assert name(2, 9, 9, 64, 8, ksize=5) == "unsupported"
     assert name(16, 64, 64, 192, 192, bits=8) == "tile"
+    assert name(2, 32, 32, 8, 320) == "small-channel-count"
+    assert name(2, 32, 32, 200, 64, ksize=1) == "small-channel-count"
+    assert name(2, 32, 32, 12, 64) == "unsupported"
+    assert name(2, 32, 32, 72, 64, bits=8) == "unsupported"
 
 
 def test_status_strings(lib):
@@ -89,7 +93,8 @@ def test_linear_argument_errors(lib):
     assert f(P, None, P, P, None, 8, 8, 64, P, 0, None) == NULL    # scales needed for fp output
     assert f(P, P, P, P, None, 8, 8, 64, None, 0, None) == NULL
     assert f(P, P, P, P, None, 8, 8, 64, P, 5, None) == DTYPE
-    assert f(P, P, P, P, None, 8, 8, 32, P, 0, None) == SHAPE       # k not a multiple of 64
+    assert f(P, P, P, P, None, 8, 8, 36, P, 0, None) == SHAPE       # k not a multiple of 8
+    assert f(P, P, P, P, None, 8, 8, 4, P, 0, None) == SHAPE
     assert f(P, P, P, P, None, 8, 0, 64, P, 0, None) == SHAPE
     assert f(P, P, P, P, None, 0, 8, 64, P, 0, None) == SHAPE
     assert f(P, P, P, P, None, 8, 8, 131072, P, 0, None) == SHAPE   # 256 * acc would overflow
@@ -105,7 +110,8 @@ def test_conv_argument_errors(lib):
         ("dt", 0), ("stream", None)]]
     assert f(*args(xq=None)) == NULL
     assert f(*args(h=0)) == SHAPE
-    assert f(*args(cin=96)) == SHAPE
+    assert f(*args(cin=20)) == SHAPE                          # not a multiple of 8
+    assert f(*args(cin=96, stride=2)) == SHAPE               # the stride-2 form needs whole 64-code chunks
     assert f(*args(stride=3)) == UNSUPPORTED
     assert f(*args(stride=2, pad=0)) == UNSUPPORTED          # stride 2 is built for 3x3, pad 1 only
     assert f(*args(stride=2, r=1, s=1, pad=0)) == UNSUPPORTED
@@ -125,7 +131,7 @@ def test_static_scale_argument_errors(lib):
     assert q(P, 0, 8, 64, 64, 5, P, P, None) == BITS
     lin = lib.hq_int_linear_static
     assert lin(P, None, P, P, None, 8, 8, 64, P, 0, None) == NULL
-    assert lin(P, P, P, P, None, 8, 8, 32, P, 0, None) == SHAPE
+    assert lin(P, P, P, P, None, 8, 8, 12, P, 0, None) == SHAPE
     conv = lib.hq_int_conv2d_static
     args = lambda **kw: [kw.get(k, d) for k, d in [
         ("xq", P), ("sx", P), ("wq", P), ("sw", P), ("bias", None), ("nb", 1), ("h", 4), ("w", 4),
@@ -135,7 +141,7 @@ def test_static_scale_argument_errors(lib):
     assert conv(*args(stride=3)) == UNSUPPORTED
     assert conv(*args(stride=2, pad=0)) == UNSUPPORTED
     assert conv(*args(cin=14592)) == SHAPE      # 9 * 14592 codes in one sum: 256 * acc would overflow
-    assert conv(*args(cin=96)) == SHAPE
+    assert conv(*args(cin=20)) == SHAPE          # not a multiple of 8
 
 
 def test_single_scheme_argument_errors(lib):
@@ -174,7 +180,7 @@ def test_width_axis_argument_errors(lib):
     assert conv(*args(xu3=None)) == NULL
     assert conv(*args(sx=None)) == NULL
     assert conv(*args(block=16)) == SHAPE
-    assert conv(*args(cin=96)) == SHAPE
+    assert conv(*args(cin=20)) == SHAPE          # not a multiple of 8
     assert conv(*args(r=1, s=1, pad=0)) == UNSUPPORTED
     assert conv(*args(stride=2)) == UNSUPPORTED
 

@@ -726,6 +726,58 @@ def test_stride_2_downsampling_layers_full_size(hq, hw, c):
     assert np.array_equal(acc_g, acc_o)
 
 
+@pytest.mark.parametrize("k", [8, 40, 72, 200, 264])
+def test_channel_counts_that_are_not_multiples_of_64(hq, k):
+    """The integer stage for k a multiple of 8 but not of 64 (a layer with fewer channels than the
+    transform's order keeps H = I): linear, 1x1 and 3x3, ragged tiles, full-range codes; int32 sums
+    bit for bit (per tap, and the one sum of the static-scale calls), fp32 outputs to 1e-5."""
+    rng = np.random.default_rng(k)
+    m, n = 200 + k, 70
+    xq = rng.integers(-8, 8, (m, k)).astype(np.int8)
+    wq = rng.integers(-8, 8, (n, k)).astype(np.int8)
+    xq[0], wq[0] = -8, -8
+    sx = rng.uniform(0.01, 1.0, m).astype(np.float32)
+    sw = rng.uniform(0.001, 0.1, n).astype(np.float32)
+    bias = rng.standard_normal(n).astype(np.float32)
+    xq_d, wq_d = dev(pack_codes(xq)), dev(pack_codes(wq))
+    acc_o, y_o = oracle.int_linear(xq, sx, wq, sw, bias)
+    assert np.array_equal(host(hq.hq_int_linear(xq_d, None, wq_d, None, None, y_dtype=torch.int32)), acc_o)
+    check_y("y", host(hq.hq_int_linear(xq_d, dev(sx), wq_d, dev(sw), dev(bias), y_dtype=torch.float32)), y_o, rtol=1e-5)
+    s1 = torch.tensor([0.37], dtype=torch.float32, device="cuda")
+    _, y_o = oracle.int_linear_static(xq, 0.37, wq, sw, bias)
+    check_y("y (static)", host(hq.hq_int_linear_static(xq_d, s1, wq_d, dev(sw), dev(bias), y_dtype=torch.float32)),
+            y_o, rtol=1e-5)
+    for ks, (nb, h, w, cout) in ((3, (2, 9, 11, 70)), (1, (3, 5, 7, 33)), (3, (1, 1, 1, 8))):
+        xc = rng.integers(-8, 8, (nb, h, w, k)).astype(np.int8)
+        wc = rng.integers(-8, 8, (cout, ks, ks, k)).astype(np.int8)
+        sxc = rng.uniform(0.01, 1.0, (nb, h, w)).astype(np.float32)
+        swc = rng.uniform(0.001, 0.1, cout).astype(np.float32)
+        bc = rng.standard_normal(cout).astype(np.float32)
+        assert hq.hq_int_conv2d_kernel_name(nb, h, w, k, cout, ksize=ks) == "small-channel-count"
+        xc_d, wc_d = dev(pack_codes(xc)), dev(pack_codes(wc.reshape(cout, ks * ks, k)))
+        acc_o, y_o = oracle.int_conv2d(xc, sxc, wc, swc, bc, stride=1, pad=(ks - 1) // 2)
+        acc_g = host(hq.hq_int_conv2d(xc_d, None, wc_d, None, None, ksize=ks, y_dtype=torch.int32))
+        assert np.array_equal(acc_g, acc_o), "per-tap sums, %dx%d" % (ks, ks)
+        y_g = host(hq.hq_int_conv2d(xc_d, dev(sxc), wc_d, dev(swc), dev(bc), ksize=ks, y_dtype=torch.float32))
+        check_y("y conv", y_g, y_o, rtol=1e-5)
+        acc_g = host(hq.hq_int_conv2d_static(xc_d, None, wc_d, None, None, ksize=ks, y_dtype=torch.int32))
+        assert np.array_equal(acc_g, acc_o.sum(axis=3)), "one sum, %dx%d" % (ks, ks)
+        _, y_o = oracle.int_conv2d_static(xc, 0.37, wc, swc, bc, stride=1, pad=(ks - 1) // 2, want_acc=False)
+        y_g = host(hq.hq_int_conv2d_static(xc_d, s1, wc_d, dev(swc), dev(bc), ksize=ks, y_dtype=torch.float32))
+        check_y("y conv (static)", y_g, y_o, rtol=1e-5)
+
+
+def test_bypass_layer_end_to_end(hq):
+    """A convolution on an 8-channel input (fewer channels than the transform's order: H = I,
+    had_block = 1) through both calls of the layer, with the three layers of checks."""
+    import dataclasses
+    layer = dataclasses.replace(workloads.tiny_layers()[3], name="t_conv3_8ch", x_shape=(2, 19, 23, 8), n_out=200)
+    run_layer(hq, layer, block=1)
+    run_layer_static(hq, layer, block=1)
+    layer = dataclasses.replace(workloads.tiny_layers()[0], name="t_lin_40", x_shape=(301, 40), n_out=96)
+    run_layer(hq, layer, block=8)
+
+
 def _random_bytes(shape, seed):
     g = torch.Generator(device="cuda")
     g.manual_seed(seed)
