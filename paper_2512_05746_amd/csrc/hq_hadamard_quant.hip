@@ -14,6 +14,7 @@
 #include <hip/hip_fp16.h>
 
 #include "hq_common.h"
+#include "hq_hadamard_mfma.h"
 
 namespace {
 
@@ -268,29 +269,6 @@ __global__ __launch_bounds__(kThreads) void rowquant_large(const T *__restrict__
 // float's bit pattern.  Eight such patterns are merged by w = (w << 4) + m; the known
 // constant contributed by the upper bits is subtracted and the offset removed by
 // xor 0x88888888, which yields the eight two's-complement nibbles.
-typedef _Float16 v8h __attribute__((ext_vector_type(8)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-
-constexpr float kMagic = 12582920.0f;                                 // 1.5 * 2^23 + 8
-constexpr uint32_t kMagicSum = 0x4B400000u * 0x11111111u;             // sum_i 0x4B400000 << 4i (mod 2^32)
-constexpr int kMaxBlocks = 16;                                        // 64-channel blocks per row
-
-__device__ __forceinline__ uint32_t pack8_magic(const float *v, float inv) {
-    uint32_t w = __float_as_uint(__builtin_fmaf(v[7], inv, kMagic));
-#pragma unroll
-    for (int i = 6; i >= 0; --i) w = (w << 4) + __float_as_uint(__builtin_fmaf(v[i], inv, kMagic));
-    return (w - kMagicSum) ^ 0x88888888u;
-}
-
-// The same with the clamp of a given scale: v is limited to [lo, hi] = [qmin / inv, qmax / inv]
-// first (rounding is monotonic and the limits are integers, so clamp and round commute).
-__device__ __forceinline__ uint32_t pack8_magic_clamped(const float *v, float inv, float lo, float hi) {
-    float c[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) c[i] = fminf(fmaxf(v[i], lo), hi);
-    return pack8_magic(c, inv);
-}
-
 // STATIC: the scale is given (one for the tensor): no abs-max, clamp active, no scale output;
 // `given` points to it.  NBLK: 64-channel blocks per row.  Four waves (token groups) per workgroup.
 template <int NBLK, bool STATIC>
@@ -322,25 +300,7 @@ __global__ __launch_bounds__(256) void hadamard64_quant_f16(const __half *__rest
     // K slice: the bits of e (0..2) and of 32 h + 8 q' (3..5) do not overlap, so the sign is
     // (pattern over e from c & 7) xor (one bit from c & (32 h + 8 q')).
     v8h hmat[4][2];
-    {
-        const int i = lane & 15;
-#pragma unroll
-        for (int ct = 0; ct < 4; ++ct) {
-            const int c = 16 * (i >> 2) + 4 * ct + (i & 3);
-            uint32_t pat[4];
-#pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) {
-                const uint32_t s0 = __popc(c & (2 * e2)) & 1, s1 = __popc(c & (2 * e2 + 1)) & 1;
-                pat[e2] = 0x3C003C00u ^ (s0 << 15) ^ (s1 << 31);   // +-1.0 in fp16
-            }
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const uint32_t flip = (__popc(c & (32 * h + 8 * q)) & 1) ? 0x80008000u : 0u;
-                const uint4 w = uint4{pat[0] ^ flip, pat[1] ^ flip, pat[2] ^ flip, pat[3] ^ flip};
-                hmat[ct][h] = __builtin_bit_cast(v8h, w);
-            }
-        }
-    }
+    hadamard64_operands(lane, hmat);
     // the 16 sums of this lane for one block: 8 x the orthonormal transform
     auto transform = [&](int blk, float (&v)[16]) {
 #pragma unroll
@@ -415,25 +375,7 @@ __global__ __launch_bounds__(64 * kMaxBlocks) void hadamard64_quant_split_f16(co
     // K slice: the bits of e (0..2) and of 32 h + 8 q' (3..5) do not overlap, so the sign is
     // (pattern over e from c & 7) xor (one bit from c & (32 h + 8 q')).
     v8h hmat[4][2];
-    {
-        const int i = lane & 15;
-#pragma unroll
-        for (int ct = 0; ct < 4; ++ct) {
-            const int c = 16 * (i >> 2) + 4 * ct + (i & 3);
-            uint32_t pat[4];
-#pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) {
-                const uint32_t s0 = __popc(c & (2 * e2)) & 1, s1 = __popc(c & (2 * e2 + 1)) & 1;
-                pat[e2] = 0x3C003C00u ^ (s0 << 15) ^ (s1 << 31);   // +-1.0 in fp16
-            }
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const uint32_t flip = (__popc(c & (32 * h + 8 * q)) & 1) ? 0x80008000u : 0u;
-                const uint4 w = uint4{pat[0] ^ flip, pat[1] ^ flip, pat[2] ^ flip, pat[3] ^ flip};
-                hmat[ct][h] = __builtin_bit_cast(v8h, w);
-            }
-        }
-    }
+    hadamard64_operands(lane, hmat);
 
     const int64_t groups = (m + 15) >> 4;
     auto fetch = [&](int64_t grp, v8h (&b)[2]) {
