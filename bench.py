@@ -219,6 +219,40 @@ def main():
             "quant_frac_hbm_peak": round(q_bytes / quant_us[i] / 1e3 / HBM_PEAK_GBS, 4),
             "rotating_buffer_sets": rot_sets[i],
         })
+    # ---- the 3x3 layers in ONE launch: transform, quantisation, integer convolution and epilogue, the
+    # codes never leaving the chip (hq_act_quant_int_conv2d), with the same buffer rotation -------------
+    fused_layers = []
+    for i, s in enumerate(state):
+        layer, x, wq, sw = s[:4]
+        if not (layer.kind == "conv" and layer.ksize == 3):
+            continue
+
+        def run_fused(r, layer=layer):
+            hq.hq_act_quant_int_conv2d(r[1], r[2], r[3], None, a_bits=layer.a_bits, y_dtype=torch.float16, out=r[6])
+
+        try:
+            run_fused(s)
+        except hq.HqError:
+            fused_layers.append({"layer": layer.name, "built": False})
+            continue
+        one = x.numel() * 2 + s[6].numel() * 2
+        n_sets = max(2, -(-ROTATE_BYTES // one))
+        rot = [s, state_b[i]]
+        while len(rot) < n_sets:
+            x2 = x.clone()
+            rot.append((layer, x2, wq, sw) + new_buffers(layer, x2))
+        f_us = batched_us(run_fused, rot)
+        del rot
+        io_bytes = x.numel() * 2 + s[6].numel() * 2 + wq.numel()
+        fused_layers.append({"layer": layer.name, "built": True, "fused_us": round(f_us, 2),
+                             "two_calls_us": round(float(quant_us[i] + int_us[i]), 2),
+                             "tops": round(layer.ops / f_us / 1e6, 1),
+                             "frac_mfma_peak": round(layer.ops / f_us / 1e6 / INT8_MFMA_PEAK_TOPS, 4),
+                             "fp16_in_out_and_weight_bytes": io_bytes,
+                             "gbs": round(io_bytes / f_us / 1e3, 1),
+                             "frac_hbm_peak": round(io_bytes / f_us / 1e3 / HBM_PEAK_GBS, 4)})
+    torch.cuda.synchronize()
+
     # ---- the same layers with ONE static activation scale (the paper's learned per-timestep
     # scale): no abs-max pass, and a 3x3 convolution keeps one integer sum over all taps ------
     static_layers = []
@@ -464,6 +498,13 @@ def main():
                          "frac_hbm_peak": round(8 * q_bytes / hq_us_large / 1e3 / HBM_PEAK_GBS, 4)},
         },
         "layers": per_layer,
+        "fused_mode": {
+            "what": "the 3x3 layers through hq_act_quant_int_conv2d (one launch per layer: block Hadamard + "
+                    "per-pixel quantisation of the fp16 tile inside the convolution kernel, codes never written "
+                    "to memory) against the two calls of the timed step; bytes = fp16 in + fp16 out + weight codes; "
+                    "not part of `value`",
+            "layers": fused_layers,
+        },
         "static_scale_mode": {
             "what": "the same sweep through hq_*_static (one caller-supplied activation scale per tensor); "
                     "not part of `value`",

@@ -145,6 +145,28 @@ hq_status hq_int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *
                         void *y, hq_dtype y_dtype, void *stream);
 
 /*
+ * The whole layer in one launch (3x3 convolution): hq_act_hadamard_quant followed by
+ * hq_int_conv2d, with the activation codes kept on chip.  (Method, "Matrix Multiplication": the
+ * transformed activations X H are only ever consumed by the integer product; Method,
+ * "Convolution".)  Every workgroup transforms and quantises the rows of its own pixel tile and of
+ * the pixels one image row and one pixel either side of it, with the arithmetic of
+ * hq_act_hadamard_quant, so codes, scales and results are those of the two calls in sequence.
+ *
+ *   x        [nb, h, w, c_in] of x_dtype; wq [c_out, 3, 3, c_in/2], w_scale [c_out], bias [c_out] of
+ *            y_dtype or NULL, y [nb, h, w, c_out] (y_dtype == HQ_I32: per-tap sums [nb, h, w, 9, c_out]).
+ *   xq_out   NULL, or out [nb, h, w, c_in/2]: the activation codes the kernel used (for inspection).
+ *   x_scale_out  NULL, or out [nb, h, w] fp32: the scales it used.
+ *   Built: x_dtype HQ_F16, had_block 64, a_bits 2..4, R = S = 3, stride 1, pad 1, c_in a multiple of
+ *   192 and small enough for a tile's activations to fit on chip (c_in <= 576 for 16-pixel-wide images,
+ *   fewer channels for wider ones); anything else returns HQ_ERR_UNSUPPORTED (use the two calls).
+ */
+hq_status hq_act_quant_int_conv2d(const void *x, hq_dtype x_dtype, const uint8_t *wq,
+                                  const float *w_scale, const void *bias, int nb, int h, int w,
+                                  int c_in, int c_out, int r, int s, int stride, int pad,
+                                  int had_block, int a_bits, void *y, hq_dtype y_dtype,
+                                  uint8_t *xq_out, float *x_scale_out, void *stream);
+
+/*
  * Diagnostic: the kernel family that hq_int_conv2d (static_scale = 0) or hq_int_conv2d_static
  * (static_scale = 1) runs for a convolution of this geometry on the current device, for 4-bit
  * (bits = 4) or 8-bit (bits = 8, hq_int_conv2d_i8) codes.  The choice depends on the geometry

@@ -23,7 +23,8 @@ SYMBOLS = ("hq_status_string", "hq_quantize_weights", "hq_act_hadamard_quant",
            "hq_int_linear_static", "hq_int_conv2d_static",
            "hq_quantize_weights_single", "hq_int_linear_single",
            "hq_act_hadamard_quant_width", "hq_int_conv2d_width",
-           "hq_int_linear_i8", "hq_int_conv2d_i8", "hq_act_hadamard_quant_i8")
+           "hq_int_linear_i8", "hq_int_conv2d_i8", "hq_act_hadamard_quant_i8",
+           "hq_act_quant_int_conv2d")
 # entry points that do not return a status
 INFO_SYMBOLS = ("hq_int_conv2d_kernel_name",)
 
@@ -65,6 +66,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.hq_int_linear_i8.argtypes = lib.hq_int_linear.argtypes
     lib.hq_act_hadamard_quant_i8.argtypes = lib.hq_act_hadamard_quant.argtypes
     lib.hq_int_conv2d_i8.argtypes = lib.hq_int_conv2d.argtypes
+    lib.hq_act_quant_int_conv2d.argtypes = [vp, i32, vp, vp, vp] + [i32] * 11 + [vp, i32, vp, vp, vp]
     for name in SYMBOLS[1:]:
         getattr(lib, name).restype = i32
     lib.hq_int_conv2d_kernel_name.argtypes = [i32] * 11
@@ -219,6 +221,36 @@ def hq_int_conv2d(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torch.T
     _check("hq_int_conv2d", load_library().hq_int_conv2d(
         _ptr(xq), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), nb, h, w, cb * 2, cout,
         ksize, ksize, stride, pad, _ptr(y), _DTYPES[y_dtype], _stream()))
+    return y
+
+
+def hq_act_quant_int_conv2d(x: torch.Tensor, wq: torch.Tensor, w_scale: Optional[torch.Tensor],
+                            bias: Optional[torch.Tensor] = None, had_block: int = 64, a_bits: int = 4,
+                            ksize: int = 3, stride: int = 1, pad: Optional[int] = None,
+                            y_dtype: torch.dtype = torch.float16, out: Optional[torch.Tensor] = None,
+                            codes_out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None) -> torch.Tensor:
+    """The whole 3x3 layer in one launch: x [nb, h, w, cin] fp16, wq [cout, 9, cin/2] -> y [nb, h, w, cout]
+    (y_dtype int32: per-tap sums [nb, h, w, 9, cout]).  codes_out = (xq uint8 [nb, h, w, cin/2],
+    x_scale fp32 [nb, h, w]) receives the codes and scales the kernel used."""
+    _dev(x, "x"), _codes(wq, torch.uint8, "wq")
+    nb, h, w, cin = x.shape
+    cout = wq.shape[0]
+    if wq.numel() != cout * ksize * ksize * (cin // 2):
+        raise ValueError("wq does not match x / ksize")
+    _vec(w_scale, cout, torch.float32, "w_scale"), _vec(bias, cout, y_dtype, "bias")
+    pad = (ksize - 1) // 2 if pad is None else pad
+    ho, wo = _conv_out(h, w, ksize, stride, pad)
+    if y_dtype == torch.int32:
+        y = _out(out, (nb, ho, wo, ksize * ksize, cout), y_dtype, x.device)
+    else:
+        y = _out(out, (nb, ho, wo, cout), y_dtype, x.device)
+    xq = sx = None
+    if codes_out is not None:
+        xq = _out(codes_out[0], (nb, h, w, cin // 2), torch.uint8, x.device)
+        sx = _out(codes_out[1], (nb, h, w), torch.float32, x.device)
+    _check("hq_act_quant_int_conv2d", load_library().hq_act_quant_int_conv2d(
+        _ptr(x), _DTYPES[x.dtype], _ptr(wq), _ptr(w_scale), _ptr(bias), nb, h, w, cin, cout, ksize, ksize,
+        stride, pad, had_block, a_bits, _ptr(y), _DTYPES[y_dtype], _ptr(xq), _ptr(sx), _stream()))
     return y
 
 

@@ -1,677 +1,14 @@
-// 3x3 / stride 1 / pad 1 NHWC convolution with per-pixel activation scales on int8 MFMA, one
-// workgroup of eight waves per CU, the activation tile expanded to int8 ONCE and resident in LDS
-// (Method, "Convolution": one integer sum per tap, taps combined in fp32 with the scale of the
-// input pixel under the tap).
-//
-// Why another kernel.  Three things held the other 3x3 kernels below a third of the int8 rate on
-// the UNet's layers: (1) tile counts that do not divide the machine (768 tiles for 512 resident
-// workgroups, 576 for 256 CUs), (2) every wave expanding the packed nibbles of BOTH operands for
-// every use, nine times for an activation row, and (3) operand streams of 250..500 bytes per MFMA
-// through a copy path that delivers about 170.  Here
-//   - a workgroup owns 192 output channels x PX pixels (PX = 256, 128 or 64, chosen on the host so
-//     that the layer has about one tile per CU), i.e. 12, 6 or 3 wave tiles of 64 x 64 for eight
-//     waves: the work is dealt out in two PHASES, and where a phase has fewer wave tiles than
-//     waves a tile's K range (its 9 x C_in/192 "units" of one tap and one 192-channel slice) is
-//     split over 2, 4 or 8 waves, whose partial fp32 sums meet in LDS in a fixed order:
-//         phase A: channels 0..127   as 2 x PX/64 wave tiles, each split 4 / (PX/64) ways in K,
-//         phase B: channels 128..191 as 1 x PX/64 wave tiles, each split 8 / (PX/64) ways in K,
-//     so every wave multiplies 1.5 / 0.75 / 0.375 tiles' worth of units, all waves the same amount;
-//   - the activation rows of the tile's pixels plus W + 1 pixels either side are fetched once (all
-//     input channels), expanded to int8 (16 x code) on the way into LDS, and all nine taps of all
-//     phases read them at shifted addresses: an activation operand is an LDS read, nothing else;
-//   - only the weights stream (direct-to-LDS loads, packed, two or three stages of one unit per K
-//     group), 64..128 bytes per MFMA; a wave expands the weight nibbles it reads (three vector
-//     instructions per MFMA in the 2 x 2 register tile).
-// The sums of one unit are folded into the fp32 result with one fma per element: the integer
-// accumulators start from the bit pattern of 1.5 * 2^23, so their bits read as a float are
-// 1.5 * 2^23 + S exactly (S = 256 * sum, |S| < 2^22 for 192 codes), and the fp32 sums start from
-// minus the known surplus.
-//
-// Integer output (HQ_I32): the same loads, stages, phases and MFMAs; instead of the fold every
-// wave adds the exact sums of its units to the zero-filled [pixel, tap, n] output with integer
-// atomics (integer addition is exact in any order).
-#include "hq_int_gemm_kernel.h"
+// Launcher of the 3x3 convolution with the int8 activation tile resident in LDS (the kernel and the
+// choice of its configuration are in hq_conv3x3_res_kernel.h), for activations that arrive as codes.
+#include "hq_conv3x3_res_kernel.h"
 
-namespace {
-
-// LDS of a workgroup: all of a CU's 160 KiB for eight waves (one workgroup per CU), half of it for
-// four waves (two workgroups per CU, each with its own barrier, so that one multiplies while the
-// other folds, waits or synchronises)
-constexpr int res_lds(int nwl) { return nwl == 3 ? 163840 : 81920; }
-constexpr int kResBlock = 64 * 96;   // weight rows of one 64-channel block of one unit (packed)
-constexpr int kRes4WaveCost = 85;    // percent: time of the four-wave form relative to the eight-wave form
-
-struct ResArgs {
-    const uint8_t *xq;   // [pixels, k/2]
-    const float *sx;     // [pixels]
-    const uint8_t *wq;   // [n, 9, k/2]
-    const float *sw;     // [n]
-    const void *bias;    // [n] of the output dtype, or null
-    void *y;             // [pixels, n]; integer output: [pixels, 9, n], zero-filled before the launch
-    uint32_t pixels;
-    int n, k, h, w;
-    uint32_t w_magic, w_shift, h_magic, h_shift;   // exact division of a pixel index by w and by h
-    uint32_t s_magic, s_shift;                     // ... of a unit index by the number of slices
-    uint32_t p_magic, p_shift;                     // ... of a piece index by the 16-byte pieces per activation row
-    int pg_log2;         // PX = 64 << pg_log2
-    int slices;          // k / 192
-    uint32_t n_co_tiles, n_tiles;
-    uint32_t stage_base, stage_bytes, tab_base;    // LDS layout: activations at 0, then stages, then tables
-};
-
-// chunk c (0..15) of a wave's 64 x 64 partial result = sub-tile c / 4 (tm * 2 + tn), registers 4 (c % 4) .. + 3;
-// among the KG waves that share a tile, wave c % KG finishes chunk c.  A wave stores the chunks it
-// does not finish compactly: chunk c of wave kg sits at position c - (chunks below c that kg finishes).
-__device__ __forceinline__ int exchange_pos(int c, int kg, int kgn_log2) {
-    return c - ((c + (1 << kgn_log2) - 1 - kg) >> kgn_log2);
-}
-
-// PGL: log2 of the pixel blocks of 64 per tile (the tile has 64 << PGL pixels)
-// weight stages of a tile of 64 << pgl pixels of a workgroup of 1 << nwl waves (a stage is
-// (1 << nwl) >> pgl blocks of 6 KiB)
-constexpr int res_stages(int pgl, int nwl) { return nwl == 3 ? (pgl == 0 ? 2 : 3) : 2; }
-
-// NWL: log2 of the waves per workgroup (3 or 2).  The K ranges are split (waves / 2) / pgn ways in
-// phase A and waves / pgn ways in phase B.
-template <int OUT, int PGL, int NWL>
-__global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kernel(ResArgs a) {
-    constexpr int NT = 64 << NWL;
-    constexpr int kResLds = res_lds(NWL);
-    static_assert(NWL - 1 - PGL >= 0, "at least one wave per tile in phase A");
-    constexpr bool INT_OUT = OUT == kOutI32;
-    constexpr int TM = 2, TN = 2, TAPS = 9, MAXL = (6 + (1 << PGL) - 1) >> PGL;
-    constexpr int NSTAGE = res_stages(PGL, NWL);
-    constexpr int kBiasBits = 0x4B400000;
-    constexpr float kBias = 12582912.0f;
-    using Out = typename OutT<OUT>::type;
-    using Ops = Packed<TM, 2 * TN>;   // b[2 * tn + m]: int8 operand of pixel block tn, MFMA m of the step
-
-    __shared__ __attribute__((aligned(16))) uint8_t lds[kResLds];
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int lrow = lane & 31, lhalf = lane >> 5;
-    const int kbytes = a.k >> 1;
-    const int S = a.slices;
-    const int NU = TAPS * S;
-    constexpr int pgn_log2 = PGL, pgn = 1 << pgn_log2, PX = 64 << pgn_log2;
-    const int halo = a.w + 1;
-    const int rows = PX + 2 * halo;
-    const uint32_t last = a.pixels - 1;
-
-    // tables (at the top of the LDS): scale of the input pixel under tap t for every pixel of the tile,
-    // tap masks, scales and bias of the tile's 192 channels
-    float *s_sx = reinterpret_cast<float *>(lds + a.tab_base);            // [9][PX], x_scale / 256, 0 outside
-    int *s_mask = reinterpret_cast<int *>(s_sx + TAPS * PX);              // [PX]
-    float *s_sw = reinterpret_cast<float *>(s_mask + PX);                 // [192]
-    float *s_bias = s_sw + 192;                                           // [192]
-
-    // ---- tile of this workgroup (XCD-contiguous: workgroup b runs on XCD b % 8) ------------------
-    uint32_t tile = blockIdx.x;
-    if (gridDim.x % 8 == 0) tile = (blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8;
-    const int co0 = static_cast<int>(tile % a.n_co_tiles) * 192;
-    const uint32_t p0 = (tile / a.n_co_tiles) * PX;
-
-    // ---- phases ------------------------------------------------------------------------------------
-    // phase 0: channel blocks 0, 1; K groups 4 / pgn.  phase 1: channel block 2; K groups 8 / pgn.
-    // In both phases wave wv works on block wv / pgn of a stage (K group major, then channel block) and
-    // the pgn waves of a block (its pixel blocks) fetch that block's weight rows together.
-    const int blk = wv >> pgn_log2;           // this wave's block of a stage
-    const int ws = wv & (pgn - 1);            // its pixel block = its index among the waves of the block
-    auto unit_first = [&](int kg, int kgn_log2) { return (kg * NU) >> kgn_log2; };
-
-    // ---- weight stream -------------------------------------------------------------------------------
-    // A block of a stage is the row-major [64 rows][6 pieces of 16 bytes] image of 64 weight rows of one
-    // unit: six wave-wide loads of 1 KiB (load r covers slots q = 64 r + lane: row q / 6, piece q % 6),
-    // adjacent pieces swapped in rows 8..15 (mod 16) against bank conflicts of the operand reads.  Wave
-    // ws of the block issues loads r = ws, ws + pgn, ... < 6.
-    uint32_t ld_off[MAXL];     // per lane: byte offset of the piece inside the weight tensor at tap 0, slice 0
-    int f_unit = 0, f_slice = 0, f_stage = 0, f_issued = 0;
-    uint32_t f_off = 0;        // uniform: tap * kbytes + slice * 96 of the unit fetched next
-    auto begin_fetch = [&](int phase, bool continuing) {
-        const int kl = phase == 0 ? NWL - 1 - pgn_log2 : NWL - pgn_log2;
-        const int cblock = phase == 0 ? (blk & 1) : 2;
-        const int kg = phase == 0 ? blk >> 1 : blk;
-#pragma unroll
-        for (int j = 0; j < MAXL; ++j) {
-            const int r = ws + (j << pgn_log2);
-            const int q = 64 * r + lane, row = q / 6, piece = (q - 6 * row) ^ ((row >> 3) & 1);
-            int co = co0 + 64 * cblock + (row & ~31) + tile_row_to_channel(row & 31);
-            co = co < a.n ? co : a.n - 1;
-            ld_off[j] = static_cast<uint32_t>(co) * TAPS * kbytes + piece * 16;
-        }
-        f_unit = unit_first(kg, kl);
-        const int tap = static_cast<int>(hq::div_magic31(static_cast<uint32_t>(f_unit), S, a.s_magic, a.s_shift));
-        f_slice = f_unit - tap * S;
-        f_off = static_cast<uint32_t>(tap) * kbytes + f_slice * 96;
-        if (!continuing) f_stage = 0;   // a stream that runs on keeps rotating through the stages
-        f_issued = 0;
-    };
-    // requests the next unit of this wave's block (a K group that has run out of its own units goes on
-    // into the following ones, which are not used; the last unit of the tensor is repeated)
-    auto issue_step = [&]() {
-        uint8_t *image = lds + a.stage_base + f_stage * a.stage_bytes + blk * kResBlock;
-        const uint8_t *src = a.wq + f_off;
-#pragma unroll
-        for (int j = 0; j < MAXL; ++j) {
-            const int r = ws + (j << pgn_log2);
-            if (r < 6) load_to_lds16(src + ld_off[j], image + r * 1024);
-        }
-        if (f_unit + 1 < NU) {
-            ++f_unit;
-            f_off += 96;
-            if (++f_slice == S) { f_slice = 0; f_off += kbytes - 96 * S; }
-        }
-        f_stage = f_stage + 1 == NSTAGE ? 0 : f_stage + 1;
-        ++f_issued;
-    };
-    // waits until this wave's loads of all steps but the youngest have landed
-    auto wait_all_but_one_step = [&]() {
-        if constexpr (INT_OUT || NSTAGE == 2) wait_vmem<0>();   // (integer output: other memory operations in between)
-        else if constexpr (PGL == 0) wait_vmem<6>();
-        else if constexpr (PGL == 1) wait_vmem<3>();
-        else if (ws < 2) wait_vmem<2>();
-        else wait_vmem<1>();
-    };
-    constexpr int kla = NWL - 1 - pgn_log2, klb = NWL - pgn_log2;   // log2 of the K groups of the two phases
-    const int ulen_of[2] = {(NU + (1 << kla) - 1) >> kla, (NU + (1 << klb) - 1) >> klb};
-    begin_fetch(0, false);
-    for (int st = 0; st < NSTAGE - 1 && st < ulen_of[0]; ++st) issue_step();
-
-    // ---- activation tile: packed rows -> int8 (16 x code) in LDS -------------------------------------
-    // Row r of the image is pixel p0 - halo + r (clamped into the tensor; rows outside the image are
-    // only ever read under taps whose scale is 0).  Plane s (192-channel slice) at s * rows * 192; a row
-    // is three 64-byte K steps of four 16-byte pieces [MFMA 0 / lane half 0, 0 / 1, 1 / 0, 1 / 1], the
-    // piece index xor-ed with (row / 4) % 4 so that the operand reads of 16 consecutive rows hit 16
-    // different bank groups (row stride 192 bytes = 12 groups).
-    {
-        const uint32_t pieces_per_row = 6u * S;
-        const uint32_t total = static_cast<uint32_t>(rows) * pieces_per_row;
-        const int64_t first = static_cast<int64_t>(p0) - halo;
-        for (uint32_t base = tid; base < total; base += NT * 5) {
-            v4i p[5];
-            uint32_t dst[5];
-#pragma unroll
-            for (int e = 0; e < 5; ++e) {
-                const uint32_t q = base + NT * e;
-                if (q < total) {
-                    const uint32_t row = hq::div_magic31(q, pieces_per_row, a.p_magic, a.p_shift);
-                    const uint32_t rem = q - row * pieces_per_row;
-                    int64_t pix = first + row;
-                    pix = pix < 0 ? 0 : (pix > static_cast<int64_t>(last) ? last : pix);
-                    p[e] = *reinterpret_cast<const v4i *>(a.xq + static_cast<uint64_t>(pix) * kbytes + rem * 16);
-                    const uint32_t slice = rem / 6, pc = rem - slice * 6;
-                    const uint32_t sw = (row >> 2) & 3;
-                    // piece index of (MFMA 0, lane half pc & 1); MFMA 1 is that index xor 2
-                    dst[e] = (slice * rows + row) * 192 + (pc >> 1) * 64 + (((pc & 1) ^ sw) * 16);
-                }
-            }
-#pragma unroll
-            for (int e = 0; e < 5; ++e) {
-                const uint32_t q = base + NT * e;
-                if (q < total) {
-                    v4i first_half, second_half;
-                    expand(p[e], first_half, second_half);
-                    *reinterpret_cast<v4i *>(lds + dst[e]) = first_half;
-                    *reinterpret_cast<v4i *>(lds + (dst[e] ^ 32)) = second_half;
-                }
-            }
-        }
-    }
-
-    // ---- tables ------------------------------------------------------------------------------------------
-    if (tid < PX) {
-        const uint32_t pix = p0 + tid;
-        const uint32_t q = hq::div_magic31(pix, a.w, a.w_magic, a.w_shift);
-        const int ow = static_cast<int>(pix - q * a.w);
-        const int oh = static_cast<int>(q - hq::div_magic31(q, a.h, a.h_magic, a.h_shift) * a.h);
-        const int cm = (ow > 0 ? 1 : 0) | 2 | (ow + 1 < a.w ? 4 : 0);
-        int mask = (oh > 0 ? cm : 0) | (cm << 3) | (oh + 1 < a.h ? cm << 6 : 0);
-        if (pix >= a.pixels) mask = 0;
-        s_mask[tid] = mask;
-        if constexpr (!INT_OUT) {
-            float v[TAPS];
-#pragma unroll
-            for (int t = 0; t < TAPS; ++t) {
-                uint32_t ip = pix + static_cast<uint32_t>((t / 3 - 1) * a.w + (t % 3 - 1));   // wraps below 0
-                ip = ip < last ? ip : last;
-                v[t] = a.sx[ip];
-            }
-#pragma unroll
-            for (int t = 0; t < TAPS; ++t) s_sx[t * PX + tid] = ((mask >> t) & 1) ? v[t] * (1.0f / 256.0f) : 0.f;
-        }
-    }
-    if constexpr (!INT_OUT) {
-        for (int c = NT - 1 - tid; c < 192; c += NT) {   // (the last threads first: they have no pixel to look up)
-            const bool ok = co0 + c < a.n;
-            const Out *bias = static_cast<const Out *>(a.bias);
-            s_sw[c] = ok ? a.sw[co0 + c] : 0.f;
-            s_bias[c] = ok && bias ? to_float(bias[co0 + c]) : 0.f;
-        }
-    }
-    __syncthreads();   // activations and tables visible (also waits for this wave's first weight loads)
-
-    const uint32_t lds_base = lds_address(lds);
-    const uint32_t lds_tab = lds_base + a.tab_base;
-    const uint32_t a_lane = lrow * 96 + (lhalf ^ ((lrow >> 3) & 1)) * 16;
-
-    v16i acc_start;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc_start[r] = INT_OUT ? 0 : kBiasBits;
-    asm volatile("" : "+v"(acc_start));   // kept in registers, not rebuilt per unit
-
-    // Steps of the phase about to start whose stages have landed and are visible to every wave (the
-    // phase's first loads are always waited for, and a barrier passed, before the phase starts).
-    int pre_landed = f_issued;
-    int r_stage = 0;           // stage of the unit multiplied next
-    auto run_phase = [&](auto PHASE) {
-        constexpr int phase = decltype(PHASE)::value;
-        constexpr int kl = phase == 0 ? kla : klb, kgn = 1 << kl;
-        constexpr bool whole = kgn == 1;   // one wave per tile: no exchange
-        const int ulen = ulen_of[phase];
-        // this wave in this phase: pixel block ws, channel block cblock, K group kg
-        const int cblock = phase == 0 ? (blk & 1) : 2;
-        const int kg = phase == 0 ? blk >> 1 : blk;
-        const int u0 = unit_first(kg, kl), u1 = unit_first(kg + 1, kl);
-        const int cb = co0 + 64 * cblock;                            // first channel of this wave's tile
-        const int px = ws * 64;                                      // first pixel (local) of this wave's tile
-        const bool exists = cb < a.n && p0 + px < a.pixels;          // else: nothing to multiply or store
-
-        v16i acc[TM][TN];
-        float facc[INT_OUT ? 1 : TM][INT_OUT ? 1 : TN][16];
-        int my_mask[TN];
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn) my_mask[tn] = s_mask[px + tn * 32 + lrow];
-        if constexpr (!INT_OUT) {
-            // fp32 sums start from minus the surplus of the units this wave folds: tap t counts
-            // |[u0, u1) intersected with [t S, (t + 1) S)| times
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-                float total = 0.f;
-#pragma unroll
-                for (int t = 0; t < TAPS; ++t) {
-                    const int lo = u0 > t * S ? u0 : t * S, hi = u1 < (t + 1) * S ? u1 : (t + 1) * S;
-                    const float cnt = hi > lo ? static_cast<float>(hi - lo) : 0.f;
-                    total = __builtin_fmaf(cnt, s_sx[t * PX + px + tn * 32 + lrow], total);
-                }
-                const float f0 = -kBias * total;
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) facc[tm][tn][r] = f0;
-            }
-        }
-
-        auto multiply = [&](Ops &o, bool first) {
-            v4i a0[TM], a1[TM];
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm) { pin(o.a[tm]); expand(o.a[tm], a0[tm], a1[tm]); }
-#pragma unroll
-            for (int i = 0; i < 2 * TN; ++i) pin(o.b[i]);
-            if (first) {
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                    for (int tn = 0; tn < TN; ++tn)
-                        acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[tm], o.b[2 * tn], acc_start, 0, 0, 0);
-            } else {
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                    for (int tn = 0; tn < TN; ++tn)
-                        acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[tm], o.b[2 * tn], acc[tm][tn], 0, 0, 0);
-            }
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[tm], o.b[2 * tn + 1], acc[tm][tn], 0, 0, 0);
-        };
-
-        // operand addresses of a unit: weights in the stage, int8 rows of this lane's pixels under the
-        // unit's tap in the unit's slice plane
-        uint32_t addr_a = 0, addr_b0[TN] = {0, 0}, addr_b1[TN] = {0, 0};
-        int r_tap = static_cast<int>(hq::div_magic31(static_cast<uint32_t>(u0), S, a.s_magic, a.s_shift));
-        int r_slice = u0 - r_tap * S;
-        int r_dpix = (r_tap / 3 - 1) * a.w + (r_tap % 3 - 1);   // pixels from an output pixel to the one under the tap
-        auto set_addresses = [&]() {
-            const int dpix = r_dpix;
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-                const int row = halo + px + tn * 32 + lrow + dpix;     // in [0, rows)
-                const uint32_t rowaddr = lds_base + (r_slice * rows + row) * 192;
-                const uint32_t o0 = (lhalf ^ ((row >> 2) & 3)) * 16;
-                addr_b0[tn] = rowaddr + o0;
-                addr_b1[tn] = rowaddr + (o0 ^ 32);
-            }
-            addr_a = lds_base + a.stage_base + r_stage * a.stage_bytes + blk * kResBlock + a_lane;
-        };
-        auto read_step = [&](Ops &o, auto KS) {
-            constexpr int ks = decltype(KS)::value;     // K step of 64 codes
-            lds_read16<ks * 32>(o.a[0], addr_a);
-            lds_read16<32 * 96 + ks * 32>(o.a[1], addr_a);
-            lds_read16<ks * 64>(o.b[0], addr_b0[0]);
-            lds_read16<ks * 64>(o.b[2], addr_b0[1]);
-            lds_read16<ks * 64>(o.b[1], addr_b1[0]);
-            lds_read16<ks * 64>(o.b[3], addr_b1[1]);
-        };
-
-        auto fold = [&](int tap, const float (&s)[TN]) {
-            if constexpr (INT_OUT) {
-                // the exact sums of the unit, added to the zero-filled output
-                int *yi = static_cast<int *>(a.y);
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn) {
-                    const uint32_t pix = p0 + px + tn * 32 + lrow;
-                    if (pix >= a.pixels || !((my_mask[tn] >> tap) & 1)) continue;
-#pragma unroll
-                    for (int tm = 0; tm < TM; ++tm) {
-                        const int cbase = cb + tm * 32 + 16 * lhalf;
-                        int *dst = yi + (static_cast<int64_t>(pix) * TAPS + tap) * a.n + cbase;
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            if (cbase + r < a.n) atomicAdd(dst + r, acc[tm][tn][r] >> 8);
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-                    for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            facc[tm][tn][r] = __builtin_fmaf(s[tn], __int_as_float(acc[tm][tn][r]), facc[tm][tn][r]);
-            }
-        };
-        auto read_scales = [&](float (&s)[TN], int tap) {
-            if constexpr (!INT_OUT) {
-                lds_read_f32<0>(s[0], lds_tab + (tap * PX + px + lrow) * 4);
-                lds_read_f32<128>(s[1], lds_tab + (tap * PX + px + lrow) * 4);
-            }
-        };
-
-        // Step i.  Once the unit's stage has landed everywhere (barrier) a free stage is refilled, the
-        // unit is multiplied and its sums are folded.  All waves meet at the barrier, and the two waves
-        // of a SIMD (wave w and w + 4) share its vector issue and its matrix pipe: so that one of them
-        // multiplies while the other folds and waits for operands, waves 0..3 fold a unit right after
-        // its MFMAs and waves 4..7 fold it at the start of the next step, after requesting that step's
-        // first operands.
-        const bool late = NWL == 3 && wv >= 4;
-        bool pend = false;         // late waves: the sums of unit pend_tap are not folded yet
-        int pend_tap = 0;
-        for (int i = 0; i < ulen; ++i) {
-            if (i >= pre_landed) {
-                if (i + 1 < ulen) wait_all_but_one_step();
-                else wait_vmem<0>();
-            }
-            __builtin_amdgcn_s_barrier();   // every wave's share has landed; the stage of unit i - 1 is no longer read
-            {
-                // units 0 .. i - 1 are done with their stages: step i + NSTAGE - 1 of the stream is next
-                const int g = i + NSTAGE - 1;
-                if (g < ulen) {
-                    issue_step();
-                } else if (whole && g - ulen < ulen_of[1]) {
-                    if (g == ulen) begin_fetch(1, true);
-                    issue_step();
-                }
-            }
-
-            const bool active = exists && u0 + i < u1;
-            if (active || pend) {
-                const int tap = r_tap;
-                float s[TN] = {0.f, 0.f};
-                Ops op[2];
-                if (late) {
-                    if (pend) read_scales(s, pend_tap);
-                } else {
-                    read_scales(s, tap);
-                }
-                if (active) {
-                    set_addresses();
-                    read_step(op[0], std::integral_constant<int, 0>{});
-                    if (!late) read_step(op[1], std::integral_constant<int, 1>{});
-                }
-                if (late && pend) {
-                    if (active) wait_lds<6>();   // LDS operations return in order: the two scales are there
-                    else wait_lds<0>();
-                    if constexpr (!INT_OUT) asm volatile("" : "+v"(s[0]), "+v"(s[1]));
-                    fold(pend_tap, s);
-                    pend = false;
-                }
-                if (active) {
-                    if (late) read_step(op[1], std::integral_constant<int, 1>{});
-                    wait_lds<6>();
-                    if constexpr (!INT_OUT) asm volatile("" : "+v"(s[0]), "+v"(s[1]));
-                    multiply(op[0], true);
-                    read_step(op[0], std::integral_constant<int, 2>{});
-                    wait_lds<6>();
-                    multiply(op[1], false);
-                    wait_lds<0>();
-                    multiply(op[0], false);
-                    if (late) {
-                        pend = true;
-                        pend_tap = tap;
-                    } else {
-                        fold(tap, s);
-                    }
-                }
-            }
-            if (++r_slice == S) {
-                r_slice = 0;
-                ++r_tap;
-                r_dpix = (r_tap / 3 - 1) * a.w + (r_tap % 3 - 1);
-            }
-            r_stage = r_stage + 1 == NSTAGE ? 0 : r_stage + 1;
-        }
-        if (pend) {
-            float s[TN] = {0.f, 0.f};
-            read_scales(s, pend_tap);
-            wait_lds<0>();
-            if constexpr (!INT_OUT) asm volatile("" : "+v"(s[0]), "+v"(s[1]));
-            fold(pend_tap, s);
-        }
-        // whole tiles: the second phase's first stages were requested during the last steps; they must have
-        // landed before the results are stored (stores would sit between them and a later counted wait)
-        if (whole) wait_vmem<0>();
-        __builtin_amdgcn_s_barrier();   // every wave has finished reading the last stage (and its loads have landed)
-        if (whole) pre_landed = ulen >= NSTAGE - 1 ? f_issued : 0;   // (a phase shorter than that did not get to request any)
-
-        if constexpr (INT_OUT) {
-            if (phase == 0 && !whole) {   // the stream starts again
-                begin_fetch(1, false);
-                r_stage = 0;
-                for (int st = 0; st < NSTAGE - 1 && st < ulen_of[1]; ++st) issue_step();
-                wait_vmem<0>();
-                __builtin_amdgcn_s_barrier();
-                pre_landed = f_issued;
-            }
-        } else {
-            Out *y = static_cast<Out *>(a.y);
-            if (whole) {
-                // ---- whole tiles: scale and store -----------------------------------------------------
-                const bool vec_ok = (a.n & 15) == 0;
-                if (exists) {
-#pragma unroll
-                    for (int tm = 0; tm < TM; ++tm) {
-                        const int clocal = 64 * cblock + tm * 32 + 16 * lhalf;
-                        const int cbase = co0 + clocal;
-                        float swv[16], bv[16];
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) { swv[r] = s_sw[clocal + r]; bv[r] = s_bias[clocal + r]; }
-#pragma unroll
-                        for (int tn = 0; tn < TN; ++tn) {
-                            const uint32_t pix = p0 + px + tn * 32 + lrow;
-                            if (pix >= a.pixels) continue;
-                            float out[16];
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) out[r] = __builtin_fmaf(facc[tm][tn][r], swv[r], bv[r]);
-                            Out *dst = y + static_cast<int64_t>(pix) * a.n + cbase;
-                            if (vec_ok && cbase + 16 <= a.n) {
-                                store16(dst, out);
-                            } else {
-#pragma unroll
-                                for (int r = 0; r < 16; ++r)
-                                    if (cbase + r < a.n) dst[r] = static_cast<Out>(out[r]);
-                            }
-                        }
-                    }
-                }
-            } else {
-                // ---- the K groups of a tile exchange their partial sums through LDS ---------------------
-                // Chunk c of a wave's 64 x 64 partial result (sub-tile c / 4, registers 4 (c % 4) .. + 3) is
-                // finished by the wave of K group c % kgn.  The first phase uses the (idle) weight stages and
-                // what lies between them and the tables, the second phase everything below the tables.
-                const uint32_t xbase = phase == 0 ? a.stage_base : 0;
-                const uint32_t per_wave = (16 - (16 >> kl)) * 1024;
-                const int wstride = phase == 0 ? 2 * pgn : pgn;          // waves of consecutive K groups of a tile
-                const int wave0 = wv - kg * wstride;                     // the tile's wave of K group 0
-                float4 *mine = reinterpret_cast<float4 *>(lds + xbase + wv * per_wave);
-#pragma unroll
-                for (int c = 0; c < 16; ++c) {
-                    if ((c & (kgn - 1)) == kg) continue;   // finished here
-                    const int tm = c >> 3, tn = (c >> 2) & 1, q4 = c & 3;
-                    mine[exchange_pos(c, kg, kl) * 64 + lane] =
-                        float4{facc[tm][tn][4 * q4], facc[tm][tn][4 * q4 + 1], facc[tm][tn][4 * q4 + 2],
-                               facc[tm][tn][4 * q4 + 3]};
-                }
-                __syncthreads();
-                // the chunks this wave finishes: their totals replace its own shares in the registers
-#pragma unroll
-                for (int c = 0; c < 16; ++c) {
-                    if ((c & (kgn - 1)) != kg) continue;   // uniform
-                    const int tm = c >> 3, tn = (c >> 2) & 1, q4 = c & 3;
-                    float4 total = float4{0.f, 0.f, 0.f, 0.f};
-                    for (int j = 0; j < kgn; ++j) {   // fixed order: the result does not depend on timing
-                        float4 t;
-                        if (j == kg) {
-                            t = float4{facc[tm][tn][4 * q4], facc[tm][tn][4 * q4 + 1], facc[tm][tn][4 * q4 + 2],
-                                       facc[tm][tn][4 * q4 + 3]};
-                        } else {
-                            const float4 *theirs =
-                                reinterpret_cast<const float4 *>(lds + xbase + (wave0 + j * wstride) * per_wave);
-                            t = theirs[exchange_pos(c, j, kl) * 64 + lane];
-                        }
-                        total.x += t.x; total.y += t.y; total.z += t.z; total.w += t.w;
-                    }
-                    const int clocal = 64 * cblock + tm * 32 + 16 * lhalf + 4 * q4;
-                    facc[tm][tn][4 * q4] = __builtin_fmaf(total.x, s_sw[clocal], s_bias[clocal]);
-                    facc[tm][tn][4 * q4 + 1] = __builtin_fmaf(total.y, s_sw[clocal + 1], s_bias[clocal + 1]);
-                    facc[tm][tn][4 * q4 + 2] = __builtin_fmaf(total.z, s_sw[clocal + 2], s_bias[clocal + 2]);
-                    facc[tm][tn][4 * q4 + 3] = __builtin_fmaf(total.w, s_sw[clocal + 3], s_bias[clocal + 3]);
-                }
-                if (phase == 0) {
-                    // the stages are free again: the second phase's weights are requested and waited for
-                    // before the results are stored
-                    __syncthreads();
-                    begin_fetch(1, false);
-                    r_stage = 0;
-                    for (int st = 0; st < NSTAGE - 1 && st < ulen_of[1]; ++st) issue_step();
-                }
-                if (phase == 0) {
-                    wait_vmem<0>();
-                    __builtin_amdgcn_s_barrier();
-                    pre_landed = f_issued;
-                }
-#pragma unroll
-                for (int c = 0; c < 16; ++c) {
-                    if ((c & (kgn - 1)) != kg) continue;   // uniform
-                    const int tm = c >> 3, tn = (c >> 2) & 1, q4 = c & 3;
-                    const int cbase = cb + tm * 32 + 16 * lhalf + 4 * q4;
-                    const uint32_t pix = p0 + px + tn * 32 + lrow;
-                    if (!exists || pix >= a.pixels) continue;
-                    const float out[4] = {facc[tm][tn][4 * q4], facc[tm][tn][4 * q4 + 1], facc[tm][tn][4 * q4 + 2],
-                                          facc[tm][tn][4 * q4 + 3]};
-                    Out *dst = y + static_cast<int64_t>(pix) * a.n + cbase;
-                    if ((a.n & 3) == 0 && cbase + 4 <= a.n) {
-                        if constexpr (OUT == kOutF16) {
-                            __half2 h01 = __floats2half2_rn(out[0], out[1]), h23 = __floats2half2_rn(out[2], out[3]);
-                            uint2 w2;
-                            w2.x = *reinterpret_cast<uint32_t *>(&h01);
-                            w2.y = *reinterpret_cast<uint32_t *>(&h23);
-                            *reinterpret_cast<uint2 *>(dst) = w2;
-                        } else {
-                            *reinterpret_cast<float4 *>(dst) = float4{out[0], out[1], out[2], out[3]};
-                        }
-                    } else {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            if (cbase + r < a.n) dst[r] = static_cast<Out>(out[r]);
-                    }
-                }
-            }
-        }
-    };
-    run_phase(std::integral_constant<int, 0>{});
-    run_phase(std::integral_constant<int, 1>{});
-}
-
-struct ResPlan {
-    int pg_log2, nw_log2;
-    uint32_t stage_base, stage_bytes, tab_base;
-    int64_t tiles;
-};
-
-// LDS layout of a tile of 64 << pg_log2 pixels for a workgroup of 1 << nw_log2 waves, or false if it
-// does not fit.
-bool res_plan(int64_t pixels, int w, int c_in, int c_out, int pg_log2, int nw_log2, ResPlan &p) {
-    if (nw_log2 - 1 - pg_log2 < 0) return false;
-    const int px = 64 << pg_log2, nw = 1 << nw_log2;
-    const int lds = res_lds(nw_log2);
-    const int slices = c_in / 192;
-    const int64_t rows = px + 2 * (static_cast<int64_t>(w) + 1);
-    const int64_t act = rows * slices * 192;
-    const int64_t tab = (9 * px + px + 2 * 192) * 4;
-    const int64_t stage = static_cast<int64_t>(nw >> pg_log2) * kResBlock;
-    const int64_t nstage = res_stages(pg_log2, nw_log2);
-    if (act + nstage * stage + tab > lds) return false;
-    // the exchange of phase A (K groups (waves / 2) / pgn > 1) happens between the activations and the tables
-    const int kgn_a = (nw / 2) >> pg_log2;
-    if (kgn_a > 1 && lds - tab - act < nw * (16 - 16 / kgn_a) * 1024) return false;
-    // ... and that of phase B below the tables
-    const int kgn_b = nw >> pg_log2;
-    if (lds - tab < nw * (16 - 16 / kgn_b) * 1024) return false;
-    p.pg_log2 = pg_log2;
-    p.nw_log2 = nw_log2;
-    p.stage_base = static_cast<uint32_t>(act);
-    p.stage_bytes = static_cast<uint32_t>(stage);
-    p.tab_base = static_cast<uint32_t>(lds - tab);
-    p.tiles = ((pixels + px - 1) / px) * ((c_out + 191) / 192);
-    return true;
-}
-
-// The configuration that minimises rounds x (time of a tile + fixed cost) on `cus` CUs.  Eight waves:
-// one tile per CU at a time.  Four waves and 128 pixels: two tiles per CU at a time, each at half
-// the rate, but the two workgroups of a CU are not in step with each other (measured faster
-// wherever the layer fills the CUs twice over).
-bool res_choose(int64_t pixels, int w, int c_in, int c_out, int cus, ResPlan &best) {
-    if (c_in % 192 != 0 || c_in <= 0 || c_in > 192 * 16) return false;
-    bool found = false;
-    int64_t best_cost = 0;
-    for (int l = 2; l >= 0; --l) {
-        ResPlan p;
-        if (!res_plan(pixels, w, c_in, c_out, l, 3, p)) continue;
-        const int64_t rounds = (p.tiles + cus - 1) / cus;
-        const int64_t cost = rounds * ((64 << l) + 48);
-        if (!found || cost < best_cost) { best = p; best_cost = cost; found = true; }
-    }
-    ResPlan p4;
-    if (res_plan(pixels, w, c_in, c_out, 1, 2, p4)) {
-        const int64_t rounds = (p4.tiles + 2 * cus - 1) / (2 * cus);
-        const int64_t cost = rounds * (2 * 128 + 48) * kRes4WaveCost / 100;
-        if (!found || cost < best_cost) { best = p4; best_cost = cost; found = true; }
-    }
-    return found;
-}
-
-}  // namespace
 
 // True if the layer is one for this kernel: per-pixel scales, channel slices of 192, a pixel tile
 // whose activations fit the LDS, and enough tiles to occupy at least half of the CUs.
 bool hq_conv3x3_res_fits(int64_t pixels, int w, int c_in, int c_out) {
     ResPlan p;
     const int cus = hq::compute_units();
-    return res_choose(pixels, w, c_in, c_out, cus, p) && 2 * p.tiles >= cus;
+    return res_choose(pixels, w, c_in, c_out, cus, false, p) && 2 * p.tiles >= cus;
 }
 
 // Pixels per workgroup tile (256, 128 or 64) the kernel takes for this layer, plus 1 if the workgroup
@@ -679,43 +16,22 @@ bool hq_conv3x3_res_fits(int64_t pixels, int w, int c_in, int c_out) {
 int hq_conv3x3_res_tile_pixels(int64_t pixels, int w, int c_in, int c_out) {
     ResPlan p;
     const int cus = hq::compute_units();
-    if (!res_choose(pixels, w, c_in, c_out, cus, p) || 2 * p.tiles < cus) return 0;
+    if (!res_choose(pixels, w, c_in, c_out, cus, false, p) || 2 * p.tiles < cus) return 0;
     return (64 << p.pg_log2) + (p.nw_log2 == 2 ? 1 : 0);
 }
 
 hq_status hq_conv3x3_res_launch(const GemmArgs &g, hq_dtype y_dtype, hipStream_t stream) {
     const hq::LaunchCheck check;   // samples the thread's error state before anything is launched
     ResPlan p;
-    if (g.sx_static || !res_choose(g.pixels, g.w, g.k, g.n, hq::compute_units(), p)) return HQ_ERR_UNSUPPORTED;
+    if (g.sx_static || !res_choose(g.pixels, g.w, g.k, g.n, hq::compute_units(), false, p)) return HQ_ERR_UNSUPPORTED;
     if (p.tiles > 0x7fffffffLL) return HQ_ERR_SHAPE;
-    ResArgs a{};
-    a.xq = g.xq; a.sx = g.sx; a.wq = g.wq; a.sw = g.sw; a.bias = g.bias; a.y = g.y;
-    a.pixels = g.pixels; a.n = g.n; a.k = g.k; a.h = g.h; a.w = g.w;
-    const hq::Magic31 mw = hq::magic31(static_cast<uint32_t>(g.w)), mh = hq::magic31(static_cast<uint32_t>(g.h));
-    a.w_magic = mw.m; a.w_shift = mw.s; a.h_magic = mh.m; a.h_shift = mh.s;
-    a.slices = g.k / 192;
-    const hq::Magic31 ms = hq::magic31(static_cast<uint32_t>(a.slices));
-    a.s_magic = ms.m; a.s_shift = ms.s;
-    const hq::Magic31 mp = hq::magic31(static_cast<uint32_t>(6 * a.slices));
-    a.p_magic = mp.m; a.p_shift = mp.s;
-    a.pg_log2 = p.pg_log2;
-    a.n_co_tiles = static_cast<uint32_t>((g.n + 191) / 192);
-    a.n_tiles = static_cast<uint32_t>(p.tiles);
-    a.stage_base = p.stage_base; a.stage_bytes = p.stage_bytes; a.tab_base = p.tab_base;
-    const dim3 grid(a.n_tiles), block(64 << p.nw_log2);
     if (y_dtype != HQ_I32 && y_dtype != HQ_F16 && y_dtype != HQ_F32) return HQ_ERR_DTYPE;
+    ResArgs a{};
+    res_fill_args(a, g, p);
     if (y_dtype == HQ_I32) {
         const hq_status st = hq_fill_zero_launch(g.y, static_cast<uint64_t>(g.pixels) * 9 * g.n, stream);
         if (st != HQ_OK) return st;
     }
-#define HQ_RES_CASE(PGL, NWL)                                                                                  \
-    if (y_dtype == HQ_I32) hipLaunchKernelGGL((conv3x3_res_kernel<kOutI32, PGL, NWL>), grid, block, 0, stream, a);      \
-    else if (y_dtype == HQ_F16) hipLaunchKernelGGL((conv3x3_res_kernel<kOutF16, PGL, NWL>), grid, block, 0, stream, a); \
-    else hipLaunchKernelGGL((conv3x3_res_kernel<kOutF32, PGL, NWL>), grid, block, 0, stream, a);
-    if (p.nw_log2 == 2) { HQ_RES_CASE(1, 2) }
-    else if (p.pg_log2 == 2) { HQ_RES_CASE(2, 3) }
-    else if (p.pg_log2 == 1) { HQ_RES_CASE(1, 3) }
-    else { HQ_RES_CASE(0, 3) }
-#undef HQ_RES_CASE
+    res_launch_plan<false>(a, p, y_dtype, stream);
     return check.status();
 }

@@ -53,6 +53,29 @@ def test_conv_kernel_choice_is_a_function_of_the_geometry(lib):
     assert name(2, 32, 32, 72, 64, bits=8) == "unsupported"
 
 
+def test_fused_conv_argument_errors(lib):
+    f = lib.hq_act_quant_int_conv2d
+    args = lambda **kw: [kw.get(k, d) for k, d in [
+        ("x", P), ("xdt", 0), ("wq", P), ("sw", P), ("bias", None), ("nb", 1), ("h", 4), ("w", 4), ("cin", 192),
+        ("cout", 8), ("r", 3), ("s", 3), ("stride", 1), ("pad", 1), ("block", 64), ("bits", 4), ("y", P),
+        ("dt", 0), ("xq", None), ("sx", None), ("stream", None)]]
+    assert f(*args(x=None)) == NULL
+    assert f(*args(sw=None)) == NULL
+    assert f(*args(dt=7)) == DTYPE
+    assert f(*args(xdt=2)) == DTYPE
+    assert f(*args(bits=5)) == BITS
+    assert f(*args(h=0)) == SHAPE
+    assert f(*args(cin=100)) == SHAPE            # not a multiple of the block
+    assert f(*args(y=P + 4)) == ALIGN
+    assert f(*args(xq=P + 8)) == ALIGN
+    assert f(*args(xdt=1)) == UNSUPPORTED        # fp32 activations: use the two calls
+    assert f(*args(block=32)) == UNSUPPORTED
+    assert f(*args(cin=128)) == UNSUPPORTED      # channel slices of 192 only
+    assert f(*args(r=1, s=1, pad=0)) == UNSUPPORTED
+    assert f(*args(stride=2)) == UNSUPPORTED
+    assert f(*args(cin=192 * 12, w=64)) == UNSUPPORTED   # the tile's activations do not fit on chip
+
+
 def test_status_strings(lib):
     texts = [hq.status_string(i) for i in range(8)]
     assert texts[0] == "ok" and len(set(texts)) == 8

@@ -778,6 +778,79 @@ def test_bypass_layer_end_to_end(hq):
     run_layer(hq, layer, block=8)
 
 
+def run_layer_fused(hq, layer):
+    """A 3x3 layer through the one-launch call that transforms and quantises its own activation
+    tile: (i) the codes and scales it used against the oracle's (tie rule) AND bit for bit against
+    the stand-alone transform-quantise call; (ii) its per-tap int32 sums against the oracle's integer
+    convolution of those (validated) codes, bit for bit; (iii) its result against the oracle's chain."""
+    print("layer (fused)", layer.name, layer.x_shape, "->", layer.n_out, flush=True)
+    x, w, bias = workloads.make_x(layer), workloads.make_w(layer), workloads.make_bias(layer)
+    ydt = TORCH_DT[layer.dtype]
+    xq_o, sx_o, tx = oracle.act_hadamard_quant(x, 64, layer.a_bits)
+    wq_o, sw_o, tw = oracle.quantize_weights(w, 64, layer.w_bits)
+    wq4 = lambda c: c.reshape(layer.n_out, 3, 3, layer.k_in)
+    xd = dev(x)
+    wq_g, sw_g = hq.hq_quantize_weights(dev(w), 64, layer.w_bits)
+    wq_gc = unpack_codes(host(wq_g))
+    flips = check_codes(layer.name + " wq", wq_gc, wq_o, tw, layer.w_bits)
+    bias_d = dev(bias) if bias is not None else None
+    xq_f = torch.zeros(x.shape[:-1] + (layer.k_in // 2,), dtype=torch.uint8, device="cuda")
+    sx_f = torch.zeros(x.shape[:-1], dtype=torch.float32, device="cuda")
+    y_g = host(hq.hq_act_quant_int_conv2d(xd, wq_g, sw_g, bias_d, a_bits=layer.a_bits, y_dtype=ydt,
+                                          codes_out=(xq_f, sx_f)))
+    # (i)
+    xq_s, sx_s = hq.hq_act_hadamard_quant(xd, 64, layer.a_bits)
+    assert np.array_equal(host(xq_f), host(xq_s)), layer.name + ": codes differ from the stand-alone call's"
+    assert np.array_equal(host(sx_f), host(sx_s)), layer.name + ": scales differ from the stand-alone call's"
+    xq_gc = unpack_codes(host(xq_f))
+    check_scales(layer.name + " x_scale", host(sx_f), sx_o)
+    flips += check_codes(layer.name + " xq", xq_gc, xq_o, tx, layer.a_bits)
+    # (ii) integer sums of the fused call (its own codes, the oracle's weight codes)
+    acc_g = host(hq.hq_act_quant_int_conv2d(xd, dev(pack_codes(wq_o)), None, None, a_bits=layer.a_bits,
+                                            y_dtype=torch.int32))
+    acc_o, y_o = oracle.int_conv2d(xq_gc, sx_o, wq4(wq_o), sw_o, bias, stride=1, pad=1)
+    assert np.array_equal(acc_g, acc_o), layer.name + " per-tap int32 sums (fused)"
+    del acc_g, acc_o
+    # (iii)
+    if flips:
+        _, y_o = oracle.int_conv2d(xq_gc, sx_o, wq4(wq_gc), sw_o, bias, stride=1, pad=1, want_acc=False)
+    else:
+        _, y_o = oracle.int_conv2d(xq_o, sx_o, wq4(wq_o), sw_o, bias, stride=1, pad=1, want_acc=False)
+    err = check_y(layer.name + " y (fused)", y_g.reshape(y_o.shape), y_o)
+    print("   ok: tie flips %d, y err %.2e" % (flips, err), flush=True)
+
+
+@pytest.mark.parametrize("idx", [4, 7])
+def test_fused_conv_tiny_layers(hq, idx):
+    run_layer_fused(hq, workloads.tiny_layers()[idx])
+
+
+@pytest.mark.parametrize("nb,h,w,cin,cout,a_bits", [(8, 41, 50, 192, 250, 4), (3, 79, 70, 192, 330, 3),
+                                                     (20, 30, 33, 384, 150, 4), (19, 15, 15, 576, 300, 4),
+                                                     (1, 1, 1, 192, 8, 4), (2, 5, 3, 384, 200, 2)])
+def test_fused_conv_odd_geometry(hq, nb, h, w, cin, cout, a_bits):
+    """The one-launch layer on image sizes that are not powers of two, tiles that span images, ragged
+    pixel and channel tiles, one to three channel slices, every tile configuration of the kernel."""
+    import dataclasses
+    layer = dataclasses.replace(workloads.tiny_layers()[4], name="fused_%dx%dx%dx%d_%d" % (nb, h, w, cin, cout),
+                                x_shape=(nb, h, w, cin), n_out=cout, a_bits=a_bits, bias_std=0.01)
+    run_layer_fused(hq, layer)
+
+
+@pytest.mark.parametrize("config,index", [(3, 0), (5, 0), (5, 1), (5, 2)])
+def test_fused_conv_benchmark_layers_full_size(hq, config, index):
+    run_layer_fused(hq, workloads.config_layers(config)[index])
+
+
+def test_fused_conv_refuses_what_is_not_built(hq):
+    x = torch.zeros((1, 8, 8, 960), dtype=torch.float16, device="cuda")
+    wq = torch.zeros((8, 9, 480), dtype=torch.uint8, device="cuda")
+    with pytest.raises(hq.HqError):   # five slices of an 8-pixel-wide image do not fit on chip
+        hq.hq_act_quant_int_conv2d(x, wq, torch.ones(8, device="cuda"))
+    with pytest.raises(hq.HqError):
+        hq.hq_act_quant_int_conv2d(x[..., :128].contiguous(), wq[..., :64].contiguous(), torch.ones(8, device="cuda"))
+
+
 def _random_bytes(shape, seed):
     g = torch.Generator(device="cuda")
     g.manual_seed(seed)
