@@ -24,7 +24,8 @@ extern "C" hq_status hq_act_quant_int_conv2d(const void *x, hq_dtype x_dtype, co
         (reinterpret_cast<uintptr_t>(bias) & 1u))
         return HQ_ERR_ALIGN;
     // built: fp16 activations, block 64, 3x3 / stride 1 / pad 1, channel slices of 192 and a tile that fits the LDS
-    if (x_dtype != HQ_F16 || had_block != 64 || r != 3 || s != 3 || stride != 1 || pad != 1 || c_in % 192 != 0)
+    if (x_dtype != HQ_F16 || had_block != 64 || r != 3 || s != 3 || stride != 1 || pad != 1 || c_in % 192 != 0 ||
+        c_in > 576)   // (the kernel keeps the fp16 pieces of up to three 192-channel slices of a row in registers)
         return HQ_ERR_UNSUPPORTED;
     const int64_t pixels = static_cast<int64_t>(nb) * h * w;
     // 32-bit pixel indices and weight offsets; the fp16 rows are addressed with 64 bits

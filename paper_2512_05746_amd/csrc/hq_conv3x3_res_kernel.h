@@ -203,31 +203,59 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
         // One wave transforms and quantises 16 rows at a time: lane l owns row l % 16 of the group and
         // K slice q = l / 16; its operands of 64-channel block b are the two 16-byte pieces at channels
         // 64 b + 32 h + 8 q, its 16 results are channels 64 b + 16 q .. + 15.  First pass: the row's
-        // abs-max over all blocks; second pass: the transform again (the fp16 pieces come from cache),
-        // eight values to a packed dword exactly as the stand-alone kernel packs them, two dwords
+        // abs-max over all blocks; second pass: the transform again (the fp16 pieces are still in
+        // registers), eight values to a packed dword exactly as the stand-alone kernel packs them, two dwords
         // expanded to the lane's 16 int8 operand bytes: piece (MFMA q % 2, lane half q / 2) of K step
         // b % 3 of slice b / 3.
         v8h hmat[4][2];
         hadamard64_operands(lane, hmat);
         const int tok = lane & 15, q = lane >> 4;
-        const int nblk = a.k >> 6;
         const int64_t first = static_cast<int64_t>(p0) - halo;
         const bool writes_debug = a.xq_out != nullptr && co0 == 0;
+        // the fp16 pieces of a row: all requested before any is used, and those of the wave's next group
+        // of rows before the current group is worked on (up to three slices of three blocks each)
+        auto row_source = [&](int g16) {
+            const int row = g16 + tok;
+            int64_t pix = first + (row < rows ? row : rows - 1);
+            pix = pix < 0 ? 0 : (pix > static_cast<int64_t>(last) ? last : pix);
+            return pix;
+        };
+        auto request = [&](v8h (&b)[3][3][2], int64_t pix) {
+            const __half *src = a.x + static_cast<uint64_t>(pix) * a.k + 8 * q;
+#pragma unroll
+            for (int sl = 0; sl < 3; ++sl) {
+                if (sl < S) {
+#pragma unroll
+                    for (int bk = 0; bk < 3; ++bk) {
+                        b[sl][bk][0] = *reinterpret_cast<const v8h *>(src + 64 * (3 * sl + bk));
+                        b[sl][bk][1] = *reinterpret_cast<const v8h *>(src + 64 * (3 * sl + bk) + 32);
+                    }
+                }
+            }
+        };
+        v8h b[3][3][2], b_next[3][3][2];
+        if (wv * 16 < rows) request(b_next, row_source(wv * 16));
         for (int g16 = wv * 16; g16 < rows; g16 += 16 << NWL) {
             const int row = g16 + tok;
             const int lrow_c = row < rows ? row : rows - 1;
-            int64_t pix = first + lrow_c;
-            pix = pix < 0 ? 0 : (pix > static_cast<int64_t>(last) ? last : pix);
-            const __half *src = a.x + static_cast<uint64_t>(pix) * a.k + 8 * q;
-            float amax = 0.f;
-            for (int blk = 0; blk < nblk; ++blk) {
-                v8h b[2];
-                b[0] = *reinterpret_cast<const v8h *>(src + 64 * blk);
-                b[1] = *reinterpret_cast<const v8h *>(src + 64 * blk + 32);
-                float v[16];
-                hadamard64_transform(hmat, b, v);
+            const int64_t pix = row_source(g16);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) amax = fmaxf(amax, fabsf(v[r]));
+            for (int sl = 0; sl < 3; ++sl)
+#pragma unroll
+                for (int bk = 0; bk < 3; ++bk) { b[sl][bk][0] = b_next[sl][bk][0]; b[sl][bk][1] = b_next[sl][bk][1]; }
+            if (g16 + (16 << NWL) < rows) request(b_next, row_source(g16 + (16 << NWL)));
+            float amax = 0.f;
+#pragma unroll
+            for (int sl = 0; sl < 3; ++sl) {
+                if (sl < S) {
+#pragma unroll
+                    for (int bk = 0; bk < 3; ++bk) {
+                        float v[16];
+                        hadamard64_transform(hmat, b[sl][bk], v);
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) amax = fmaxf(amax, fabsf(v[r]));
+                    }
+                }
             }
             amax = fmaxf(amax, __shfl_xor(amax, 16));   // the row's other three K slices
             amax = fmaxf(amax, __shfl_xor(amax, 32));
@@ -241,23 +269,26 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
             }
             const uint32_t sw4 = (static_cast<uint32_t>(lrow_c) >> 2) & 3;
             const uint32_t piece = ((((q & 1) << 1) | (q >> 1)) ^ sw4) * 16;
-            for (int blk = 0; blk < nblk; ++blk) {
-                v8h b[2];
-                b[0] = *reinterpret_cast<const v8h *>(src + 64 * blk);
-                b[1] = *reinterpret_cast<const v8h *>(src + 64 * blk + 32);
-                float v[16];
-                hadamard64_transform(hmat, b, v);
-                v4i p = {0, 0, 0, 0};
-                p.x = static_cast<int>(pack8_magic(v, inv));
-                p.y = static_cast<int>(pack8_magic(v + 8, inv));
-                v4i first_half, second_half;
-                expand(p, first_half, second_half);
-                if (row < rows) {
-                    const int slice = blk / 3, ks = blk - 3 * slice;
-                    *reinterpret_cast<v4i *>(lds + (slice * rows + row) * 192 + ks * 64 + piece) = first_half;
-                    if (writes_debug && own)
-                        *reinterpret_cast<uint2 *>(a.xq_out + static_cast<uint64_t>(pix) * kbytes + blk * 32 + q * 8) =
-                            uint2{static_cast<uint32_t>(p.x), static_cast<uint32_t>(p.y)};
+#pragma unroll
+            for (int sl = 0; sl < 3; ++sl) {
+                if (sl < S) {
+#pragma unroll
+                    for (int bk = 0; bk < 3; ++bk) {
+                        float v[16];
+                        hadamard64_transform(hmat, b[sl][bk], v);   // (cheaper than keeping 144 values)
+                        v4i p = {0, 0, 0, 0};
+                        p.x = static_cast<int>(pack8_magic(v, inv));
+                        p.y = static_cast<int>(pack8_magic(v + 8, inv));
+                        v4i first_half, second_half;
+                        expand(p, first_half, second_half);
+                        if (row < rows) {
+                            *reinterpret_cast<v4i *>(lds + (sl * rows + row) * 192 + bk * 64 + piece) = first_half;
+                            if (writes_debug && own)
+                                *reinterpret_cast<uint2 *>(a.xq_out + static_cast<uint64_t>(pix) * kbytes +
+                                                           (3 * sl + bk) * 32 + q * 8) =
+                                    uint2{static_cast<uint32_t>(p.x), static_cast<uint32_t>(p.y)};
+                        }
+                    }
                 }
             }
         }
