@@ -454,7 +454,7 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
         int r_tap = static_cast<int>(hq::div_magic31(static_cast<uint32_t>(u0), S, a.s_magic, a.s_shift));
         int r_slice = u0 - r_tap * S;
         int r_dpix = (r_tap / 3 - 1) * a.w + (r_tap % 3 - 1);   // pixels from an output pixel to the one under the tap
-        auto set_addresses = [&]() {
+        auto set_addresses_b = [&]() {
             const int dpix = r_dpix;
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
@@ -464,12 +464,17 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
                 addr_b0[tn] = rowaddr + o0;
                 addr_b1[tn] = rowaddr + (o0 ^ 32);
             }
+        };
+        auto set_address_a = [&]() {
             addr_a = lds_base + a.stage_base + r_stage * a.stage_bytes + blk * kResBlock + a_lane;
         };
-        auto read_step = [&](Ops &o, auto KS) {
+        auto read_a = [&](Ops &o, auto KS) {
             constexpr int ks = decltype(KS)::value;     // K step of 64 codes
             lds_read16<ks * 32>(o.a[0], addr_a);
             lds_read16<32 * 96 + ks * 32>(o.a[1], addr_a);
+        };
+        auto read_b = [&](Ops &o, auto KS) {
+            constexpr int ks = decltype(KS)::value;
             lds_read16<ks * 64>(o.b[0], addr_b0[0]);
             lds_read16<ks * 64>(o.b[2], addr_b0[1]);
             lds_read16<ks * 64>(o.b[1], addr_b1[0]);
@@ -494,10 +499,12 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
                     }
                 }
             } else {
+                // in the order in which the tiles' last MFMAs were issued: the first sums are folded while the
+                // last MFMAs still execute
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
+                for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-                    for (int tm = 0; tm < TM; ++tm)
+                    for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
                         for (int r = 0; r < 16; ++r)
                             facc[tm][tn][r] = __builtin_fmaf(s[tn], __int_as_float(acc[tm][tn][r]), facc[tm][tn][r]);
@@ -510,21 +517,32 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
             }
         };
 
-        // Step i.  Once the unit's stage has landed everywhere (barrier) a free stage is refilled, the
-        // unit is multiplied and its sums are folded.  All waves meet at the barrier, and the two waves
-        // of a SIMD (wave w and w + 4) share its vector issue and its matrix pipe: so that one of them
-        // multiplies while the other folds and waits for operands, waves 0..3 fold a unit right after
-        // its MFMAs and waves 4..7 fold it at the start of the next step, after requesting that step's
-        // first operands.
-        const bool late = NWL == 3 && wv >= 4;
-        bool pend = false;         // late waves: the sums of unit pend_tap are not folded yet
-        int pend_tap = 0;
+        // Step i.  The activation operands of a unit's first two K steps do not depend on the weight
+        // stream and are requested one step ahead, before the previous unit's sums are folded.  Once the
+        // unit's stage has landed everywhere (barrier) its weight operands are requested, a free stage is
+        // refilled while they are on their way, the unit is multiplied, the next unit's activation
+        // operands are requested and the sums are folded.
+        Ops op[2];
+        if (exists && u0 < u1) {
+            set_addresses_b();
+            read_b(op[0], std::integral_constant<int, 0>{});
+            read_b(op[1], std::integral_constant<int, 1>{});
+        }
         for (int i = 0; i < ulen; ++i) {
             if (i >= pre_landed) {
                 if (i + 1 < ulen) wait_all_but_one_step();
                 else wait_vmem<0>();
             }
             __builtin_amdgcn_s_barrier();   // every wave's share has landed; the stage of unit i - 1 is no longer read
+            const bool active = exists && u0 + i < u1;
+            const int tap = r_tap;
+            float s[TN] = {0.f, 0.f};
+            if (active) {
+                read_scales(s, tap);
+                set_address_a();
+                read_a(op[0], std::integral_constant<int, 0>{});
+                read_a(op[1], std::integral_constant<int, 1>{});
+            }
             {
                 // units 0 .. i - 1 are done with their stages: step i + NSTAGE - 1 of the stream is next
                 const int g = i + NSTAGE - 1;
@@ -535,46 +553,17 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
                     issue_step();
                 }
             }
-
-            const bool active = exists && u0 + i < u1;
-            if (active || pend) {
-                const int tap = r_tap;
-                float s[TN] = {0.f, 0.f};
-                Ops op[2];
-                if (late) {
-                    if (pend) read_scales(s, pend_tap);
-                } else {
-                    read_scales(s, tap);
-                }
-                if (active) {
-                    set_addresses();
-                    read_step(op[0], std::integral_constant<int, 0>{});
-                    if (!late) read_step(op[1], std::integral_constant<int, 1>{});
-                }
-                if (late && pend) {
-                    if (active) wait_lds<6>();   // LDS operations return in order: the two scales are there
-                    else wait_lds<0>();
-                    if constexpr (!INT_OUT) asm volatile("" : "+v"(s[0]), "+v"(s[1]));
-                    fold(pend_tap, s);
-                    pend = false;
-                }
-                if (active) {
-                    if (late) read_step(op[1], std::integral_constant<int, 1>{});
-                    wait_lds<6>();
-                    if constexpr (!INT_OUT) asm volatile("" : "+v"(s[0]), "+v"(s[1]));
-                    multiply(op[0], true);
-                    read_step(op[0], std::integral_constant<int, 2>{});
-                    wait_lds<6>();
-                    multiply(op[1], false);
-                    wait_lds<0>();
-                    multiply(op[0], false);
-                    if (late) {
-                        pend = true;
-                        pend_tap = tap;
-                    } else {
-                        fold(tap, s);
-                    }
-                }
+            const bool next_active = exists && i + 1 < ulen && u0 + i + 1 < u1;
+            if (active) {
+                wait_lds<2>();   // LDS operations return in order: all but the weights of the second K step are there
+                if constexpr (!INT_OUT) asm volatile("" : "+v"(s[0]), "+v"(s[1]));
+                multiply(op[0], true);
+                read_a(op[0], std::integral_constant<int, 2>{});
+                read_b(op[0], std::integral_constant<int, 2>{});
+                wait_lds<6>();
+                multiply(op[1], false);
+                wait_lds<0>();
+                multiply(op[0], false);
             }
             if (++r_slice == S) {
                 r_slice = 0;
@@ -582,13 +571,12 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
                 r_dpix = (r_tap / 3 - 1) * a.w + (r_tap % 3 - 1);
             }
             r_stage = r_stage + 1 == NSTAGE ? 0 : r_stage + 1;
-        }
-        if (pend) {
-            float s[TN] = {0.f, 0.f};
-            read_scales(s, pend_tap);
-            wait_lds<0>();
-            if constexpr (!INT_OUT) asm volatile("" : "+v"(s[0]), "+v"(s[1]));
-            fold(pend_tap, s);
+            if (next_active) {
+                set_addresses_b();
+                read_b(op[0], std::integral_constant<int, 0>{});
+                read_b(op[1], std::integral_constant<int, 1>{});
+            }
+            if (active) fold(tap, s);
         }
         // whole tiles: the second phase's first stages were requested during the last steps; they must have
         // landed before the results are stored (stores would sit between them and a later counted wait)
@@ -617,7 +605,12 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
                         const int cbase = co0 + clocal;
                         float swv[16], bv[16];
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) { swv[r] = s_sw[clocal + r]; bv[r] = s_bias[clocal + r]; }
+                        for (int r = 0; r < 16; r += 4) {
+                            const float4 s4 = *reinterpret_cast<const float4 *>(s_sw + clocal + r);
+                            const float4 b4 = *reinterpret_cast<const float4 *>(s_bias + clocal + r);
+                            swv[r] = s4.x; swv[r + 1] = s4.y; swv[r + 2] = s4.z; swv[r + 3] = s4.w;
+                            bv[r] = b4.x; bv[r + 1] = b4.y; bv[r + 2] = b4.z; bv[r + 3] = b4.w;
+                        }
 #pragma unroll
                         for (int tn = 0; tn < TN; ++tn) {
                             const uint32_t pix = p0 + px + tn * 32 + lrow;
@@ -645,16 +638,19 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
                 const uint32_t per_wave = (16 - (16 >> kl)) * 1024;
                 const int wstride = phase == 0 ? 2 * pgn : pgn;          // waves of consecutive K groups of a tile
                 const int wave0 = wv - kg * wstride;                     // the tile's wave of K group 0
-                float4 *mine = reinterpret_cast<float4 *>(lds + xbase + wv * per_wave);
+                // (written with hand-placed LDS stores: stores the compiler knows of would first wait for every
+                // outstanding memory operation, i.e. for the first phase's results to reach memory)
+                const uint32_t mine = lds_base + xbase + wv * per_wave + lane * 16;
 #pragma unroll
                 for (int c = 0; c < 16; ++c) {
                     if ((c & (kgn - 1)) == kg) continue;   // finished here
                     const int tm = c >> 3, tn = (c >> 2) & 1, q4 = c & 3;
-                    mine[exchange_pos(c, kg, kl) * 64 + lane] =
-                        float4{facc[tm][tn][4 * q4], facc[tm][tn][4 * q4 + 1], facc[tm][tn][4 * q4 + 2],
-                               facc[tm][tn][4 * q4 + 3]};
+                    const v4i bits = {__float_as_int(facc[tm][tn][4 * q4]), __float_as_int(facc[tm][tn][4 * q4 + 1]),
+                                      __float_as_int(facc[tm][tn][4 * q4 + 2]), __float_as_int(facc[tm][tn][4 * q4 + 3])};
+                    asm volatile("ds_write_b128 %0, %1" : : "v"(mine + exchange_pos(c, kg, kl) * 1024), "v"(bits) : "memory");
                 }
-                __syncthreads();
+                wait_lds<0>();
+                __builtin_amdgcn_s_barrier();
                 // the chunks this wave finishes: their totals replace its own shares in the registers
 #pragma unroll
                 for (int c = 0; c < 16; ++c) {
@@ -674,10 +670,12 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
                         total.x += t.x; total.y += t.y; total.z += t.z; total.w += t.w;
                     }
                     const int clocal = 64 * cblock + tm * 32 + 16 * lhalf + 4 * q4;
-                    facc[tm][tn][4 * q4] = __builtin_fmaf(total.x, s_sw[clocal], s_bias[clocal]);
-                    facc[tm][tn][4 * q4 + 1] = __builtin_fmaf(total.y, s_sw[clocal + 1], s_bias[clocal + 1]);
-                    facc[tm][tn][4 * q4 + 2] = __builtin_fmaf(total.z, s_sw[clocal + 2], s_bias[clocal + 2]);
-                    facc[tm][tn][4 * q4 + 3] = __builtin_fmaf(total.w, s_sw[clocal + 3], s_bias[clocal + 3]);
+                    const float4 s4 = *reinterpret_cast<const float4 *>(s_sw + clocal);
+                    const float4 b4 = *reinterpret_cast<const float4 *>(s_bias + clocal);
+                    facc[tm][tn][4 * q4] = __builtin_fmaf(total.x, s4.x, b4.x);
+                    facc[tm][tn][4 * q4 + 1] = __builtin_fmaf(total.y, s4.y, b4.y);
+                    facc[tm][tn][4 * q4 + 2] = __builtin_fmaf(total.z, s4.z, b4.z);
+                    facc[tm][tn][4 * q4 + 3] = __builtin_fmaf(total.w, s4.w, b4.w);
                 }
                 if (phase == 0) {
                     // the stages are free again: the second phase's weights are requested and waited for
