@@ -68,10 +68,13 @@ struct ResArgs {
 };
 
 // chunk c (0..15) of a wave's 64 x 64 partial result = sub-tile c / 4 (tm * 2 + tn), registers 4 (c % 4) .. + 3;
-// among the KG waves that share a tile, wave c % KG finishes chunk c.  A wave stores the chunks it
-// does not finish compactly: chunk c of wave kg sits at position c - (chunks below c that kg finishes).
+// among the KG waves that share a tile, wave c / (16 / KG) finishes chunk c (whole 32 x 32 sub-tiles
+// for KG <= 4).  A wave stores the chunks it does not finish compactly: chunk c of wave kg sits at
+// position c, or c - 16 / KG if it lies after the chunks kg finishes itself.
+__device__ __forceinline__ int exchange_owner(int c, int kgn_log2) { return c >> (4 - kgn_log2); }
 __device__ __forceinline__ int exchange_pos(int c, int kg, int kgn_log2) {
-    return c - ((c + (1 << kgn_log2) - 1 - kg) >> kgn_log2);
+    const int g = 16 >> kgn_log2;
+    return c < kg * g ? c : c - g;
 }
 
 // PGL: log2 of the pixel blocks of 64 per tile (the tile has 64 << PGL pixels)
@@ -517,12 +520,62 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
             }
         };
 
+        // Stores the 32 x 32 sub-tile (tm, tn) of this wave, v = the lane's 16 finished values (channels
+        // cb + tm * 32 + 16 * lhalf + r of pixel tn * 32 + lrow).  fp16 results pass through a 2 KiB staging
+        // area of the wave in LDS as [pixel][32 channels], so that four neighbouring lanes store the 64
+        // contiguous bytes of one pixel (16 requests per store instead of 64 pieces 2 n bytes apart).
+        auto store_subtile = [&](int tm, int tn, const float (&v)[16], uint32_t staging) {
+          if constexpr (!INT_OUT) {
+            Out *y = static_cast<Out *>(a.y);
+            const int csub = cb + tm * 32;
+            if constexpr (OUT == kOutF16) {
+                if ((a.n & 7) == 0 && csub + 32 <= a.n) {
+                    uint32_t h[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const __half2 two = __floats2half2_rn(v[2 * i], v[2 * i + 1]);
+                        h[i] = *reinterpret_cast<const uint32_t *>(&two);
+                    }
+                    const v4i w0 = {static_cast<int>(h[0]), static_cast<int>(h[1]), static_cast<int>(h[2]), static_cast<int>(h[3])};
+                    const v4i w1 = {static_cast<int>(h[4]), static_cast<int>(h[5]), static_cast<int>(h[6]), static_cast<int>(h[7])};
+                    const uint32_t wr = staging + lrow * 64 + lhalf * 32;
+                    asm volatile("ds_write_b128 %0, %1" : : "v"(wr), "v"(w0) : "memory");
+                    asm volatile("ds_write_b128 %0, %1 offset:16" : : "v"(wr), "v"(w1) : "memory");
+                    wait_lds<0>();
+                    v4i r0, r1;
+                    lds_read16<0>(r0, staging + lane * 16);
+                    lds_read16<1024>(r1, staging + lane * 16);
+                    wait_lds<0>();
+                    pin(r0);
+                    pin(r1);
+                    const uint32_t pix0 = p0 + px + tn * 32 + (lane >> 2), pix1 = pix0 + 16;
+                    __half *dst = reinterpret_cast<__half *>(y) + csub + (lane & 3) * 8;
+                    if (pix0 < a.pixels) *reinterpret_cast<v4i *>(dst + static_cast<int64_t>(pix0) * a.n) = r0;
+                    if (pix1 < a.pixels) *reinterpret_cast<v4i *>(dst + static_cast<int64_t>(pix1) * a.n) = r1;
+                    return;
+                }
+            }
+            const uint32_t pix = p0 + px + tn * 32 + lrow;
+            if (pix >= a.pixels) return;
+            const int cbase = csub + 16 * lhalf;
+            Out *dst = y + static_cast<int64_t>(pix) * a.n + cbase;
+            if ((a.n & 15) == 0 && cbase + 16 <= a.n) {
+                store16(dst, v);
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (cbase + r < a.n) dst[r] = static_cast<Out>(v[r]);
+            }
+          }
+        };
+
         // Step i.  The activation operands of a unit's first two K steps do not depend on the weight
         // stream and are requested one step ahead, before the previous unit's sums are folded.  Once the
         // unit's stage has landed everywhere (barrier) its weight operands are requested, a free stage is
         // refilled while they are on their way, the unit is multiplied, the next unit's activation
         // operands are requested and the sums are folded.
         Ops op[2];
+        bool next_begun = false;   // whole tiles: the stream has gone on to the second phase's weights
         if (exists && u0 < u1) {
             set_addresses_b();
             read_b(op[0], std::integral_constant<int, 0>{});
@@ -530,7 +583,8 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
         }
         for (int i = 0; i < ulen; ++i) {
             if (i >= pre_landed) {
-                if (i + 1 < ulen) wait_all_but_one_step();
+                // unit i's loads have landed once at most one younger step's are pending
+                if (!next_begun && f_issued - (i + 1) == 1) wait_all_but_one_step();
                 else wait_vmem<0>();
             }
             __builtin_amdgcn_s_barrier();   // every wave's share has landed; the stage of unit i - 1 is no longer read
@@ -543,15 +597,15 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
                 read_a(op[0], std::integral_constant<int, 0>{});
                 read_a(op[1], std::integral_constant<int, 1>{});
             }
-            {
-                // units 0 .. i - 1 are done with their stages: step i + NSTAGE - 1 of the stream is next
-                const int g = i + NSTAGE - 1;
-                if (g < ulen) {
-                    issue_step();
-                } else if (whole && g - ulen < ulen_of[1]) {
-                    if (g == ulen) begin_fetch(1, true);
-                    issue_step();
-                }
+            // units 0 .. i - 1 are done with their stages: units up to i + NSTAGE - 1 may be on their way
+            // (more than one request only right after a phase that began with a single prefetched stage)
+            while (f_issued < ulen && f_issued < i + NSTAGE && !next_begun) issue_step();
+            if (whole && i + NSTAGE - 1 == ulen) {
+                // the stream goes on to the second phase's first unit (one stage only: the others serve as
+                // staging for the stores of this phase's results)
+                begin_fetch(1, true);
+                next_begun = true;
+                issue_step();
             }
             const bool next_active = exists && i + 1 < ulen && u0 + i + 1 < u1;
             if (active) {
@@ -582,7 +636,7 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
         // landed before the results are stored (stores would sit between them and a later counted wait)
         if (whole) wait_vmem<0>();
         __builtin_amdgcn_s_barrier();   // every wave has finished reading the last stage (and its loads have landed)
-        if (whole) pre_landed = ulen >= NSTAGE - 1 ? f_issued : 0;   // (a phase shorter than that did not get to request any)
+        if (whole) pre_landed = next_begun ? f_issued : 0;
 
         if constexpr (INT_OUT) {
             if (phase == 0 && !whole) {   // the stream starts again
@@ -597,12 +651,13 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
             Out *y = static_cast<Out *>(a.y);
             if (whole) {
                 // ---- whole tiles: scale and store -----------------------------------------------------
-                const bool vec_ok = (a.n & 15) == 0;
+                // (staging: a weight stage that does not hold the second phase's first unit)
+                const int free_stage = (r_stage + 1 + (NSTAGE == 3 && wv >= 4 ? 1 : 0)) % NSTAGE;
+                const uint32_t staging = lds_base + a.stage_base + free_stage * a.stage_bytes + (wv & 3) * 2048;
                 if (exists) {
 #pragma unroll
                     for (int tm = 0; tm < TM; ++tm) {
                         const int clocal = 64 * cblock + tm * 32 + 16 * lhalf;
-                        const int cbase = co0 + clocal;
                         float swv[16], bv[16];
 #pragma unroll
                         for (int r = 0; r < 16; r += 4) {
@@ -613,26 +668,17 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
                         }
 #pragma unroll
                         for (int tn = 0; tn < TN; ++tn) {
-                            const uint32_t pix = p0 + px + tn * 32 + lrow;
-                            if (pix >= a.pixels) continue;
                             float out[16];
 #pragma unroll
                             for (int r = 0; r < 16; ++r) out[r] = __builtin_fmaf(facc[tm][tn][r], swv[r], bv[r]);
-                            Out *dst = y + static_cast<int64_t>(pix) * a.n + cbase;
-                            if (vec_ok && cbase + 16 <= a.n) {
-                                store16(dst, out);
-                            } else {
-#pragma unroll
-                                for (int r = 0; r < 16; ++r)
-                                    if (cbase + r < a.n) dst[r] = static_cast<Out>(out[r]);
-                            }
+                            store_subtile(tm, tn, out, staging);
                         }
                     }
                 }
             } else {
                 // ---- the K groups of a tile exchange their partial sums through LDS ---------------------
                 // Chunk c of a wave's 64 x 64 partial result (sub-tile c / 4, registers 4 (c % 4) .. + 3) is
-                // finished by the wave of K group c % kgn.  The first phase uses the (idle) weight stages and
+                // finished by the wave of K group c / (16 / kgn).  The first phase uses the (idle) weight stages and
                 // what lies between them and the tables, the second phase everything below the tables.
                 const uint32_t xbase = phase == 0 ? a.stage_base : 0;
                 const uint32_t per_wave = (16 - (16 >> kl)) * 1024;
@@ -643,7 +689,7 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
                 const uint32_t mine = lds_base + xbase + wv * per_wave + lane * 16;
 #pragma unroll
                 for (int c = 0; c < 16; ++c) {
-                    if ((c & (kgn - 1)) == kg) continue;   // finished here
+                    if (exchange_owner(c, kl) == kg) continue;   // finished here
                     const int tm = c >> 3, tn = (c >> 2) & 1, q4 = c & 3;
                     const v4i bits = {__float_as_int(facc[tm][tn][4 * q4]), __float_as_int(facc[tm][tn][4 * q4 + 1]),
                                       __float_as_int(facc[tm][tn][4 * q4 + 2]), __float_as_int(facc[tm][tn][4 * q4 + 3])};
@@ -654,7 +700,7 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
                 // the chunks this wave finishes: their totals replace its own shares in the registers
 #pragma unroll
                 for (int c = 0; c < 16; ++c) {
-                    if ((c & (kgn - 1)) != kg) continue;   // uniform
+                    if (exchange_owner(c, kl) != kg) continue;   // uniform
                     const int tm = c >> 3, tn = (c >> 2) & 1, q4 = c & 3;
                     float4 total = float4{0.f, 0.f, 0.f, 0.f};
                     for (int j = 0; j < kgn; ++j) {   // fixed order: the result does not depend on timing
@@ -690,30 +736,43 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
                     __builtin_amdgcn_s_barrier();
                     pre_landed = f_issued;
                 }
+                // staging for the stores: phase A - the last weight stage (the second phase's first units sit
+                // in the stages before it); phase B - just below the tables, above the exchanged sums
+                const uint32_t staging = lds_base + (phase == 0 ? a.stage_base + (NSTAGE - 1) * a.stage_bytes
+                                                                : a.tab_base - (2048u << NWL)) + wv * 2048;
+                if constexpr (kgn <= 4) {
 #pragma unroll
-                for (int c = 0; c < 16; ++c) {
-                    if ((c & (kgn - 1)) != kg) continue;   // uniform
-                    const int tm = c >> 3, tn = (c >> 2) & 1, q4 = c & 3;
-                    const int cbase = cb + tm * 32 + 16 * lhalf + 4 * q4;
-                    const uint32_t pix = p0 + px + tn * 32 + lrow;
-                    if (!exists || pix >= a.pixels) continue;
-                    const float out[4] = {facc[tm][tn][4 * q4], facc[tm][tn][4 * q4 + 1], facc[tm][tn][4 * q4 + 2],
-                                          facc[tm][tn][4 * q4 + 3]};
-                    Out *dst = y + static_cast<int64_t>(pix) * a.n + cbase;
-                    if ((a.n & 3) == 0 && cbase + 4 <= a.n) {
-                        if constexpr (OUT == kOutF16) {
-                            __half2 h01 = __floats2half2_rn(out[0], out[1]), h23 = __floats2half2_rn(out[2], out[3]);
-                            uint2 w2;
-                            w2.x = *reinterpret_cast<uint32_t *>(&h01);
-                            w2.y = *reinterpret_cast<uint32_t *>(&h23);
-                            *reinterpret_cast<uint2 *>(dst) = w2;
+                    for (int sub = 0; sub < 4; ++sub) {
+                        if (exchange_owner(4 * sub, kl) != kg) continue;   // uniform
+                        if (exists) store_subtile(sub >> 1, sub & 1, facc[sub >> 1][sub & 1], staging);
+                    }
+                } else {
+                    // eight K groups: this wave finishes half a sub-tile, 8 channels of every pixel
+#pragma unroll
+                    for (int c = 0; c < 16; ++c) {
+                        if (exchange_owner(c, kl) != kg) continue;   // uniform
+                        const int tm = c >> 3, tn = (c >> 2) & 1, q4 = c & 3;
+                        const int cbase = cb + tm * 32 + 16 * lhalf + 4 * q4;
+                        const uint32_t pix = p0 + px + tn * 32 + lrow;
+                        if (!exists || pix >= a.pixels) continue;
+                        const float out[4] = {facc[tm][tn][4 * q4], facc[tm][tn][4 * q4 + 1], facc[tm][tn][4 * q4 + 2],
+                                              facc[tm][tn][4 * q4 + 3]};
+                        Out *dst = y + static_cast<int64_t>(pix) * a.n + cbase;
+                        if ((a.n & 3) == 0 && cbase + 4 <= a.n) {
+                            if constexpr (OUT == kOutF16) {
+                                __half2 h01 = __floats2half2_rn(out[0], out[1]), h23 = __floats2half2_rn(out[2], out[3]);
+                                uint2 w2;
+                                w2.x = *reinterpret_cast<uint32_t *>(&h01);
+                                w2.y = *reinterpret_cast<uint32_t *>(&h23);
+                                *reinterpret_cast<uint2 *>(dst) = w2;
+                            } else {
+                                *reinterpret_cast<float4 *>(dst) = float4{out[0], out[1], out[2], out[3]};
+                            }
                         } else {
-                            *reinterpret_cast<float4 *>(dst) = float4{out[0], out[1], out[2], out[3]};
-                        }
-                    } else {
 #pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            if (cbase + r < a.n) dst[r] = static_cast<Out>(out[r]);
+                            for (int r = 0; r < 4; ++r)
+                                if (cbase + r < a.n) dst[r] = static_cast<Out>(out[r]);
+                        }
                     }
                 }
             }
@@ -747,7 +806,8 @@ bool res_plan(int64_t pixels, int w, int c_in, int c_out, int pg_log2, int nw_lo
     if (kgn_a > 1 && lds - tab - act < nw * (16 - 16 / kgn_a) * 1024) return false;
     // ... and that of phase B below the tables
     const int kgn_b = nw >> pg_log2;
-    if (lds - tab < nw * (16 - 16 / kgn_b) * 1024) return false;
+    if (lds - tab < nw * (16 - 16 / kgn_b) * 1024 + nw * 2048) return false;   // (+ staging of the stores)
+    if (stage < 4 * 2048) return false;
     p.pg_log2 = pg_log2;
     p.nw_log2 = nw_log2;
     p.stage_base = static_cast<uint32_t>(act);
