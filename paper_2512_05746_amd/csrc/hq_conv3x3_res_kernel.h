@@ -530,24 +530,8 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
             const int csub = cb + tm * 32;
             if constexpr (OUT == kOutF16) {
                 if ((a.n & 7) == 0 && csub + 32 <= a.n) {
-                    uint32_t h[8];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const __half2 two = __floats2half2_rn(v[2 * i], v[2 * i + 1]);
-                        h[i] = *reinterpret_cast<const uint32_t *>(&two);
-                    }
-                    const v4i w0 = {static_cast<int>(h[0]), static_cast<int>(h[1]), static_cast<int>(h[2]), static_cast<int>(h[3])};
-                    const v4i w1 = {static_cast<int>(h[4]), static_cast<int>(h[5]), static_cast<int>(h[6]), static_cast<int>(h[7])};
-                    const uint32_t wr = staging + lrow * 64 + lhalf * 32;
-                    asm volatile("ds_write_b128 %0, %1" : : "v"(wr), "v"(w0) : "memory");
-                    asm volatile("ds_write_b128 %0, %1 offset:16" : : "v"(wr), "v"(w1) : "memory");
-                    wait_lds<0>();
                     v4i r0, r1;
-                    lds_read16<0>(r0, staging + lane * 16);
-                    lds_read16<1024>(r1, staging + lane * 16);
-                    wait_lds<0>();
-                    pin(r0);
-                    pin(r1);
+                    transpose_tile_f16(v, staging, lane, r0, r1);
                     const uint32_t pix0 = p0 + px + tn * 32 + (lane >> 2), pix1 = pix0 + 16;
                     __half *dst = reinterpret_cast<__half *>(y) + csub + (lane & 3) * 8;
                     if (pix0 < a.pixels) *reinterpret_cast<v4i *>(dst + static_cast<int64_t>(pix0) * a.n) = r0;

@@ -132,6 +132,35 @@ __device__ __forceinline__ void lds_read_f32(float &dst, uint32_t addr) {
     asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFFSET) : "memory");
 }
 
+template <int OFFSET>
+__device__ __forceinline__ void lds_write16(uint32_t addr, const v4i &v) {
+    asm volatile("ds_write_b128 %0, %1 offset:%2" : : "v"(addr), "v"(v), "n"(OFFSET) : "memory");
+}
+
+// fp16 results of a 32-channel x 32-pixel MFMA tile (v: the lane's 16 consecutive channels of pixel
+// lane % 32, channel half lane / 32) through a 2 KiB staging area of the wave in LDS, laid out
+// [pixel][32 channels]: afterwards lane l holds the 16-byte piece l % 4 of pixels l / 4 (r0) and
+// 16 + l / 4 (r1), so that four neighbouring lanes store the 64 contiguous bytes of one pixel
+// instead of every lane storing a piece 2 n bytes away from its neighbour's.
+__device__ __forceinline__ void transpose_tile_f16(const float (&v)[16], uint32_t staging, int lane, v4i &r0, v4i &r1) {
+    uint32_t h[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const __half2 two = __floats2half2_rn(v[2 * i], v[2 * i + 1]);
+        h[i] = *reinterpret_cast<const uint32_t *>(&two);
+    }
+    const v4i w0 = {static_cast<int>(h[0]), static_cast<int>(h[1]), static_cast<int>(h[2]), static_cast<int>(h[3])};
+    const v4i w1 = {static_cast<int>(h[4]), static_cast<int>(h[5]), static_cast<int>(h[6]), static_cast<int>(h[7])};
+    const uint32_t wr = staging + (lane & 31) * 64 + (lane >> 5) * 32;
+    lds_write16<0>(wr, w0);
+    lds_write16<16>(wr, w1);
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): the wave's own stores are in LDS
+    asm volatile("ds_read_b128 %0, %1" : "=v"(r0) : "v"(staging + lane * 16) : "memory");
+    asm volatile("ds_read_b128 %0, %1 offset:1024" : "=v"(r1) : "v"(staging + lane * 16) : "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+    asm volatile("" : "+v"(r0), "+v"(r1));
+}
+
 // Ties a register to the point after the preceding hand-placed wait.
 __device__ __forceinline__ void pin(v4i &v) { asm volatile("" : "+v"(v)); }
 
