@@ -219,17 +219,17 @@ def main():
             "quant_frac_hbm_peak": round(q_bytes / quant_us[i] / 1e3 / HBM_PEAK_GBS, 4),
             "rotating_buffer_sets": rot_sets[i],
         })
-    # ---- the 3x3 layers in ONE launch: transform, quantisation, integer convolution and epilogue, the
-    # codes never leaving the chip (hq_act_quant_int_conv2d), with the same buffer rotation -------------
+    # ---- every layer in ONE launch: transform, quantisation, integer stage and epilogue, the codes never
+    # leaving the chip (hq_act_quant_int_conv2d / hq_act_quant_int_linear), with the same buffer rotation ---
     fused_layers = []
     for i, s in enumerate(state):
         layer, x, wq, sw = s[:4]
-        if not (layer.kind == "conv" and layer.ksize == 3):
-            continue
-
-        def run_fused(r, layer=layer):
-            hq.hq_act_quant_int_conv2d(r[1], r[2], r[3], None, a_bits=layer.a_bits, y_dtype=torch.float16, out=r[6])
-
+        if layer.kind == "conv" and layer.ksize == 3:
+            def run_fused(r, layer=layer):
+                hq.hq_act_quant_int_conv2d(r[1], r[2], r[3], None, a_bits=layer.a_bits, y_dtype=torch.float16, out=r[6])
+        else:
+            def run_fused(r, layer=layer):
+                hq.hq_act_quant_int_linear(r[1], r[2], r[3], None, a_bits=layer.a_bits, y_dtype=torch.float16, out=r[6])
         try:
             run_fused(s)
         except hq.HqError:
@@ -499,10 +499,10 @@ def main():
         },
         "layers": per_layer,
         "fused_mode": {
-            "what": "the 3x3 layers through hq_act_quant_int_conv2d (one launch per layer: block Hadamard + "
-                    "per-pixel quantisation of the fp16 tile inside the convolution kernel, codes never written "
-                    "to memory) against the two calls of the timed step; bytes = fp16 in + fp16 out + weight codes; "
-                    "not part of `value`",
+            "what": "every layer in ONE launch (hq_act_quant_int_conv2d for 3x3, hq_act_quant_int_linear for 1x1 / "
+                    "linear: block Hadamard + per-token quantisation inside the kernel that multiplies, codes never "
+                    "written to memory) against the two calls of the timed step; bytes = fp16 in + fp16 out + weight "
+                    "codes; not part of `value`",
             "layers": fused_layers,
         },
         "static_scale_mode": {

@@ -167,6 +167,22 @@ hq_status hq_act_quant_int_conv2d(const void *x, hq_dtype x_dtype, const uint8_t
                                   uint8_t *xq_out, float *x_scale_out, void *stream);
 
 /*
+ * The same for a linear layer / 1x1 convolution (m = N*H*W rows): hq_act_hadamard_quant followed by
+ * hq_int_linear in one launch, codes and scales identical to those of the two calls.  (Method,
+ * "Matrix Multiplication".)  Such layers are bound by reading their input and writing their output;
+ * the single launch saves the round trip of the codes and one launch.
+ *
+ *   x [m, k] of x_dtype; wq [n, k/2], w_scale [n], bias [n] of y_dtype or NULL; y [m, n]
+ *   (y_dtype == HQ_I32: the int32 sums).  xq_out NULL or out [m, k/2]; x_scale_out NULL or out [m].
+ *   Built: x_dtype HQ_F16, had_block 64, a_bits 2..4, k a multiple of 64 up to 1024; anything else
+ *   returns HQ_ERR_UNSUPPORTED (use the two calls).
+ */
+hq_status hq_act_quant_int_linear(const void *x, hq_dtype x_dtype, const uint8_t *wq,
+                                  const float *w_scale, const void *bias, int64_t m, int n, int k,
+                                  int had_block, int a_bits, void *y, hq_dtype y_dtype,
+                                  uint8_t *xq_out, float *x_scale_out, void *stream);
+
+/*
  * Diagnostic: the kernel family that hq_int_conv2d (static_scale = 0) or hq_int_conv2d_static
  * (static_scale = 1) runs for a convolution of this geometry on the current device, for 4-bit
  * (bits = 4) or 8-bit (bits = 8, hq_int_conv2d_i8) codes.  The choice depends on the geometry

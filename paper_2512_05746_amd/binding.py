@@ -24,7 +24,7 @@ SYMBOLS = ("hq_status_string", "hq_quantize_weights", "hq_act_hadamard_quant",
            "hq_quantize_weights_single", "hq_int_linear_single",
            "hq_act_hadamard_quant_width", "hq_int_conv2d_width",
            "hq_int_linear_i8", "hq_int_conv2d_i8", "hq_act_hadamard_quant_i8",
-           "hq_act_quant_int_conv2d")
+           "hq_act_quant_int_conv2d", "hq_act_quant_int_linear")
 # entry points that do not return a status
 INFO_SYMBOLS = ("hq_int_conv2d_kernel_name",)
 
@@ -67,6 +67,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.hq_act_hadamard_quant_i8.argtypes = lib.hq_act_hadamard_quant.argtypes
     lib.hq_int_conv2d_i8.argtypes = lib.hq_int_conv2d.argtypes
     lib.hq_act_quant_int_conv2d.argtypes = [vp, i32, vp, vp, vp] + [i32] * 11 + [vp, i32, vp, vp, vp]
+    lib.hq_act_quant_int_linear.argtypes = [vp, i32, vp, vp, vp, i64, i32, i32, i32, i32, vp, i32, vp, vp, vp]
     for name in SYMBOLS[1:]:
         getattr(lib, name).restype = i32
     lib.hq_int_conv2d_kernel_name.argtypes = [i32] * 11
@@ -251,6 +252,31 @@ def hq_act_quant_int_conv2d(x: torch.Tensor, wq: torch.Tensor, w_scale: Optional
     _check("hq_act_quant_int_conv2d", load_library().hq_act_quant_int_conv2d(
         _ptr(x), _DTYPES[x.dtype], _ptr(wq), _ptr(w_scale), _ptr(bias), nb, h, w, cin, cout, ksize, ksize,
         stride, pad, had_block, a_bits, _ptr(y), _DTYPES[y_dtype], _ptr(xq), _ptr(sx), _stream()))
+    return y
+
+
+def hq_act_quant_int_linear(x: torch.Tensor, wq: torch.Tensor, w_scale: Optional[torch.Tensor],
+                            bias: Optional[torch.Tensor] = None, had_block: int = 64, a_bits: int = 4,
+                            y_dtype: torch.dtype = torch.float16, out: Optional[torch.Tensor] = None,
+                            codes_out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None) -> torch.Tensor:
+    """A linear layer / 1x1 convolution in one launch: x [..., k] fp16, wq [n, k/2] (or [n, 1, k/2]) ->
+    y [..., n] (y_dtype int32: the integer sums).  codes_out = (xq uint8 [..., k/2], x_scale fp32 [...])
+    receives the codes and scales the kernel used."""
+    _dev(x, "x"), _codes(wq, torch.uint8, "wq")
+    k = x.shape[-1]
+    m = x.numel() // k
+    n = wq.shape[0]
+    if wq.numel() != n * (k // 2):
+        raise ValueError("wq does not match x")
+    _vec(w_scale, n, torch.float32, "w_scale"), _vec(bias, n, y_dtype, "bias")
+    y = _out(out, tuple(x.shape[:-1]) + (n,), y_dtype, x.device)
+    xq = sx = None
+    if codes_out is not None:
+        xq = _out(codes_out[0], tuple(x.shape[:-1]) + (k // 2,), torch.uint8, x.device)
+        sx = _out(codes_out[1], tuple(x.shape[:-1]), torch.float32, x.device)
+    _check("hq_act_quant_int_linear", load_library().hq_act_quant_int_linear(
+        _ptr(x), _DTYPES[x.dtype], _ptr(wq), _ptr(w_scale), _ptr(bias), m, n, k, had_block, a_bits,
+        _ptr(y), _DTYPES[y_dtype], _ptr(xq), _ptr(sx), _stream()))
     return y
 
 

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libhq.so")
 SOURCES = ["hq_hadamard_quant.hip", "hq_int_gemm.hip", "hq_int_gemm_128x128.hip",
-           "hq_int_gemm_64x128.hip", "hq_int_gemm_64x64.hip", "hq_conv3x3_wave.hip", "hq_conv3x3_halo.hip", "hq_conv3x3_res.hip", "hq_conv3x3_fused.hip", "hq_int_gemm_anyk.hip",
+           "hq_int_gemm_64x128.hip", "hq_int_gemm_64x64.hip", "hq_conv3x3_wave.hip", "hq_conv3x3_halo.hip", "hq_conv3x3_res.hip", "hq_conv3x3_fused.hip", "hq_linear_fused.hip", "hq_int_gemm_anyk.hip",
            "hq_single_weights.hip", "hq_width_quant.hip"]
 HEADERS = ["hq_common.h", "hq_int_gemm_kernel.h", "hq_hadamard_mfma.h", "hq_conv3x3_res_kernel.h"]
 

@@ -76,6 +76,23 @@ def test_fused_conv_argument_errors(lib):
     assert f(*args(cin=192 * 12, w=64)) == UNSUPPORTED   # the tile's activations do not fit on chip
 
 
+def test_fused_linear_argument_errors(lib):
+    f = lib.hq_act_quant_int_linear
+    args = lambda **kw: [kw.get(k, d) for k, d in [
+        ("x", P), ("xdt", 0), ("wq", P), ("sw", P), ("bias", None), ("m", 8), ("n", 8), ("k", 64), ("block", 64),
+        ("bits", 4), ("y", P), ("dt", 0), ("xq", None), ("sx", None), ("stream", None)]]
+    assert f(*args(x=None)) == NULL
+    assert f(*args(sw=None)) == NULL
+    assert f(*args(dt=7)) == DTYPE
+    assert f(*args(bits=5)) == BITS
+    assert f(*args(m=0)) == SHAPE
+    assert f(*args(k=100)) == SHAPE
+    assert f(*args(y=P + 4)) == ALIGN
+    assert f(*args(xdt=1)) == UNSUPPORTED
+    assert f(*args(block=32, k=96)) == UNSUPPORTED
+    assert f(*args(k=2048)) == UNSUPPORTED
+
+
 def test_status_strings(lib):
     texts = [hq.status_string(i) for i in range(8)]
     assert texts[0] == "ok" and len(set(texts)) == 8

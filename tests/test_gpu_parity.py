@@ -842,6 +842,64 @@ def test_fused_conv_benchmark_layers_full_size(hq, config, index):
     run_layer_fused(hq, workloads.config_layers(config)[index])
 
 
+def run_linear_fused(hq, layer):
+    """A linear layer / 1x1 convolution through the one-launch call: codes and scales against the
+    oracle (tie rule) and bit for bit against the stand-alone call, int32 sums of those codes bit for
+    bit, the result against the oracle's chain."""
+    print("layer (fused linear)", layer.name, layer.x_shape, "->", layer.n_out, flush=True)
+    x, w, bias = workloads.make_x(layer), workloads.make_w(layer)[:, 0, :], workloads.make_bias(layer)
+    ydt = TORCH_DT[layer.dtype]
+    x2 = x.reshape(-1, layer.k_in)
+    xq_o, sx_o, tx = oracle.act_hadamard_quant(x2, 64, layer.a_bits)
+    wq_o, sw_o, tw = oracle.quantize_weights(w[:, None, :], 64, layer.w_bits)
+    wq_o = wq_o[:, 0, :]
+    xd = dev(x2)
+    wq_g, sw_g = hq.hq_quantize_weights(dev(w[:, None, :]), 64, layer.w_bits)
+    wq_gc = unpack_codes(host(wq_g))[:, 0, :]
+    flips = check_codes(layer.name + " wq", wq_gc, wq_o, tw[:, 0, :], layer.w_bits)
+    bias_d = dev(bias) if bias is not None else None
+    xq_f = torch.zeros((x2.shape[0], layer.k_in // 2), dtype=torch.uint8, device="cuda")
+    sx_f = torch.zeros((x2.shape[0],), dtype=torch.float32, device="cuda")
+    y_g = host(hq.hq_act_quant_int_linear(xd, wq_g, sw_g, bias_d, a_bits=layer.a_bits, y_dtype=ydt,
+                                          codes_out=(xq_f, sx_f)))
+    xq_s, sx_s = hq.hq_act_hadamard_quant(xd, 64, layer.a_bits)
+    assert np.array_equal(host(xq_f), host(xq_s)), layer.name + ": codes differ from the stand-alone call's"
+    assert np.array_equal(host(sx_f), host(sx_s)), layer.name + ": scales differ from the stand-alone call's"
+    xq_gc = unpack_codes(host(xq_f))
+    check_scales(layer.name + " x_scale", host(sx_f), sx_o)
+    flips += check_codes(layer.name + " xq", xq_gc, xq_o, tx, layer.a_bits)
+    acc_g = host(hq.hq_act_quant_int_linear(xd, dev(pack_codes(wq_o)), None, None, a_bits=layer.a_bits,
+                                            y_dtype=torch.int32))
+    acc_o, y_o = oracle.int_linear(xq_gc, sx_o, wq_o, sw_o, bias)
+    assert np.array_equal(acc_g, acc_o), layer.name + " int32 sums (fused linear)"
+    if flips:
+        _, y_o = oracle.int_linear(xq_gc, sx_o, wq_gc, sw_o, bias)
+    else:
+        _, y_o = oracle.int_linear(xq_o, sx_o, wq_o, sw_o, bias)
+    err = check_y(layer.name + " y (fused linear)", y_g.reshape(y_o.shape), y_o)
+    print("   ok: tie flips %d, y err %.2e" % (flips, err), flush=True)
+
+
+@pytest.mark.parametrize("idx", [0, 2, 5])
+def test_fused_linear_tiny_layers(hq, idx):
+    run_linear_fused(hq, workloads.tiny_layers()[idx])
+
+
+@pytest.mark.parametrize("m,k,n,a_bits", [(1, 64, 1, 4), (65, 128, 40, 3), (333, 1024, 200, 4), (700, 960, 1000, 4),
+                                          (5000, 192, 72, 2)])
+def test_fused_linear_shapes(hq, m, k, n, a_bits):
+    """One row, ragged row and column tiles, the longest row, several column groups per row tile."""
+    import dataclasses
+    layer = dataclasses.replace(workloads.tiny_layers()[0], name="fl_%d_%d_%d" % (m, k, n), x_shape=(m, k),
+                                n_out=n, a_bits=a_bits)
+    run_linear_fused(hq, layer)
+
+
+@pytest.mark.parametrize("config,index", [(2, 0), (4, 1), (5, 4), (5, 5), (5, 6), (5, 7), (5, 8)])
+def test_fused_linear_benchmark_layers_full_size(hq, config, index):
+    run_linear_fused(hq, workloads.config_layers(config)[index])
+
+
 def test_fused_conv_refuses_what_is_not_built(hq):
     x = torch.zeros((1, 8, 8, 960), dtype=torch.float16, device="cuda")
     wq = torch.zeros((8, 9, 480), dtype=torch.uint8, device="cuda")
