@@ -103,7 +103,10 @@ hq_status int_linear_single(const uint8_t *xq, const float *x_scale, const uint8
     if (!fits_32bit(m, 1, n, 3, k)) return HQ_ERR_UNSUPPORTED;
     const float norm = static_cast<float>(1.0 / sqrt(static_cast<double>(had_block)));
     GemmArgs a{xq, x_scale, wq3, w_scale, bias, y, static_cast<uint32_t>(m), n, k, 1, 1, 0, 0, 0, 1, 0, norm, 4};
-    return launch_gemm(a, 3, y_dtype, static_cast<hipStream_t>(stream));
+    // |W_int H_raw| <= 8 x block: up to block 8 that is two signed base-16 digits ([-136, 119]) and the third
+    // plane is zero, so its pass is skipped (the integer output keeps all three sums)
+    const int planes = had_block <= 8 && y_dtype != HQ_I32 ? 2 : 3;
+    return launch_gemm(a, planes, y_dtype, static_cast<hipStream_t>(stream));
 }
 
 hq_status int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq, const float *w_scale,
@@ -164,7 +167,8 @@ hq_status int_conv2d_width(const uint8_t *xu3, const float *x_scale, const uint8
     const float norm = static_cast<float>(1.0 / sqrt(static_cast<double>(had_block)));
     GemmArgs a{xu3, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(pixels), c_out, c_in, h, w, 0, 0, 0, 1,
                1, norm, 4};
-    return launch_gemm(a, 27, y_dtype, static_cast<hipStream_t>(stream));
+    // |q H_raw| <= 8 x block: up to block 8 the third digit plane is zero and its nine steps are skipped
+    return launch_gemm(a, had_block <= 8 ? 18 : 27, y_dtype, static_cast<hipStream_t>(stream));
 }
 
 }  // namespace

@@ -72,10 +72,16 @@ constexpr int kOutF16 = 0, kOutF32 = 1, kOutI32 = 2;
 // a 3x3 convolution whose ACTIVATIONS are three such digit planes [3, pixels, k/2] (one scale for
 // the tensor): 27 steps, plane-major, one integer sum per plane over its nine taps.
 constexpr int kLinear = 0, kConvPerTap = 1, kConvSum = 2, kPlanes = 3, kConvPlanes = 4;
+// The same two kinds walking only the two low digit planes (the third is known to be zero when the
+// integers it encodes cannot exceed two signed base-16 digits, i.e. 8 x block <= 119).
+constexpr int kPlanes2 = 5, kConvPlanes2 = 6;
+constexpr bool is_planes(int kind) { return kind == kPlanes || kind == kPlanes2; }
+constexpr bool is_conv_planes(int kind) { return kind == kConvPlanes || kind == kConvPlanes2; }
 
 // steps of a tile's tap loop
 constexpr int taps_of(int kind) {
-    return kind == kLinear ? 1 : (kind == kPlanes ? 3 : (kind == kConvPlanes ? 27 : 9));
+    return kind == kLinear ? 1 : kind == kPlanes ? 3 : kind == kPlanes2 ? 2 : kind == kConvPlanes ? 27
+           : kind == kConvPlanes2 ? 18 : 9;
 }
 
 
@@ -316,12 +322,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
     constexpr int SHIFT = XB == 8 ? 0 : 8;                    // log2 of the factor the integer sums carry
     constexpr float UNIT = XB == 8 ? 1.0f : 1.0f / 256.0f;
     constexpr int TAPS = taps_of(KIND);
-    constexpr int WTAPS = KIND == kConvPlanes ? 9 : TAPS;             // taps of the weight tensor [n, WTAPS, k/2]
-    constexpr bool CONV = KIND == kConvPerTap || KIND == kConvSum || KIND == kConvPlanes;   // taps read shifted pixels
-    constexpr bool PER_TAP = KIND == kConvPerTap || KIND == kPlanes;  // one integer sum and one scale row per tap
+    constexpr int WTAPS = is_conv_planes(KIND) ? 9 : (is_planes(KIND) ? 3 : TAPS);   // taps of the weight tensor [n, WTAPS, k/2]
+    constexpr bool CONV = KIND == kConvPerTap || KIND == kConvSum || is_conv_planes(KIND);   // taps read shifted pixels
+    constexpr bool PER_TAP = KIND == kConvPerTap || is_planes(KIND);  // one integer sum and one scale row per tap
     constexpr bool SUM = KIND == kConvSum;                            // one integer sum over all taps
-    constexpr bool ZPAD = KIND == kConvSum || KIND == kConvPlanes;    // taps outside the image load zeros
-    constexpr bool FACC = PER_TAP || KIND == kConvPlanes;             // integer sums are folded into fp32 sums
+    constexpr bool ZPAD = KIND == kConvSum || is_conv_planes(KIND);    // taps outside the image load zeros
+    constexpr bool FACC = PER_TAP || is_conv_planes(KIND);             // integer sums are folded into fp32 sums
     constexpr int STAPS = PER_TAP ? TAPS : 1;       // rows of the activation-scale table
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int NT = 64 * NW;
@@ -455,7 +461,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
             for (int j = 0; j < SX_PER_T; ++j) {
                 const int e = tid + j * NT;
                 // the sums carry a factor 256 (both operands are 16 x code); digit plane t weighs 16^t
-                const float unit = KIND == kPlanes ? static_cast<float>(1 << (4 * (e / BP))) * UNIT : UNIT;
+                const float unit = is_planes(KIND) ? static_cast<float>(1 << (4 * (e / BP))) * UNIT : UNIT;
                 if (e < STAPS * BP) (&s_sx[k & 1][0][0])[e] = t_sx[j] * unit;
             }
             if (tid < BCO) {
@@ -494,7 +500,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
                 const uint32_t shift = static_cast<uint32_t>(((t / 3 - 1) * a.w + (t % 3 - 1)) * kbytes);
                 const uint32_t o = ld_b[j] + shift;
                 ld_bcur[j] = o < ld_bmax[j] ? o : ld_bmax[j];
-                if constexpr (KIND == kConvPlanes) ld_bcur[j] += static_cast<uint32_t>(step / 9) * (a.pixels * kbytes);
+                if constexpr (is_conv_planes(KIND)) ld_bcur[j] += static_cast<uint32_t>(step / 9) * (a.pixels * kbytes);
             } else {
                 ld_bcur[j] = ld_b[j];
             }
@@ -594,7 +600,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
                     for (int r = 0; r < 16; ++r) facc[tm][tn][r] = 0.f;
         }
         // digit planes of the activations, integer output: the exact sum over the planes
-        constexpr bool ISUM = KIND == kConvPlanes && OUT == kOutI32;
+        constexpr bool ISUM = is_conv_planes(KIND) && OUT == kOutI32;
         int iacc[ISUM ? TM : 1][ISUM ? TN : 1][16];
         if constexpr (ISUM) {
 #pragma unroll
@@ -679,7 +685,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
                 const uint32_t sa = lds_a + stage * STAGE_BYTES, sb = lds_b + stage * STAGE_BYTES;
                 Ops op[2];
                 read_packed<TM, TN, ROWB, 0>(op[0], sa, sb);
-                const bool sum_starts = SUM ? chunk == 0 : (KIND == kConvPlanes ? ch == 0 && tap % 9 == 0 : ch == 0);
+                const bool sum_starts = SUM ? chunk == 0 : (is_conv_planes(KIND) ? ch == 0 && tap % 9 == 0 : ch == 0);
                 chunk_steps<0, KS, TM, TN, ROWB>(op, sa, sb, sum_starts, multiply);
             }
 
@@ -687,7 +693,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
                 ch = 0;
                 // ---- end of a tap: fold the integer sums into the result (one sum over all taps:
                 // nothing to do before the last tap) ---------------------------------------------
-                const bool sum_ends = SUM ? tap == TAPS - 1 : (KIND == kConvPlanes ? tap % 9 == 8 : true);
+                const bool sum_ends = SUM ? tap == TAPS - 1 : (is_conv_planes(KIND) ? tap % 9 == 8 : true);
                 if (active && sum_ends) {
                 if constexpr (ISUM) {
                     // 256 x the plane's sum, weighted by 16^plane; stored after the last plane
@@ -737,7 +743,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
                 } else if constexpr (FACC) {
                     float s[TN];
                     read_tap_scales<TN>(s, lds_sx + (tb * STAPS + (PER_TAP ? tap : 0)) * BP * 4);
-                    if constexpr (KIND == kConvPlanes) {   // the plane's weight 16^plane
+                    if constexpr (is_conv_planes(KIND)) {   // the plane's weight 16^plane
                         const float weight = static_cast<float>(1 << (4 * (tap / 9)));
 #pragma unroll
                         for (int tn = 0; tn < TN; ++tn) s[tn] *= weight;
@@ -890,6 +896,13 @@ hq_status launch_config(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream
         if (y_dtype == HQ_F16) { HQ_GEMM_CASE(kPlanes, kOutF16) }
         if (y_dtype == HQ_F32) { HQ_GEMM_CASE(kPlanes, kOutF32) }
         if (y_dtype == HQ_I32) { HQ_GEMM_CASE(kPlanes, kOutI32) }
+    } else if (taps == 2) {    // two digit planes of the weights (floating-point output only)
+        if (y_dtype == HQ_F16) { HQ_GEMM_CASE(kPlanes2, kOutF16) }
+        if (y_dtype == HQ_F32) { HQ_GEMM_CASE(kPlanes2, kOutF32) }
+    } else if (taps == 18) {   // two digit planes of the activations
+        if (y_dtype == HQ_F16) { HQ_GEMM_CASE(kConvPlanes2, kOutF16) }
+        if (y_dtype == HQ_F32) { HQ_GEMM_CASE(kConvPlanes2, kOutF32) }
+        if (y_dtype == HQ_I32) { HQ_GEMM_CASE(kConvPlanes2, kOutI32) }
     } else if (taps == 27) {
         if (y_dtype == HQ_F16) { HQ_GEMM_CASE(kConvPlanes, kOutF16) }
         if (y_dtype == HQ_F32) { HQ_GEMM_CASE(kConvPlanes, kOutF32) }

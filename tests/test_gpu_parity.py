@@ -210,9 +210,10 @@ def test_single_scheme_tiny_linears(hq, idx):
     run_linear_single(hq, workloads.tiny_layers()[idx])
 
 
-@pytest.mark.parametrize("block", [1, 16, 128])
+@pytest.mark.parametrize("block", [1, 4, 8, 16, 128])
 def test_single_scheme_other_block_sizes(hq, block):
-    """H = I (all higher digits zero), a small block, and the largest block (sums up to 8 * 128)."""
+    """H = I (all higher digits zero), blocks up to 8 (third digit plane zero: its pass is skipped),
+    a block just above that, and the largest block (sums up to 8 * 128)."""
     layer = workloads.tiny_layers()[1]          # k = 128, fp32 input
     run_linear_single(hq, layer, block)
 
@@ -294,7 +295,7 @@ def run_conv_width(hq, layer, block):
     return flips, err
 
 
-@pytest.mark.parametrize("idx,block", [(3, 1), (4, 4), (6, 1), (7, 16), (7, 2)])
+@pytest.mark.parametrize("idx,block", [(3, 1), (4, 4), (6, 1), (7, 16), (7, 2), (7, 8)])
 def test_width_conv_tiny_layers(hq, idx, block):
     run_conv_width(hq, workloads.tiny_layers()[idx], block)
 
