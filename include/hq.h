@@ -279,7 +279,8 @@ hq_status hq_quantize_weights_single(const void *w, hq_dtype w_dtype, int n_out,
  *
  * acc_0 + 16 acc_1 + 256 acc_2 is the integer (XH)_int H_raw W_int^T of the paper's equation;
  * the three sums are combined in fp32.  Shapes as in hq_int_linear, with wq3 [n, 3, k/2].
- * y_dtype == HQ_I32 writes the three sums, [m, 3, n] (bias and scales ignored).
+ * y_dtype == HQ_I32 writes the three sums, [m, 3, n] (bias and scales ignored).  For floating-point
+ * outputs and had_block <= 8 the third plane (zero by construction: |W_int H_raw| <= 64) is not read.
  */
 hq_status hq_int_linear_single(const uint8_t *xq, const float *x_scale, const uint8_t *wq3,
                                const float *w_scale, const void *bias, int64_t m, int n, int k,
@@ -320,8 +321,10 @@ hq_status hq_act_hadamard_quant_width(const void *x, hq_dtype x_dtype, int nb, i
  * as acc_0 + 16 acc_1 + 256 acc_2).  A tap outside the image contributes 0.
  *   xu3 [3, nb, h, w, c_in/2], wq [c_out, 3, 3, c_in/2] (codes of the un-transformed weights),
  *   w_scale [c_out], bias [c_out] of y_dtype or NULL, y [nb, h, w, c_out].
- * Built: R = S = 3, stride 1, pad 1; c_in a multiple of 64, 9 c_in < 131072.
- * y_dtype == HQ_I32 writes acc, [nb, h, w, c_out].
+ * Built: R = S = 3, pad 1, stride 1 (y [nb, h, w, c_out]) or stride 2 (y [nb, (h-1)/2 + 1, (w-1)/2 + 1, c_out],
+ * the window of output (p, q) centred on input (2p, 2q)); c_in a multiple of 64, 9 c_in < 131072.
+ * Up to had_block = 8 the third digit plane is zero by construction and is not read.
+ * y_dtype == HQ_I32 writes acc, [nb, h_out, w_out, c_out].
  */
 hq_status hq_int_conv2d_width(const uint8_t *xu3, const float *x_scale, const uint8_t *wq,
                               const float *w_scale, const void *bias, int nb, int h, int w,
@@ -336,9 +339,9 @@ hq_status hq_int_conv2d_width(const uint8_t *xu3, const float *x_scale, const ui
  * hq_quantize_weights with a_bits = w_bits = 8 write one int8 code per byte (xq [m, k],
  * wq [n_out, taps, k_in]); the two calls below take such codes.  The codes feed the int8
  * matrix instruction as they are.  Everything else (scales, per-tap sums of a convolution,
- * bias, HQ_I32 outputs, error behaviour) is as in hq_int_linear / hq_int_conv2d; the
- * convolution is built for stride 1 only (R = S in {1, 3}, pad (R-1)/2); k (c_in) a
- * multiple of 64.
+ * bias, HQ_I32 outputs, error behaviour) is as in hq_int_linear / hq_int_conv2d, including the
+ * built geometries of the convolution (R = S in {1, 3} at stride 1, pad (R-1)/2; R = S = 3 at
+ * stride 2, pad 1); k (c_in) a multiple of 64.
  */
 /*
  * Mixed widths (the paper also reports W8A4): the activation path of hq_act_hadamard_quant with

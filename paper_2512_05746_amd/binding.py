@@ -396,9 +396,9 @@ def hq_act_hadamard_quant_width(x: torch.Tensor, x_scale: torch.Tensor, had_bloc
 def hq_int_conv2d_width(xu3: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torch.Tensor,
                         w_scale: Optional[torch.Tensor], bias: Optional[torch.Tensor] = None,
                         had_block: int = 64, y_dtype: torch.dtype = torch.float16,
-                        out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """xu3 [3, N, H, W, Cin/2], wq [Cout, 9, Cin/2] (or [Cout, 3, 3, Cin/2]) -> y [N, H, W, Cout];
-    y_dtype int32 returns the exact integer sums."""
+                        out: Optional[torch.Tensor] = None, stride: int = 1) -> torch.Tensor:
+    """xu3 [3, N, H, W, Cin/2], wq [Cout, 9, Cin/2] (or [Cout, 3, 3, Cin/2]) -> y [N, Ho, Wo, Cout]
+    (same size for stride 1; stride 2 halves it, rounding up); y_dtype int32 returns the exact integer sums."""
     _codes(xu3, torch.uint8, "xu3"), _codes(wq, torch.uint8, "wq")
     if xu3.dim() != 5 or xu3.shape[0] != 3:
         raise ValueError("xu3 must be [3, N, H, W, Cin/2]")
@@ -408,9 +408,10 @@ def hq_int_conv2d_width(xu3: torch.Tensor, x_scale: Optional[torch.Tensor], wq: 
         raise ValueError("wq does not match xu3 in Cin or is not a 3x3 kernel")
     _vec(x_scale, 1, torch.float32, "x_scale"), _vec(w_scale, c_out, torch.float32, "w_scale")
     _vec(bias, c_out, y_dtype, "bias")
-    y = _out(out, (nb, h, w, c_out), y_dtype, xu3.device)
+    ho, wo = _conv_out(h, w, 3, stride, 1)
+    y = _out(out, (nb, ho, wo, c_out), y_dtype, xu3.device)
     _check("hq_int_conv2d_width", load_library().hq_int_conv2d_width(
-        _ptr(xu3), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), nb, h, w, kb * 2, c_out, 3, 3, 1, 1,
+        _ptr(xu3), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), nb, h, w, kb * 2, c_out, 3, 3, stride, 1,
         had_block, _ptr(y), _DTYPES[y_dtype], _stream()))
     return y
 
@@ -450,9 +451,10 @@ def hq_int_linear_i8(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torc
 def hq_int_conv2d_i8(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torch.Tensor,
                      w_scale: Optional[torch.Tensor], bias: Optional[torch.Tensor] = None,
                      ksize: int = 3, y_dtype: torch.dtype = torch.float16,
-                     out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """xq int8 [N, H, W, Cin], wq int8 [Cout, ksize*ksize, Cin] -> y [N, H, W, Cout] (stride 1, same
-    size); y_dtype int32 returns the per-tap sums [N, H, W, ksize*ksize, Cout]."""
+                     out: Optional[torch.Tensor] = None, stride: int = 1) -> torch.Tensor:
+    """xq int8 [N, H, W, Cin], wq int8 [Cout, ksize*ksize, Cin] -> y [N, Ho, Wo, Cout] (same size for
+    stride 1; ksize 3 at stride 2 halves it, rounding up); y_dtype int32 returns the per-tap sums
+    [N, Ho, Wo, ksize*ksize, Cout]."""
     _codes(xq, torch.int8, "xq"), _codes(wq, torch.int8, "wq")
     nb, h, w, c_in = xq.shape
     c_out = wq.shape[0]
@@ -461,9 +463,10 @@ def hq_int_conv2d_i8(xq: torch.Tensor, x_scale: Optional[torch.Tensor], wq: torc
         raise ValueError("wq does not match xq in Cin or the kernel size")
     _vec(x_scale, nb * h * w, torch.float32, "x_scale"), _vec(w_scale, c_out, torch.float32, "w_scale")
     _vec(bias, c_out, y_dtype, "bias")
-    shape = (nb, h, w, taps, c_out) if (y_dtype == torch.int32 and taps > 1) else (nb, h, w, c_out)
+    ho, wo = _conv_out(h, w, ksize, stride, (ksize - 1) // 2)
+    shape = (nb, ho, wo, taps, c_out) if (y_dtype == torch.int32 and taps > 1) else (nb, ho, wo, c_out)
     y = _out(out, shape, y_dtype, xq.device)
     _check("hq_int_conv2d_i8", load_library().hq_int_conv2d_i8(
-        _ptr(xq), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), nb, h, w, c_in, c_out, ksize, ksize, 1,
+        _ptr(xq), _ptr(x_scale), _ptr(wq), _ptr(w_scale), _ptr(bias), nb, h, w, c_in, c_out, ksize, ksize, stride,
         (ksize - 1) // 2, _ptr(y), _DTYPES[y_dtype], _stream()))
     return y

@@ -118,9 +118,9 @@ hq_status int_conv2d(const uint8_t *xq, const float *x_scale, const uint8_t *wq,
     }
     const int64_t pixels = static_cast<int64_t>(nb) * h * w;
     hq_status st = check_common(xq, x_scale, wq, w_scale, bias, pixels, c_out, c_in, y, y_dtype,
-                                bits == 4 && stride == 1 ? 8 : 64);
+                                bits == 4 && stride == 1 ? 8 : 64);   // (8-bit codes and stride 2: whole 64-code chunks)
     if (st != HQ_OK) return st;
-    const bool down = r == 3 && s == 3 && stride == 2 && pad == 1 && bits == 4;   // the downsampling convolution
+    const bool down = r == 3 && s == 3 && stride == 2 && pad == 1 && !(bits == 8 && sx_static);   // the downsampling convolution
     if (!down && (r != s || (r != 1 && r != 3) || stride != 1 || pad != (r - 1) / 2)) return HQ_ERR_UNSUPPORTED;
     if (!fits_32bit(pixels, w, c_out, r * s, bits == 8 ? 2 * c_in : c_in)) return HQ_ERR_UNSUPPORTED;
     // one sum over all taps: 256 * (64 per product) * (codes per sum) must stay below 2^31
@@ -160,13 +160,21 @@ hq_status int_conv2d_width(const uint8_t *xu3, const float *x_scale, const uint8
     hq_status st = check_common(xu3, x_scale, wq, w_scale, bias, pixels, c_out, c_in, y, y_dtype);
     if (st != HQ_OK) return st;
     if (!hq::pow2_upto_128(had_block) || had_block > 64 || w % had_block != 0) return HQ_ERR_SHAPE;
-    if (r != 3 || s != 3 || stride != 1 || pad != 1) return HQ_ERR_UNSUPPORTED;
+    if (r != 3 || s != 3 || (stride != 1 && stride != 2) || pad != 1) return HQ_ERR_UNSUPPORTED;
     // three planes of activations behind one 32-bit offset; 256 * 64 * (codes per plane sum) below 2^31
     if (!fits_32bit(3 * pixels, w, c_out, 9, c_in)) return HQ_ERR_UNSUPPORTED;
     if (static_cast<int64_t>(c_in) * 9 >= 131072) return HQ_ERR_SHAPE;
     const float norm = static_cast<float>(1.0 / sqrt(static_cast<double>(had_block)));
     GemmArgs a{xu3, x_scale, wq, w_scale, bias, y, static_cast<uint32_t>(pixels), c_out, c_in, h, w, 0, 0, 0, 1,
                1, norm, 4};
+    if (stride == 2) {   // output [nb, (h - 1) / 2 + 1, (w - 1) / 2 + 1, c_out]: the tile kernel's stride-2 form
+        a.stride = 2;
+        a.h_out = (h - 1) / 2 + 1;
+        a.w_out = (w - 1) / 2 + 1;
+        a.in_pixels = static_cast<uint32_t>(pixels);
+        a.pixels = static_cast<uint32_t>(static_cast<int64_t>(nb) * a.h_out * a.w_out);
+        return hq_gemm_launch_64x64(a, had_block <= 8 ? 18 : 27, y_dtype, static_cast<hipStream_t>(stream));
+    }
     // |q H_raw| <= 8 x block: up to block 8 the third digit plane is zero and its nine steps are skipped
     return launch_gemm(a, had_block <= 8 ? 18 : 27, y_dtype, static_cast<hipStream_t>(stream));
 }
@@ -233,7 +241,7 @@ extern "C" hq_status hq_int_conv2d_i8(const int8_t *xq, const float *x_scale, co
 extern "C" const char *hq_int_conv2d_kernel_name(int nb, int h, int w, int c_in, int c_out, int r, int s, int stride,
                                                  int pad, int static_scale, int bits) {
     if (nb <= 0 || h <= 0 || w <= 0 || c_in <= 0 || c_out <= 0 || (bits != 4 && bits != 8)) return "unsupported";
-    if (r == 3 && s == 3 && stride == 2 && pad == 1 && bits == 4) return "tile (stride 2)";
+    if (r == 3 && s == 3 && stride == 2 && pad == 1) return c_in % 64 == 0 ? "tile (stride 2)" : "unsupported";
     if (r != s || (r != 1 && r != 3) || stride != 1 || pad != (r - 1) / 2) return "unsupported";
     if (c_in % 8 != 0 || (bits == 8 && c_in % 64 != 0)) return "unsupported";
     if (c_in % 64 != 0) return "small-channel-count";

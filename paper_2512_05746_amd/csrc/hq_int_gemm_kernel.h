@@ -318,7 +318,7 @@ template <int TM, int TN, int WAVES_M, int WAVES_N, int KIND, int OUT, int KCH, 
           bool S2 = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(GemmArgs a) {
     static_assert(XB == 4 || XB == 8, "4-bit codes in pairs or int8 codes");
-    static_assert(!S2 || KIND == kConvPerTap || KIND == kConvSum, "stride 2 is a 3x3 window's");
+    static_assert(!S2 || KIND == kConvPerTap || KIND == kConvSum || is_conv_planes(KIND), "stride 2 is a 3x3 window's");
     constexpr int SHIFT = XB == 8 ? 0 : 8;                    // log2 of the factor the integer sums carry
     constexpr float UNIT = XB == 8 ? 1.0f : 1.0f / 256.0f;
     constexpr int TAPS = taps_of(KIND);
@@ -500,7 +500,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void int_gemm_kernel(G
                 const uint32_t shift = static_cast<uint32_t>(((t / 3 - 1) * a.w + (t % 3 - 1)) * kbytes);
                 const uint32_t o = ld_b[j] + shift;
                 ld_bcur[j] = o < ld_bmax[j] ? o : ld_bmax[j];
-                if constexpr (is_conv_planes(KIND)) ld_bcur[j] += static_cast<uint32_t>(step / 9) * (a.pixels * kbytes);
+                // (the digit planes are planes of the INPUT tensor)
+                if constexpr (is_conv_planes(KIND))
+                    ld_bcur[j] += static_cast<uint32_t>(step / 9) * ((S2 ? a.in_pixels : a.pixels) * kbytes);
             } else {
                 ld_bcur[j] = ld_b[j];
             }
@@ -840,18 +842,37 @@ hq_status launch_config(const GemmArgs &a, int taps, hq_dtype y_dtype, hipStream
     const bool wide = (a.bits == 8 ? a.k : a.k / 2) % 96 == 0;   // whole chunks of six 16-byte pieces per row
     if (a.stride == 2) {
         if constexpr (WITH_S2) {
-            if (taps != 9 || a.bits != 4) return HQ_ERR_UNSUPPORTED;
-#define HQ_GEMM_CASE_S2(KIND, OUT)                                                                       \
-    if (wide) return launch_tile<TM, TN, WAVES_M, WAVES_N, KIND, OUT, 6, NSTAGE_WIDE, OCC, 4, true>(a, stream); \
-    return launch_tile<TM, TN, WAVES_M, WAVES_N, KIND, OUT, 2, 4, OCC, 4, true>(a, stream);
+#define HQ_GEMM_CASE_S2(KIND, OUT, XB)                                                                    \
+    if (wide) return launch_tile<TM, TN, WAVES_M, WAVES_N, KIND, OUT, 6, NSTAGE_WIDE, OCC, XB, true>(a, stream); \
+    return launch_tile<TM, TN, WAVES_M, WAVES_N, KIND, OUT, 2, 4, OCC, XB, true>(a, stream);
+            if (a.bits == 8) {   // int8 codes: per-pixel scales only
+                if (taps != 9 || a.sx_static) return HQ_ERR_UNSUPPORTED;
+                if (y_dtype == HQ_F16) { HQ_GEMM_CASE_S2(kConvPerTap, kOutF16, 8) }
+                if (y_dtype == HQ_F32) { HQ_GEMM_CASE_S2(kConvPerTap, kOutF32, 8) }
+                if (y_dtype == HQ_I32) { HQ_GEMM_CASE_S2(kConvPerTap, kOutI32, 8) }
+                return HQ_ERR_DTYPE;
+            }
+            if (taps == 27 || taps == 18) {   // digit planes of the activations (width-axis convolution)
+                if (taps == 27) {
+                    if (y_dtype == HQ_F16) { HQ_GEMM_CASE_S2(kConvPlanes, kOutF16, 4) }
+                    if (y_dtype == HQ_F32) { HQ_GEMM_CASE_S2(kConvPlanes, kOutF32, 4) }
+                    if (y_dtype == HQ_I32) { HQ_GEMM_CASE_S2(kConvPlanes, kOutI32, 4) }
+                } else {
+                    if (y_dtype == HQ_F16) { HQ_GEMM_CASE_S2(kConvPlanes2, kOutF16, 4) }
+                    if (y_dtype == HQ_F32) { HQ_GEMM_CASE_S2(kConvPlanes2, kOutF32, 4) }
+                    if (y_dtype == HQ_I32) { HQ_GEMM_CASE_S2(kConvPlanes2, kOutI32, 4) }
+                }
+                return HQ_ERR_DTYPE;
+            }
+            if (taps != 9) return HQ_ERR_UNSUPPORTED;
             if (a.sx_static) {
-                if (y_dtype == HQ_F16) { HQ_GEMM_CASE_S2(kConvSum, kOutF16) }
-                if (y_dtype == HQ_F32) { HQ_GEMM_CASE_S2(kConvSum, kOutF32) }
-                if (y_dtype == HQ_I32) { HQ_GEMM_CASE_S2(kConvSum, kOutI32) }
+                if (y_dtype == HQ_F16) { HQ_GEMM_CASE_S2(kConvSum, kOutF16, 4) }
+                if (y_dtype == HQ_F32) { HQ_GEMM_CASE_S2(kConvSum, kOutF32, 4) }
+                if (y_dtype == HQ_I32) { HQ_GEMM_CASE_S2(kConvSum, kOutI32, 4) }
             } else {
-                if (y_dtype == HQ_F16) { HQ_GEMM_CASE_S2(kConvPerTap, kOutF16) }
-                if (y_dtype == HQ_F32) { HQ_GEMM_CASE_S2(kConvPerTap, kOutF32) }
-                if (y_dtype == HQ_I32) { HQ_GEMM_CASE_S2(kConvPerTap, kOutI32) }
+                if (y_dtype == HQ_F16) { HQ_GEMM_CASE_S2(kConvPerTap, kOutF16, 4) }
+                if (y_dtype == HQ_F32) { HQ_GEMM_CASE_S2(kConvPerTap, kOutF32, 4) }
+                if (y_dtype == HQ_I32) { HQ_GEMM_CASE_S2(kConvPerTap, kOutI32, 4) }
             }
 #undef HQ_GEMM_CASE_S2
             return HQ_ERR_DTYPE;

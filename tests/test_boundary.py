@@ -222,7 +222,7 @@ def test_width_axis_argument_errors(lib):
     assert conv(*args(block=16)) == SHAPE
     assert conv(*args(cin=20)) == SHAPE          # not a multiple of 8
     assert conv(*args(r=1, s=1, pad=0)) == UNSUPPORTED
-    assert conv(*args(stride=2)) == UNSUPPORTED
+    assert conv(*args(stride=3)) == UNSUPPORTED
 
 
 def test_int8_code_argument_errors(lib):
@@ -231,7 +231,7 @@ def test_int8_code_argument_errors(lib):
     assert lin(P, P, P, P, None, 8, 8, 96, P, 0, None) == SHAPE
     assert lin(P, P, P, P, None, 8, 8, 64, P, 5, None) == DTYPE
     conv = lib.hq_int_conv2d_i8
-    assert conv(P, P, P, P, None, 1, 4, 4, 64, 8, 3, 3, 2, 1, P, 0, None) == UNSUPPORTED
+    assert conv(P, P, P, P, None, 1, 4, 4, 64, 8, 3, 3, 3, 1, P, 0, None) == UNSUPPORTED
     assert conv(P, None, P, P, None, 1, 4, 4, 64, 8, 3, 3, 1, 1, P, 0, None) == NULL
     q8 = lib.hq_act_hadamard_quant_i8
     assert q8(P, 0, 8, 64, 64, 4, None, P, None) == NULL

@@ -706,6 +706,49 @@ def test_int_conv_stride_2(hq, nb, h, w, cin, cout):
     check_y("y (static)", y_g, y_o, rtol=1e-5)
 
 
+@pytest.mark.parametrize("nb,h,w,cin,cout", [(1, 1, 1, 64, 8), (2, 5, 7, 64, 16), (3, 9, 6, 192, 24), (1, 33, 31, 64, 130),
+                                             (5, 12, 20, 384, 64)])
+def test_int8_conv_stride_2(hq, nb, h, w, cin, cout):
+    """The downsampling convolution with 8-bit codes: per-tap int32 sums bit for bit, fp32 output."""
+    rng = np.random.default_rng(nb * 1000 + h * 100 + w * 10 + cin + cout + 8)
+    xq = rng.integers(-128, 128, (nb, h, w, cin)).astype(np.int8)
+    wq = rng.integers(-128, 128, (cout, 3, 3, cin)).astype(np.int8)
+    sx = rng.uniform(0.01, 1.0, (nb, h, w)).astype(np.float32)
+    sw = rng.uniform(0.001, 0.1, cout).astype(np.float32)
+    bias = rng.standard_normal(cout).astype(np.float32)
+    xq_d, wq_d = dev(xq), dev(wq.reshape(cout, 9, cin))
+    acc_o, y_o = oracle.int_conv2d(xq, sx, wq, sw, bias, stride=2, pad=1)
+    acc_g = host(hq.hq_int_conv2d_i8(xq_d, None, wq_d, None, None, ksize=3, stride=2, y_dtype=torch.int32))
+    assert acc_g.shape == acc_o.shape and np.array_equal(acc_g, acc_o)
+    y_g = host(hq.hq_int_conv2d_i8(xq_d, dev(sx), wq_d, dev(sw), dev(bias), ksize=3, stride=2, y_dtype=torch.float32))
+    check_y("y", y_g, y_o, rtol=1e-5)
+
+
+@pytest.mark.parametrize("nb,h,w,cin,cout,block", [(2, 5, 8, 64, 16, 8), (1, 9, 16, 192, 24, 16), (3, 12, 32, 128, 70, 32),
+                                                   (2, 7, 4, 64, 8, 1), (1, 16, 64, 64, 40, 64)])
+def test_width_conv_stride_2(hq, nb, h, w, cin, cout, block):
+    """The paper's width-axis convolution at stride 2 (two and three digit planes): the exact integer
+    sums on the oracle's codes, bit for bit, and the fp32 output."""
+    rng = np.random.default_rng(nb * 1000 + h * 100 + w * 10 + cin + cout + block)
+    q = rng.integers(-8, 8, (nb, h, w, cin)).astype(np.int8)
+    wq = rng.integers(-8, 8, (cout, 3, 3, cin)).astype(np.int8)
+    sw = rng.uniform(0.001, 0.1, cout).astype(np.float32)
+    bias = rng.standard_normal(cout).astype(np.float32)
+    hb = np.kron(np.eye(w // block, dtype=np.int64), np.rint(oracle.hadamard_raw(block)).astype(np.int64))
+    u = np.einsum("nhwc,wv->nhvc", q.astype(np.int64), hb)
+    d0 = ((u + 8) % 16) - 8
+    r1 = (u - d0) // 16
+    d1 = ((r1 + 8) % 16) - 8
+    planes = dev(pack_codes(np.stack([d0, d1, (r1 - d1) // 16]).astype(np.int8)))
+    acc_o, y_o = oracle.int_conv2d_width(q, 0.3, wq, sw, block, bias, stride=2, pad=1)
+    wq_d = dev(pack_codes(wq.reshape(cout, 9, cin)))
+    acc_g = host(hq.hq_int_conv2d_width(planes, None, wq_d, None, None, block, y_dtype=torch.int32, stride=2))
+    assert acc_g.shape == acc_o.shape and np.array_equal(acc_g, acc_o)
+    s1 = torch.tensor([0.3], dtype=torch.float32, device="cuda")
+    y_g = host(hq.hq_int_conv2d_width(planes, s1, wq_d, dev(sw), dev(bias), block, y_dtype=torch.float32, stride=2))
+    check_y("y", y_g, y_o, rtol=1e-5)
+
+
 @pytest.mark.parametrize("hw,c", [(64, 192), (32, 384), (16, 576)])
 def test_stride_2_downsampling_layers_full_size(hq, hw, c):
     """The three downsampling convolutions of an LDM-4-shaped UNet at batch 16, fp16 output with
