@@ -196,6 +196,37 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
     begin_fetch(0, false);
     for (int st = 0; st < NSTAGE - 1 && st < ulen_of[0]; ++st) issue_step();
 
+    // ---- table entries are requested first, so that their latency and that of the activation rows
+    //      below pass together -------------------------------------------------------------------------------
+    int t_mask = 0;
+    float t_sx[TAPS];
+    float t_sw = 0.f, t_bias = 0.f;
+    const int t_chan = NT - 1 - tid;   // (the last threads first: they have no pixel to look up)
+    if (tid < PX) {
+        const uint32_t pix = p0 + tid;
+        const uint32_t q = hq::div_magic31(pix, a.w, a.w_magic, a.w_shift);
+        const int ow = static_cast<int>(pix - q * a.w);
+        const int oh = static_cast<int>(q - hq::div_magic31(q, a.h, a.h_magic, a.h_shift) * a.h);
+        const int cm = (ow > 0 ? 1 : 0) | 2 | (ow + 1 < a.w ? 4 : 0);
+        t_mask = (oh > 0 ? cm : 0) | (cm << 3) | (oh + 1 < a.h ? cm << 6 : 0);
+        if (pix >= a.pixels) t_mask = 0;
+        if constexpr (!INT_OUT && !FUSED) {
+#pragma unroll
+            for (int t = 0; t < TAPS; ++t) {
+                uint32_t ip = pix + static_cast<uint32_t>((t / 3 - 1) * a.w + (t % 3 - 1));   // wraps below 0
+                ip = ip < last ? ip : last;
+                t_sx[t] = a.sx[ip];
+            }
+        }
+    }
+    if constexpr (!INT_OUT) {
+        if (t_chan < 192 && co0 + t_chan < a.n) {
+            const Out *bias = static_cast<const Out *>(a.bias);
+            t_sw = a.sw[co0 + t_chan];
+            t_bias = bias ? to_float(bias[co0 + t_chan]) : 0.f;
+        }
+    }
+
     // ---- activation tile: packed rows -> int8 (16 x code) in LDS -------------------------------------
     // Row r of the image is pixel p0 - halo + r (clamped into the tensor; rows outside the image are
     // only ever read under taps whose scale is 0).  Plane s (192-channel slice) at s * rows * 192; a row
@@ -300,11 +331,12 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
         const uint32_t pieces_per_row = 6u * S;
         const uint32_t total = static_cast<uint32_t>(rows) * pieces_per_row;
         const int64_t first = static_cast<int64_t>(p0) - halo;
-        for (uint32_t base = tid; base < total; base += NT * 5) {
-            v4i p[5];
-            uint32_t dst[5];
+        constexpr int BATCH = NWL == 3 ? 5 : 7;   // pieces per thread in flight: one batch covers a tile
+        for (uint32_t base = tid; base < total; base += NT * BATCH) {
+            v4i p[BATCH];
+            uint32_t dst[BATCH];
 #pragma unroll
-            for (int e = 0; e < 5; ++e) {
+            for (int e = 0; e < BATCH; ++e) {
                 const uint32_t q = base + NT * e;
                 if (q < total) {
                     const uint32_t row = hq::div_magic31(q, pieces_per_row, a.p_magic, a.p_shift);
@@ -319,7 +351,7 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
                 }
             }
 #pragma unroll
-            for (int e = 0; e < 5; ++e) {
+            for (int e = 0; e < BATCH; ++e) {
                 const uint32_t q = base + NT * e;
                 if (q < total) {
                     v4i first_half, second_half;
@@ -333,24 +365,10 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
 
     // ---- tables ------------------------------------------------------------------------------------------
     if (tid < PX) {
-        const uint32_t pix = p0 + tid;
-        const uint32_t q = hq::div_magic31(pix, a.w, a.w_magic, a.w_shift);
-        const int ow = static_cast<int>(pix - q * a.w);
-        const int oh = static_cast<int>(q - hq::div_magic31(q, a.h, a.h_magic, a.h_shift) * a.h);
-        const int cm = (ow > 0 ? 1 : 0) | 2 | (ow + 1 < a.w ? 4 : 0);
-        int mask = (oh > 0 ? cm : 0) | (cm << 3) | (oh + 1 < a.h ? cm << 6 : 0);
-        if (pix >= a.pixels) mask = 0;
-        s_mask[tid] = mask;
+        s_mask[tid] = t_mask;
         if constexpr (!INT_OUT && !FUSED) {
-            float v[TAPS];
 #pragma unroll
-            for (int t = 0; t < TAPS; ++t) {
-                uint32_t ip = pix + static_cast<uint32_t>((t / 3 - 1) * a.w + (t % 3 - 1));   // wraps below 0
-                ip = ip < last ? ip : last;
-                v[t] = a.sx[ip];
-            }
-#pragma unroll
-            for (int t = 0; t < TAPS; ++t) s_sx[t * PX + tid] = ((mask >> t) & 1) ? v[t] * (1.0f / 256.0f) : 0.f;
+            for (int t = 0; t < TAPS; ++t) s_sx[t * PX + tid] = ((t_mask >> t) & 1) ? t_sx[t] * (1.0f / 256.0f) : 0.f;
         }
     }
     if constexpr (!INT_OUT && FUSED) {
@@ -365,11 +383,9 @@ __global__ __launch_bounds__(64 << NWL, NWL == 3 ? 1 : 2) void conv3x3_res_kerne
         }
     }
     if constexpr (!INT_OUT) {
-        for (int c = NT - 1 - tid; c < 192; c += NT) {   // (the last threads first: they have no pixel to look up)
-            const bool ok = co0 + c < a.n;
-            const Out *bias = static_cast<const Out *>(a.bias);
-            s_sw[c] = ok ? a.sw[co0 + c] : 0.f;
-            s_bias[c] = ok && bias ? to_float(bias[co0 + c]) : 0.f;
+        if (t_chan < 192) {
+            s_sw[t_chan] = t_sw;
+            s_bias[t_chan] = t_bias;
         }
     }
     __syncthreads();   // activations and tables visible (also waits for this wave's first weight loads)
