@@ -481,6 +481,8 @@ def main():
                             "rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this command "
                             "(profiles/bench_config5_hbm_traffic.txt), not measured in this run",
             "ops_per_launch": round(conv3_ops / len(conv3)), "us_per_launch": round(conv3_us / len(conv3), 2),
+            "duration": "period of back-to-back launches in one graph replay (HIP events on the launch stream); "
+                        "rocprofv3's per-dispatch durations of the same kernels run a few percent longer",
         },
         "hadamard_quant": {
             "kernel": "hq_act_hadamard_quant on %s fp16" % (list(xb.shape),),
