@@ -1222,6 +1222,61 @@ def test_hip_graph_replay_of_the_other_schemes(hq):
         torch.cuda.synchronize()
 
 
+def test_hip_graph_replay_of_the_one_launch_layers_and_integer_outputs(hq):
+    """The one-launch 3x3 and linear layers, the int8-resident convolution and the integer outputs that
+    are accumulated with atomics (their output is zeroed by a kernel inside the call, not by a memset
+    node) captured into one HIP graph: every replay must reproduce the eager results bit for bit."""
+    rng = np.random.default_rng(11)
+    nb, h, w, cin, cout = 8, 41, 50, 192, 250
+    x = dev((rng.standard_normal((nb, h, w, cin)) * 2).astype(np.float16))
+    wc = dev(rng.integers(-8, 8, (cout, 9, cin // 2 * 2)).astype(np.int8))
+    wq = dev(pack_codes(rng.integers(-8, 8, (cout, 9, cin)).astype(np.int8)))
+    sw = dev(rng.uniform(0.001, 0.1, cout).astype(np.float32))
+    wl = dev(pack_codes(rng.integers(-8, 8, (cout, cin)).astype(np.int8)))
+    xq = torch.empty((nb, h, w, cin // 2), dtype=torch.uint8, device="cuda")
+    sx = torch.empty((nb, h, w), dtype=torch.float32, device="cuda")
+    xs = dev(rng.integers(-8, 8, (1, 16, 16, 192)).astype(np.int8))      # a shape of the wave-split kernel
+    xs_q = dev(pack_codes(host(xs)))
+    ws_q = dev(pack_codes(rng.integers(-8, 8, (100, 9, 192)).astype(np.int8)))
+    ys = [torch.empty((nb, h, w, cout), dtype=torch.float16, device="cuda") for _ in range(3)]
+    yi = torch.empty((nb, h, w, 9, cout), dtype=torch.int32, device="cuda")
+    yw = torch.empty((1, 16, 16, 9, 100), dtype=torch.int32, device="cuda")
+    del wc
+    assert hq.hq_int_conv2d_kernel_name(nb, h, w, cin, cout).startswith("activation-resident-int8")
+    assert hq.hq_int_conv2d_kernel_name(1, 16, 16, 192, 100) == "wave-split"
+
+    def run():
+        hq.hq_act_quant_int_conv2d(x, wq, sw, None, y_dtype=torch.float16, out=ys[0])
+        hq.hq_act_quant_int_linear(x, wl, sw, None, y_dtype=torch.float16, out=ys[1])
+        hq.hq_act_hadamard_quant(x, 64, 4, out=(xq, sx))
+        hq.hq_int_conv2d(xq, sx, wq, sw, None, ksize=3, y_dtype=torch.float16, out=ys[2])
+        hq.hq_int_conv2d(xq, None, wq, None, None, ksize=3, y_dtype=torch.int32, out=yi)
+        hq.hq_int_conv2d(xs_q, None, ws_q, None, None, ksize=3, y_dtype=torch.int32, out=yw)
+
+    outs = ys + [yi, yw]
+    run()
+    want = [host(t).copy() for t in outs]
+    assert np.array_equal(want[0], want[2]), "the one-launch layer differs from the two calls"
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for i in range(4):
+        for t in outs:
+            t.fill_(7)
+        torch.cuda.synchronize()
+        graph.replay()
+        for j, t in enumerate(outs):
+            assert np.array_equal(host(t), want[j]), "replay %d output %d" % (i, j)
+        run()   # eager work between replays
+        torch.cuda.synchronize()
+
+
 def test_two_streams_at_once(hq):
     """The library keeps no state: two layers run on two streams at the same time and both results
     equal those of running them one after the other."""
