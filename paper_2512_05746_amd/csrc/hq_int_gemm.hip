@@ -52,26 +52,31 @@ enum ConvKernel { kConvKernelTile = 0, kConvKernelWave = 1, kConvKernelHalo = 2,
 
 ConvKernel choose_conv_kernel(int64_t pixels, int w, int c_in, int c_out, int r, int sx_static, int bits) {
     if (bits == 8 || r != 3) return kConvKernelTile;   // the other kernels expand nibbles, 3x3 only
-    // Per-pixel scales, 192-channel slices, an activation tile that fits the LDS as int8 and at least
-    // half a tile per CU: the eight-wave kernel with the expanded activation tile resident.
-    if (!sx_static && hq_conv3x3_res_fits(pixels, w, c_in, c_out)) return kConvKernelRes;
-    // A 3x3 layer with about one 64x64 output tile per CU or fewer cannot fill the machine with
-    // whole tiles: it takes the kernel that also splits a tile's K range over waves.  (With one
-    // scale for the tensor that kernel still combines per-tap sums in fp32, which equals the one
-    // integer sum times one product of scales up to fp32 rounding.)
     const int64_t cus = hq::compute_units();
-    const int64_t tiles64 = ((pixels + 63) / 64) * ((c_out + 63) / 64);
-    if (c_in % 192 == 0 && tiles64 * 4 <= 5 * cus) return kConvKernelWave;
-    // One scale for the tensor and at least one 64 x 256 tile per CU: no per-tap fold at all, the
-    // kernel that keeps the packed activation tile in LDS for all nine taps, three workgroups per CU.
-    // (It also serves per-pixel scales with one 192-channel slice where the int8-resident kernel
-    // above does not fit, e.g. very wide images.)
+    // At least one 64 x 256 tile per CU and image rows short enough for the packed activation tile of
+    // the four-wave kernel that keeps it in LDS for all nine taps.
     const int64_t tiles256 = ((pixels + 255) / 256) * ((c_out + 63) / 64);
     GemmArgs probe{};
     probe.k = c_in;
     probe.w = w;
     probe.pixels = static_cast<uint32_t>(pixels);
-    if ((sx_static || c_in == 192) && tiles256 >= cus && hq_conv3x3_halo_fits(probe, HQ_F16)) return kConvKernelHalo;
+    const bool halo_ok = tiles256 >= cus && hq_conv3x3_halo_fits(probe, HQ_F16);
+    // Per-pixel scales and ONE 192-channel slice: that kernel is still the fastest (measured 30.4 against
+    // 31.9 us on 64 x 64 x 192 at batch 16, buffers rotating through HBM).
+    if (!sx_static && c_in == 192 && halo_ok) return kConvKernelHalo;
+    // Per-pixel scales, 192-channel slices, an activation tile that fits the LDS as int8 and at least
+    // half a tile per CU: the kernel with the expanded activation tile resident, whose workgroup
+    // splits the K range over its waves so that one round of tiles fills the machine.
+    if (!sx_static && hq_conv3x3_res_fits(pixels, w, c_in, c_out)) return kConvKernelRes;
+    // A 3x3 layer with about one 64x64 output tile per CU or fewer cannot fill the machine with
+    // whole tiles: it takes the kernel that also splits a tile's K range over waves.  (With one
+    // scale for the tensor that kernel still combines per-tap sums in fp32, which equals the one
+    // integer sum times one product of scales up to fp32 rounding.)
+    const int64_t tiles64 = ((pixels + 63) / 64) * ((c_out + 63) / 64);
+    if (c_in % 192 == 0 && tiles64 * 4 <= 5 * cus) return kConvKernelWave;
+    // One scale for the tensor: no per-tap fold at all, the kernel with the packed activation tile in
+    // LDS at three workgroups per CU.
+    if (sx_static && halo_ok) return kConvKernelHalo;
     return kConvKernelTile;
 }
 

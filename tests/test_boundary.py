@@ -35,8 +35,9 @@ def test_conv_kernel_choice_is_a_function_of_the_geometry(lib):
     """The kernel family is reported per geometry (no output type among the arguments): the three
     3x3 families are each reachable, and geometries that are not built say so."""
     name = hq.hq_int_conv2d_kernel_name
-    assert name(16, 64, 64, 192, 192) == "activation-resident-int8 (128 pixels, 4 waves)"
-    assert name(3, 79, 70, 192, 330) == "activation-resident-int8 (256 pixels)"
+    assert name(16, 64, 64, 192, 192) == "activation-resident"
+    assert name(20, 50, 50, 192, 64) == "activation-resident-int8 (128 pixels, 4 waves)"
+    assert name(6, 70, 75, 192, 330) == "activation-resident-int8 (256 pixels)"
     assert name(16, 32, 32, 384, 384) == "activation-resident-int8 (128 pixels)"
     assert name(16, 16, 16, 576, 576) == "activation-resident-int8 (64 pixels)"
     assert name(16, 8, 8, 960, 960) == "wave-split"
