@@ -1,10 +1,10 @@
 // 3x3 / stride 1 / pad 1 NHWC convolution with per-pixel activation scales on int8 MFMA, one
-// workgroup of eight waves per CU, the activation tile expanded to int8 ONCE and resident in LDS
-// (Method, "Convolution": one integer sum per tap, taps combined in fp32 with the scale of the
-// input pixel under the tap).
+// workgroup of eight waves per CU (or two of four waves), the activation tile expanded to int8
+// ONCE and resident in LDS (Method, "Convolution": one integer sum per tap, taps combined in fp32
+// with the scale of the input pixel under the tap).
 //
-// Why another kernel.  Three things held the other 3x3 kernels below a third of the int8 rate on
-// the UNet's layers: (1) tile counts that do not divide the machine (768 tiles for 512 resident
+// Why.  Three things hold the other 3x3 kernels below a third of the int8 rate on the UNet's
+// layers: (1) tile counts that do not divide the machine (768 tiles for 512 resident
 // workgroups, 576 for 256 CUs), (2) every wave expanding the packed nibbles of BOTH operands for
 // every use, nine times for an activation row, and (3) operand streams of 250..500 bytes per MFMA
 // through a copy path that delivers about 170.  Here
@@ -15,7 +15,8 @@
 //     split over 2, 4 or 8 waves, whose partial fp32 sums meet in LDS in a fixed order:
 //         phase A: channels 0..127   as 2 x PX/64 wave tiles, each split 4 / (PX/64) ways in K,
 //         phase B: channels 128..191 as 1 x PX/64 wave tiles, each split 8 / (PX/64) ways in K,
-//     so every wave multiplies 1.5 / 0.75 / 0.375 tiles' worth of units, all waves the same amount;
+//     so every wave multiplies 1.5 / 0.75 / 0.375 tiles' worth of units, all waves the same amount
+//     (four waves: 192 channels x 128 pixels, no split in phase A, two ways in phase B);
 //   - the activation rows of the tile's pixels plus W + 1 pixels either side are fetched once (all
 //     input channels), expanded to int8 (16 x code) on the way into LDS, and all nine taps of all
 //     phases read them at shifted addresses: an activation operand is an LDS read, nothing else;
@@ -25,7 +26,10 @@
 // The sums of one unit are folded into the fp32 result with one fma per element: the integer
 // accumulators start from the bit pattern of 1.5 * 2^23, so their bits read as a float are
 // 1.5 * 2^23 + S exactly (S = 256 * sum, |S| < 2^22 for 192 codes), and the fp32 sums start from
-// minus the known surplus.
+// minus the known surplus.  A wave requests the activation operands of a unit one step ahead (they
+// do not depend on the weight stream), its weight operands after the step's barrier, and refills
+// the freed weight stage while those are on their way.  fp16 results are transposed through a
+// per-wave LDS staging area so that neighbouring lanes store contiguous bytes.
 //
 // Integer output (HQ_I32): the same loads, stages, phases and MFMAs; instead of the fold every
 // wave adds the exact sums of its units to the zero-filled [pixel, tap, n] output with integer
